@@ -1,0 +1,176 @@
+/*
+ * slicemoe.h -- C ABI of the MI355X (gfx950) SliceMoE expert-FFN library.
+ *
+ * The calls follow the paper's statement of the problem (SliceMoE, arXiv 2512.12990):
+ *   quantize/slice   AMAT: group-wise asymmetric 8-bit codes whose upper 4 bits are the
+ *                    low-bit model (Section 4.2 and its equation, Table 1 note 1)
+ *   route            cache-aware top-k: resident experts get a score boost (Section 2.1)
+ *   expert_ffn(mask) per selected expert a SwiGLU FFN run from the MSB slice alone or from
+ *                    MSB+LSB, decided by slice residency (Section 4.1)
+ *   prefill_histogram  token-parallel high-bit prefill that also counts expert accesses, the
+ *                    statistic Predictive Cache Warmup ranks slices by (Section 4.3)
+ * plus host-only bookkeeping (slice LRU, top-N) that produces the mask and never touches the GPU.
+ *
+ * Conventions
+ *   - Every function returns 0 (SMOE_OK) or a negative smoe_status; nothing throws.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host memory.
+ *     All device pointers must be 16-byte aligned.  The caller owns every buffer it passes; a
+ *     bank only borrows its store and must be destroyed before that memory is freed.
+ *   - All device work is enqueued on the stream given to smoe_ctx_create and is asynchronous
+ *     unless a function says it synchronises.  One ctx per host thread.
+ *   - Matrices are row-major W[out, in]; quantisation groups are `group` consecutive elements
+ *     along `in` of one output row; a last shorter group is allowed.
+ *   - dtype codes: SMOE_F32 = 0, SMOE_BF16 = 1 (bf16 = upper 16 bits of an IEEE fp32).
+ *   - slice_mask[e]: bit0 = MSB slice of expert e resident, bit1 = LSB slice resident.
+ */
+#ifndef SLICEMOE_H
+#define SLICEMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SMOE_OK = 0,
+  SMOE_EINVAL = -1,   /* null or invalid argument */
+  SMOE_ESHAPE = -2,   /* inconsistent or unsupported dimensions */
+  SMOE_EALIGN = -3,   /* device pointer not 16-byte aligned */
+  SMOE_ESIZE = -4,    /* a caller buffer or the ctx workspace is too small */
+  SMOE_EHIP = -5,     /* a HIP call failed; see smoe_last_hip_error */
+  SMOE_ENOTIMPL = -6  /* valid request this build does not implement (e.g. 6/3-bit nests) */
+} smoe_status;
+
+enum { SMOE_F32 = 0, SMOE_BF16 = 1 };
+
+typedef struct smoe_ctx smoe_ctx;     /* host object: device id, stream, small device workspace */
+typedef struct smoe_bank smoe_bank;   /* host object describing one sliced expert store in HBM */
+typedef struct smoe_cache smoe_cache; /* host-only slice LRU */
+
+/* One set of equally shaped SwiGLU experts: gate, up are [d_ff, d_model], down is [d_model, d_ff].
+ * d_model, d_ff and group must be multiples of 32 (a K that is not a multiple of `group` gets a
+ * short last group).  b_high/b_low: only 8/4 is implemented. */
+typedef struct {
+  int32_t n_experts, d_model, d_ff, group;
+  int32_t b_high, b_low;
+  int32_t w_dtype;      /* dtype of the source weights handed to smoe_quantize_slice */
+  int32_t scale_dtype;  /* dtype the per-group scales are stored in (and rounded to) */
+} smoe_bank_desc;
+
+typedef struct {
+  uint64_t msb_hit, msb_miss, lsb_hit, lsb_miss;
+} smoe_cache_stats;
+
+/* ---- context ---------------------------------------------------------------------------- */
+/* Creates a context bound to `device` and to `hip_stream` (a hipStream_t, NULL = default
+ * stream).  Allocates a fixed 4 MiB device workspace (slot table, SwiGLU intermediates); this
+ * is the only device allocation the library ever makes.  smoe_ctx_destroy frees it. */
+int smoe_ctx_create(int device, void* hip_stream, smoe_ctx** out);
+int smoe_ctx_destroy(smoe_ctx* ctx);
+const char* smoe_strerror(int status);
+int smoe_last_hip_error(const smoe_ctx* ctx); /* hipError_t of the last failing HIP call, else 0 */
+
+/* ---- quantize / slice (Section 4.2; Table 1 note 1) ------------------------------------- */
+/* Bytes of device memory a bank's store needs. */
+int smoe_bank_bytes(const smoe_bank_desc* desc, size_t* store_bytes);
+/* Wraps caller-owned device memory `store_dev` (>= store_bytes, 256-byte aligned) as a bank.
+ * No device work. */
+int smoe_bank_create(smoe_ctx* ctx, const smoe_bank_desc* desc, void* store_dev, size_t store_bytes,
+                     smoe_bank** out);
+int smoe_bank_destroy(smoe_bank* bank);
+/* Quantises experts [e0, e0+n) from dense device weights w_gate[n, d_ff, d_model],
+ * w_up[n, d_ff, d_model], w_down[n, d_model, d_ff] (dtype desc.w_dtype, finite values) into the
+ * bank: per group lo = min(0, min w), hi = max(0, max w), s = round_to_scale_dtype((hi-lo)/255)
+ * (1 if that is not positive), zp = clamp(rint(-lo/s)), q = clamp(rint(w/s) + zp), all fp32
+ * round-to-nearest-even; then the code is split into its upper nibble (MSB slice, = the 4-bit
+ * model's code floor(q/16)) and lower nibble (LSB slice), stored in separate planes. */
+int smoe_quantize_slice(smoe_ctx* ctx, smoe_bank* bank, int e0, int n, const void* w_gate_dev,
+                        const void* w_up_dev, const void* w_down_dev);
+/* Copies one matrix of one expert back in canonical form (matrix: 0 gate, 1 up, 2 down; N x K its
+ * shape, ng = ceil(K/group)).  Host outputs, any may be NULL: q[N*K] 8-bit codes, msb[N*K] and
+ * lsb[N*K] nibble values 0..15, zp[N*ng], scale[N*ng] widened to fp32.  Synchronises. */
+int smoe_export_codes(smoe_ctx* ctx, const smoe_bank* bank, int expert, int matrix, uint8_t* q_host,
+                      uint8_t* msb_host, uint8_t* lsb_host, uint8_t* zp_host, float* scale_host);
+
+/* ---- route (Section 2.1) ------------------------------------------------------------------ */
+/* For each of T tokens: z = logits_dev[t] (fp32 [T,E]) or, if logits_dev is NULL,
+ * z_e = sum_i w_router_dev[e,i] * x_dev[t,i] (w_router fp32 [E,d_model], x of act_dtype, fp32
+ * accumulation); score = z + bias (bias_dev fp32 [E] or NULL = 0); idx_dev[t,0..k) = the k largest
+ * scores from the highest down, equal scores to the lower index; w_dev[t,j] = softmax(z)[idx]
+ * (unbiased logits), divided by their sum if norm_topk, times routed_scale.  logits_out_dev
+ * (fp32 [T,E], may be NULL) receives z.  E <= 256, k <= 16. */
+int smoe_route(smoe_ctx* ctx, int T, int E, int k, int d_model, const float* logits_dev,
+               const void* x_dev, int act_dtype, const float* w_router_dev, const float* bias_dev,
+               int norm_topk, float routed_scale, float* logits_out_dev, int32_t* idx_dev,
+               float* w_dev);
+
+/* ---- expert_ffn(mask) (Section 4.1) ------------------------------------------------------- */
+/* One token.  y = sum_j w[j] * FFN_{idx[j]}^{prec[j]}(x) + sum_{shared e} gamma * FFN_e^{HIGH}(x)
+ * (+ x if add_residual), FFN(x) = Wd (silu(Wg x) * (Wu x)).
+ * prec[j] = HIGH iff (slice_mask[idx[j]] & 3) == 3 and (tau_head <= 0 or w[j] >= tau_head):
+ * HIGH uses s*(16*msb + lsb - zp), LOW uses 16*s*(msb - floor(zp/16)) and never reads the LSB
+ * plane.  gamma = 1, or sigmoid(shared_gate_w . x) when shared_gate_w_dev (act_dtype [d_model]) is
+ * given.  `routed` may be NULL with k = 0 (dense FFN through `shared`); `shared` may be NULL.
+ * x_dev, y_dev: act_dtype [d_model]; idx_dev int32 [k]; w_dev fp32 [k]; slice_mask_dev uint8 [E];
+ * prec_out_dev uint8 [k] or NULL.  y_dev may not alias x_dev. */
+int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared,
+                    const void* x_dev, int act_dtype, int k, const int32_t* idx_dev,
+                    const float* w_dev, const uint8_t* slice_mask_dev, float tau_head,
+                    const void* shared_gate_w_dev, int add_residual, void* y_dev,
+                    uint8_t* prec_out_dev);
+
+/* route + expert_ffn for one token without a host round trip between them; same results as the
+ * two calls.  logits_dev fp32 [E] or NULL (then w_router_dev is used); idx_out_dev / w_out_dev /
+ * prec_out_dev ([k], may be NULL) receive the routing decision for the host's cache bookkeeping. */
+int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared,
+                      const void* x_dev, int act_dtype, int k, const float* logits_dev,
+                      const float* w_router_dev, const float* bias_dev, int norm_topk,
+                      float routed_scale, const uint8_t* slice_mask_dev, float tau_head,
+                      const void* shared_gate_w_dev, int add_residual, void* y_dev,
+                      int32_t* idx_out_dev, float* w_out_dev, uint8_t* prec_out_dev);
+
+/* ---- prefill_histogram (Section 4.3) ------------------------------------------------------ */
+/* Bytes of device scratch smoe_prefill_histogram needs for T tokens. */
+int smoe_prefill_bytes(int T, int E, int k, int d_model, int d_ff, int shared_d_ff, size_t* scratch_bytes);
+/* T tokens through one layer, every expert HIGH: routes each token (as smoe_route), counts
+ * hist_dev[e] = number of (token, slot) pairs sent to expert e (uint32 [E], overwritten), runs the
+ * experts as a grouped GEMM over the tokens of each expert, and writes
+ * y_dev[t] = sum_j w[t,j] * FFN_{idx[t,j]}(x[t]) (+ shared experts, + x[t] if add_residual).
+ * x_dev, y_dev: act_dtype [T, d_model] (bf16 only); idx_dev int32 [T,k]; w_dev fp32 [T,k]. */
+int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, int T,
+                           const void* x_dev, int act_dtype, int k, const float* logits_dev,
+                           const float* w_router_dev, int norm_topk, float routed_scale,
+                           const void* shared_gate_w_dev, int add_residual, void* scratch_dev,
+                           size_t scratch_bytes, void* y_dev, int32_t* idx_dev, float* w_dev,
+                           uint32_t* hist_dev);
+
+/* Host only.  Retention order after prefill, hottest first: slice id = ((layer*E + expert) << 1)
+ * | is_lsb; every MSB slice before any LSB slice, within a plane by descending count, equal counts
+ * by ascending layer then expert.  Writes min(N, 2*L*E) ids, returns that number in *n_out. */
+int smoe_topn_slices(const uint32_t* hist_host, int L, int E, int N, uint32_t* slice_ids_host,
+                     int* n_out);
+
+/* ---- host bookkeeping that produces the mask (Sections 4.1, 5.1-3); no device work -------- */
+/* One LRU over the slices of all layers; capacity in slices (>= 2). */
+int smoe_cache_create(int L, int E, int capacity_slices, smoe_cache** out);
+int smoe_cache_destroy(smoe_cache* c);
+/* Replaces the contents by slice_ids[0..n) (most recently used first), truncated to capacity. */
+int smoe_cache_init_order(smoe_cache* c, const uint32_t* slice_ids, int n);
+/* slice_mask[e] and bias[e] = beta if the MSB slice of (layer, e) is resident else 0. */
+int smoe_cache_snapshot(const smoe_cache* c, int layer, float beta, uint8_t* slice_mask_host,
+                        float* bias_host);
+/* Applies one token's accesses in slot order.  MSB: hit -> most recent; miss -> fetched, most
+ * recent.  LSB (only if want_high[j]): hit -> position unchanged; miss -> fetched, placed as the
+ * next eviction victim.  A fetch into a full cache first evicts the least recent slice. */
+int smoe_cache_access(smoe_cache* c, int layer, int k, const int32_t* idx_host,
+                      const uint8_t* want_high_host);
+int smoe_cache_stats_get(const smoe_cache* c, smoe_cache_stats* out);
+/* Copies the resident slice ids, most recent first; returns their number in *n_out. */
+int smoe_cache_order(const smoe_cache* c, uint32_t* slice_ids_host, int max_n, int* n_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLICEMOE_H */

@@ -1,0 +1,172 @@
+// Context, bank construction and export: the host side of the C ABI.
+#include "common.hpp"
+#include <new>
+#include <vector>
+#include <string.h>
+
+extern "C" const char* smoe_strerror(int status) {
+  switch (status) {
+    case SMOE_OK: return "ok";
+    case SMOE_EINVAL: return "null or invalid argument";
+    case SMOE_ESHAPE: return "inconsistent or unsupported dimensions";
+    case SMOE_EALIGN: return "device pointer not 16-byte aligned";
+    case SMOE_ESIZE: return "buffer or workspace too small";
+    case SMOE_EHIP: return "a HIP call failed (see smoe_last_hip_error)";
+    case SMOE_ENOTIMPL: return "not implemented in this build";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int smoe_ctx_create(int device, void* hip_stream, smoe_ctx** out) {
+  if (!out || device < 0) return SMOE_EINVAL;
+  *out = nullptr;
+  smoe_ctx* c = new (std::nothrow) smoe_ctx();
+  if (!c) return SMOE_EINVAL;
+  c->device = device; c->stream = (hipStream_t)hip_stream; c->ws = nullptr; c->last_hip = 0; c->n_cu = 256;
+  hipError_t e = hipSetDevice(device);
+  if (e == hipSuccess) e = hipMalloc((void**)&c->ws, SMOE_WORKSPACE_BYTES);
+  if (e == hipSuccess) {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
+      c->n_cu = prop.multiProcessorCount;
+  }
+  if (e != hipSuccess) { (void)hipGetLastError(); delete c; return SMOE_EHIP; }
+  *out = c;
+  return SMOE_OK;
+}
+
+extern "C" int smoe_ctx_destroy(smoe_ctx* ctx) {
+  if (!ctx) return SMOE_EINVAL;
+  if (ctx->ws) { (void)hipSetDevice(ctx->device); (void)hipFree(ctx->ws); }
+  delete ctx;
+  return SMOE_OK;
+}
+
+extern "C" int smoe_last_hip_error(const smoe_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+// ---- bank layout ------------------------------------------------------------------------------
+static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+static inline size_t up16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+static int check_desc(const smoe_bank_desc* d) {
+  if (!d) return SMOE_EINVAL;
+  if (d->n_experts <= 0 || d->d_model <= 0 || d->d_ff <= 0 || d->group <= 0) return SMOE_ESHAPE;
+  if (d->d_model % 32 || d->d_ff % 32 || d->group % 32) return SMOE_ESHAPE;
+  if ((d->w_dtype != SMOE_F32 && d->w_dtype != SMOE_BF16) || (d->scale_dtype != SMOE_F32 && d->scale_dtype != SMOE_BF16))
+    return SMOE_EINVAL;
+  if (d->b_high <= d->b_low || d->b_low < 1 || d->b_high > 8) return SMOE_ESHAPE;
+  if (d->b_high != 8 || d->b_low != 4) return SMOE_ENOTIMPL;
+  return SMOE_OK;
+}
+
+struct MatOff { size_t msb, lsb, zp, sc; };
+
+static size_t layout(const smoe_bank_desc* d, BankDev* b, MatOff* ogu, MatOff* odn) {
+  const size_t E = (size_t)d->n_experts, ssz = d->scale_dtype == SMOE_BF16 ? 2 : 4;
+  MatDev* m[2] = {&b->gu, &b->dn};
+  MatOff* o[2] = {ogu, odn};
+  m[0]->N = 2 * d->d_ff; m[0]->K = d->d_model;
+  m[1]->N = d->d_model;  m[1]->K = d->d_ff;
+  size_t off = 0;
+  for (int i = 0; i < 2; i++) {
+    m[i]->ng = (m[i]->K + d->group - 1) / d->group;
+    m[i]->cpg = d->group / 32;
+    m[i]->plane_stride = (size_t)m[i]->N * m[i]->K / 2;
+    m[i]->zp_stride = up16((size_t)m[i]->N * m[i]->ng);
+    m[i]->sc_stride = up16((size_t)m[i]->N * m[i]->ng * ssz);
+  }
+  // MSB planes of both families first, then LSB planes, then metadata: a low-bit read never
+  // touches the LSB region.
+  for (int i = 0; i < 2; i++) { o[i]->msb = off; off = up256(off + E * m[i]->plane_stride); }
+  for (int i = 0; i < 2; i++) { o[i]->zp = off; off = up256(off + E * m[i]->zp_stride); }
+  for (int i = 0; i < 2; i++) { o[i]->sc = off; off = up256(off + E * m[i]->sc_stride); }
+  for (int i = 0; i < 2; i++) { o[i]->lsb = off; off = up256(off + E * m[i]->plane_stride); }
+  b->n_experts = d->n_experts; b->d_model = d->d_model; b->d_ff = d->d_ff; b->group = d->group;
+  b->sc_bf16 = d->scale_dtype == SMOE_BF16;
+  return off;
+}
+
+extern "C" int smoe_bank_bytes(const smoe_bank_desc* desc, size_t* store_bytes) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!store_bytes) return SMOE_EINVAL;
+  BankDev b; MatOff a, c;
+  *store_bytes = layout(desc, &b, &a, &c);
+  return SMOE_OK;
+}
+
+extern "C" int smoe_bank_create(smoe_ctx* ctx, const smoe_bank_desc* desc, void* store_dev, size_t store_bytes,
+                                smoe_bank** out) {
+  if (!ctx || !out || !store_dev) return SMOE_EINVAL;
+  *out = nullptr;
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (((uintptr_t)store_dev) & 255u) return SMOE_EALIGN;
+  smoe_bank* b = new (std::nothrow) smoe_bank();
+  if (!b) return SMOE_EINVAL;
+  MatOff ogu, odn;
+  size_t need = layout(desc, &b->dev, &ogu, &odn);
+  if (store_bytes < need) { delete b; return SMOE_ESIZE; }
+  uint8_t* s = (uint8_t*)store_dev;
+  b->dev.gu.msb = s + ogu.msb; b->dev.gu.lsb = s + ogu.lsb; b->dev.gu.zp = s + ogu.zp; b->dev.gu.sc = s + ogu.sc;
+  b->dev.dn.msb = s + odn.msb; b->dev.dn.lsb = s + odn.lsb; b->dev.dn.zp = s + odn.zp; b->dev.dn.sc = s + odn.sc;
+  b->desc = *desc; b->store = s; b->store_bytes = store_bytes; b->device = ctx->device;
+  *out = b;
+  return SMOE_OK;
+}
+
+extern "C" int smoe_bank_destroy(smoe_bank* bank) {
+  if (!bank) return SMOE_EINVAL;
+  delete bank;
+  return SMOE_OK;
+}
+
+extern "C" int smoe_quantize_slice(smoe_ctx* ctx, smoe_bank* bank, int e0, int n, const void* w_gate_dev,
+                                   const void* w_up_dev, const void* w_down_dev) {
+  if (!ctx || !bank || !w_gate_dev || !w_up_dev || !w_down_dev) return SMOE_EINVAL;
+  if (e0 < 0 || n <= 0 || e0 + n > bank->desc.n_experts) return SMOE_ESHAPE;
+  if (!aligned16(w_gate_dev) || !aligned16(w_up_dev) || !aligned16(w_down_dev)) return SMOE_EALIGN;
+  return smoe_launch_quantize(ctx, bank, e0, n, w_gate_dev, w_up_dev, w_down_dev);
+}
+
+// ---- export ---------------------------------------------------------------------------------
+extern "C" int smoe_export_codes(smoe_ctx* ctx, const smoe_bank* bank, int expert, int matrix, uint8_t* q_host,
+                                 uint8_t* msb_host, uint8_t* lsb_host, uint8_t* zp_host, float* scale_host) {
+  if (!ctx || !bank) return SMOE_EINVAL;
+  if (expert < 0 || expert >= bank->desc.n_experts || matrix < 0 || matrix > 2) return SMOE_ESHAPE;
+  const MatDev& m = matrix == 2 ? bank->dev.dn : bank->dev.gu;
+  const int N = matrix == 2 ? m.N : m.N / 2, K = m.K, ng = m.ng;
+  const size_t row_b = (size_t)K / 2, ssz = bank->dev.sc_bf16 ? 2 : 4;
+  HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+  std::vector<uint8_t> pm(m.plane_stride), pl(m.plane_stride), zp((size_t)m.N * ng), sc((size_t)m.N * ng * ssz);
+  HIPCHK(ctx, hipMemcpy(pm.data(), m.msb + (size_t)expert * m.plane_stride, pm.size(), hipMemcpyDeviceToHost));
+  HIPCHK(ctx, hipMemcpy(pl.data(), m.lsb + (size_t)expert * m.plane_stride, pl.size(), hipMemcpyDeviceToHost));
+  HIPCHK(ctx, hipMemcpy(zp.data(), m.zp + (size_t)expert * m.zp_stride, zp.size(), hipMemcpyDeviceToHost));
+  HIPCHK(ctx, hipMemcpy(sc.data(), m.sc + (size_t)expert * m.sc_stride, sc.size(), hipMemcpyDeviceToHost));
+  for (int r = 0; r < N; r++) {
+    // gate rows are the even rows of the interleaved family, up rows the odd ones
+    const size_t sr = matrix == 2 ? (size_t)r : (size_t)2 * r + (matrix == 1);
+    for (int kk = 0; kk < K; kk++) {
+      const uint8_t bm = pm[sr * row_b + kk / 2], bl = pl[sr * row_b + kk / 2];
+      const uint8_t mv = (kk & 1) ? (bm >> 4) : (bm & 15), lv = (kk & 1) ? (bl >> 4) : (bl & 15);
+      const size_t o = (size_t)r * K + kk;
+      if (msb_host) msb_host[o] = mv;
+      if (lsb_host) lsb_host[o] = lv;
+      if (q_host) q_host[o] = (uint8_t)((mv << 4) | lv);
+    }
+    for (int g = 0; g < ng; g++) {
+      if (zp_host) zp_host[(size_t)r * ng + g] = zp[sr * ng + g];
+      if (scale_host) {
+        float f;
+        if (bank->dev.sc_bf16) {
+          uint32_t u = (uint32_t)((const uint16_t*)sc.data())[sr * ng + g] << 16;
+          memcpy(&f, &u, 4);
+        } else {
+          f = ((const float*)sc.data())[sr * ng + g];
+        }
+        scale_host[(size_t)r * ng + g] = f;
+      }
+    }
+  }
+  return SMOE_OK;
+}

@@ -1,0 +1,117 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/slicemoe.h"
+
+#define SMOE_MAX_SLOTS 24      // top-k (<= 16) routed + up to 8 shared experts
+#define SMOE_MAX_EXPERTS 256
+#define SMOE_MAX_TOPK 16
+#define SMOE_WORKSPACE_BYTES (4u << 20)
+
+// ---- host objects -------------------------------------------------------------------------
+// Device view of one quantised matrix family inside a bank ("gu": gate and up rows interleaved,
+// row 2r = gate r, row 2r+1 = up r, shape [2*d_ff, d_model]; "dn": down, [d_model, d_ff]).
+// Per expert e the data starts at base + e * stride.  Planes hold two 4-bit values per byte,
+// row-major, low nibble = even column.  Metadata: zp uint8 [N, ng], scale [N, ng].
+struct MatDev {
+  const uint8_t* msb; const uint8_t* lsb; const uint8_t* zp; const uint8_t* sc;
+  unsigned long long plane_stride, zp_stride, sc_stride;   // bytes per expert
+  int N, K, ng, cpg;                                       // cpg = 32-column chunks per group
+};
+
+struct BankDev {
+  MatDev gu, dn;
+  int n_experts, d_model, d_ff, group, sc_bf16;
+};
+
+struct smoe_ctx {
+  int device;
+  hipStream_t stream;
+  uint8_t* ws;          // SMOE_WORKSPACE_BYTES of device memory
+  int last_hip;
+  int n_cu;
+};
+
+struct smoe_bank {
+  smoe_bank_desc desc;
+  BankDev dev;          // device pointers are non-const views of `store`
+  uint8_t* store;
+  size_t store_bytes;
+  int device;
+};
+
+// ---- per-token slot table (device) ----------------------------------------------------------
+struct Slot {
+  const uint8_t *gu_msb, *gu_lsb, *gu_zp, *gu_sc;
+  const uint8_t *dn_msb, *dn_lsb, *dn_zp, *dn_sc;
+  int f;          // d_ff of this expert
+  int h_off;      // offset of its SwiGLU vector in the h buffer (floats) == first flat row pair
+  int prec;       // 1 = HIGH (MSB+LSB), 0 = LOW (MSB only)
+  float weight;   // gate weight w_j, or gamma for a shared expert
+  int gu_ng, gu_cpg, dn_ng, dn_cpg, sc_bf16, pad;
+};
+
+struct SlotTable {
+  int n_slots, total_f, pad0, pad1;
+  Slot s[SMOE_MAX_SLOTS];
+};
+
+// workspace layout (offsets in bytes)
+#define WS_TABLE_OFF 0                       // SlotTable
+#define WS_IDX_OFF (16 << 10)                // int32 [16], float [16], uint8 [16] routing scratch
+#define WS_H_OFF (64 << 10)                  // float h[total_f]   (<= 1M - 16K floats)
+
+#define HIPCHK(ctx, expr)                                  \
+  do {                                                     \
+    hipError_t _e = (expr);                                \
+    if (_e != hipSuccess) { (ctx)->last_hip = (int)_e; return SMOE_EHIP; } \
+  } while (0)
+
+static inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+// ---- device helpers ---------------------------------------------------------------------------
+#ifdef __HIPCC__
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// round-to-nearest-even fp32 -> bf16 bits (finite inputs)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <int ACT> __device__ __forceinline__ float load_act(const void* p, size_t i) {
+  if (ACT == SMOE_F32) return ((const float*)p)[i];
+  return bf16_bits_to_f32(((const uint16_t*)p)[i]);
+}
+template <int ACT> __device__ __forceinline__ void store_act(void* p, size_t i, float v) {
+  if (ACT == SMOE_F32) ((float*)p)[i] = v;
+  else ((uint16_t*)p)[i] = (uint16_t)f32_to_bf16_bits(v);
+}
+
+__device__ __forceinline__ float load_scale(const uint8_t* sc, int sc_bf16, size_t i) {
+  return sc_bf16 ? bf16_bits_to_f32(((const uint16_t*)sc)[i]) : ((const float*)sc)[i];
+}
+
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over the 64 lanes of a wavefront; every lane of the wave must call it.  The total is
+// returned in all lanes (DPP within rows of 16, then the four row totals are read out).
+__device__ __forceinline__ float wave_sum(float v) {
+  v += dpp_f32<0xB1>(v);     // quad_perm [1,0,3,2]
+  v += dpp_f32<0x4E>(v);     // quad_perm [2,3,0,1]
+  v += dpp_f32<0x124>(v);    // row_ror 4
+  v += dpp_f32<0x128>(v);    // row_ror 8
+  float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  return (r0 + r1) + (r2 + r3);
+}
+#endif
+
+// launchers implemented in the .hip files
+int smoe_launch_quantize(smoe_ctx* ctx, smoe_bank* bank, int e0, int n, const void* wg, const void* wu, const void* wd);

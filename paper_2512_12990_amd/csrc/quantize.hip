@@ -1,0 +1,92 @@
+// AMAT quantise + slice (paper Section 4.2 and its equation; Table 1 note 1).
+//
+// One work-group per destination row, one wavefront per quantisation group.  All arithmetic
+// that decides an integer (scale, zero-point, code) is plain IEEE fp32 with round-to-nearest-
+// even, no fused multiply-add and true division, so codes are reproducible bit for bit.
+#include "common.hpp"
+
+#pragma clang fp contract(off)
+
+template <int WDT> __device__ __forceinline__ float load_w(const void* p, size_t i) {
+  if (WDT == SMOE_F32) return ((const float*)p)[i];
+  return bf16_bits_to_f32(((const uint16_t*)p)[i]);
+}
+
+__device__ __forceinline__ float wave_min(float v) {
+  for (int m = 32; m >= 1; m >>= 1) v = fminf(v, __shfl_xor(v, m));
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+  for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m));
+  return v;
+}
+
+// w0/w1: source matrices of the n experts being converted ([n, N/2, K] each when `interleave`,
+// else w0 is [n, N, K]).  Destination family `m` already points at expert 0 of the bank.
+template <int WDT>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restrict__ w0, const void* __restrict__ w1,
+                                                            MatDev m, int e0, int group, int sc_bf16, int interleave) {
+  const int row = blockIdx.x, el = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int K = m.K, ng = m.ng;
+  const void* src;
+  size_t src_row;
+  if (interleave) {
+    src = (row & 1) ? w1 : w0;
+    src_row = (size_t)el * (m.N / 2) + (row >> 1);
+  } else {
+    src = w0;
+    src_row = (size_t)el * m.N + row;
+  }
+  const size_t sbase = src_row * (size_t)K;
+  const size_t e = (size_t)(e0 + el);
+  uint8_t* pm = const_cast<uint8_t*>(m.msb) + e * m.plane_stride + (size_t)row * (K / 2);
+  uint8_t* pl = const_cast<uint8_t*>(m.lsb) + e * m.plane_stride + (size_t)row * (K / 2);
+  uint8_t* pz = const_cast<uint8_t*>(m.zp) + e * m.zp_stride + (size_t)row * ng;
+  uint8_t* ps = const_cast<uint8_t*>(m.sc) + e * m.sc_stride;
+
+  for (int g = wave; g < ng; g += 4) {
+    const int k0 = g * group;
+    const int gsz = min(group, K - k0);
+    const int np = gsz >> 1;
+    float lo = 0.0f, hi = 0.0f;                       // the range always contains 0
+    for (int p = lane; p < np; p += 64) {
+      const float a = load_w<WDT>(src, sbase + k0 + 2 * p), b = load_w<WDT>(src, sbase + k0 + 2 * p + 1);
+      lo = fminf(lo, fminf(a, b));
+      hi = fmaxf(hi, fmaxf(a, b));
+    }
+    lo = wave_min(lo);
+    hi = wave_max(hi);
+    float s = (hi - lo) / 255.0f;
+    if (sc_bf16) s = bf16_bits_to_f32(f32_to_bf16_bits(s));
+    if (!(s > 0.0f)) s = 1.0f;
+    const int zp = (int)fminf(fmaxf(rintf((-lo) / s), 0.0f), 255.0f);
+    for (int p = lane; p < np; p += 64) {
+      const float a = load_w<WDT>(src, sbase + k0 + 2 * p), b = load_w<WDT>(src, sbase + k0 + 2 * p + 1);
+      const int qa = min(max((int)rintf(a / s) + zp, 0), 255);
+      const int qb = min(max((int)rintf(b / s) + zp, 0), 255);
+      pm[(k0 >> 1) + p] = (uint8_t)((qa >> 4) | (qb & 0xF0));          // floor(q/16): the low-bit code
+      pl[(k0 >> 1) + p] = (uint8_t)((qa & 15) | ((qb & 15) << 4));     // the bits truncation drops
+    }
+    if (lane == 0) {
+      pz[g] = (uint8_t)zp;
+      const size_t si = (size_t)row * ng + g;
+      if (sc_bf16) ((uint16_t*)ps)[si] = (uint16_t)f32_to_bf16_bits(s);
+      else ((float*)ps)[si] = s;
+    }
+  }
+}
+
+int smoe_launch_quantize(smoe_ctx* ctx, smoe_bank* bank, int e0, int n, const void* wg, const void* wu, const void* wd) {
+  const BankDev& b = bank->dev;
+  HIPCHK(ctx, hipSetDevice(ctx->device));
+  dim3 blk(256);
+  if (bank->desc.w_dtype == SMOE_F32) {
+    quantize_rows_kernel<SMOE_F32><<<dim3(b.gu.N, n), blk, 0, ctx->stream>>>(wg, wu, b.gu, e0, b.group, b.sc_bf16, 1);
+    quantize_rows_kernel<SMOE_F32><<<dim3(b.dn.N, n), blk, 0, ctx->stream>>>(wd, nullptr, b.dn, e0, b.group, b.sc_bf16, 0);
+  } else {
+    quantize_rows_kernel<SMOE_BF16><<<dim3(b.gu.N, n), blk, 0, ctx->stream>>>(wg, wu, b.gu, e0, b.group, b.sc_bf16, 1);
+    quantize_rows_kernel<SMOE_BF16><<<dim3(b.dn.N, n), blk, 0, ctx->stream>>>(wd, nullptr, b.dn, e0, b.group, b.sc_bf16, 0);
+  }
+  HIPCHK(ctx, hipGetLastError());
+  return SMOE_OK;
+}

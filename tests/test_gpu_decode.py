@@ -1,0 +1,272 @@
+"""GPU parity: HIP path (through the C ABI) against the CPU oracle, same seeded inputs.
+
+Integer results (codes, planes, zero-points, scale bits, top-k indices, precision flags) must be
+bit-exact; FFN outputs within max-abs-rel 1e-4 (fp32 activations) / 2e-2 (bf16)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import slicemoe_oracle as O
+from paper_2512_12990_amd import binding as B
+from paper_2512_12990_amd import synth
+from helpers import LayerPair, t2np
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    c = B.Ctx(0)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def dev(a, dtype=None):
+    t = torch.as_tensor(a)
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to("cuda:0").contiguous()
+
+
+# ------------------------------------------------------------------------------ quantise / slice
+@pytest.mark.parametrize("d,f,G,dt", [(256, 128, 64, "f32"), (256, 160, 64, "bf16"), (2048, 1408, 128, "bf16"),
+                                      (96, 64, 32, "f32")])
+def test_quantize_slice_bit_exact(ctx, d, f, G, dt):
+    say("quantize", d, f, G, dt)
+    shape = synth.LayerShape(d, 2, f, 1, G, act=dt)
+    pair = LayerPair(ctx, shape, seed=3)
+    for e in range(2):
+        ex = pair.oracle_expert(e)
+        for mi, qm in enumerate((ex.gate, ex.up, ex.down)):
+            got = B.smoe_export_codes(ctx, pair.routed, e, mi)
+            assert np.array_equal(got["q"], qm.q)
+            assert np.array_equal(got["msb"], qm.msb()) and np.array_equal(got["lsb"], qm.lsb())
+            assert np.array_equal(got["zp"], qm.zp)
+            assert np.array_equal(got["scale"].view(np.uint32), qm.scale.view(np.uint32))
+
+
+def test_quantize_special_groups_bit_exact(ctx):
+    # flat groups, one-sided groups, exact zeros, a huge and a tiny group next to each other
+    say("quantize special")
+    d, f, G = 128, 64, 32
+    rng = np.random.default_rng(0)
+    wg = (rng.standard_normal((1, f, d)) * 0.02).astype(np.float32)
+    wg[0, 0, :32] = 0.0
+    wg[0, 1, :32] = np.abs(wg[0, 1, :32]) + 0.1
+    wg[0, 2, :32] = -np.abs(wg[0, 2, :32]) - 0.1
+    wg[0, 3, 32:64] *= 1e4
+    wg[0, 3, 64:96] *= 1e-6
+    wg[0, 4, ::5] = 0.0
+    wu = (rng.standard_normal((1, f, d)) * 0.02).astype(np.float32)
+    wd = (rng.standard_normal((1, d, f)) * 0.02).astype(np.float32)
+    for dt in ("f32", "bf16"):
+        bank = B.Bank(ctx, 1, d, f, G, "f32", dt)
+        B.smoe_quantize_slice(ctx, bank, 0, dev(wg), dev(wu), dev(wd))
+        for mi, w in enumerate((wg, wu, wd)):
+            ref = O.quantize(w[0], G, scale_dtype=dt)
+            got = B.smoe_export_codes(ctx, bank, 0, mi)
+            assert np.array_equal(got["q"], ref.q) and np.array_equal(got["zp"], ref.zp)
+            assert np.array_equal(got["scale"].view(np.uint32), ref.scale.view(np.uint32))
+
+
+# ------------------------------------------------------------------------------ route
+@pytest.mark.parametrize("E,k,T", [(8, 2, 16), (64, 6, 200), (60, 4, 64), (256, 16, 8), (5, 5, 3)])
+def test_route_given_logits(ctx, E, k, T):
+    say("route logits", E, k, T)
+    z = synth.normal_logits(7, T, E)
+    z[0, : min(E, 4)] = 0.25                      # ties
+    z[1 % T, :] = -0.0
+    bias = torch.zeros(E)
+    bias[torch.randperm(E, generator=torch.Generator().manual_seed(1))[: E // 2]] = 1.0
+    for b, norm, rs in [(None, False, 1.0), (bias, False, 1.0), (bias, True, 2.5)]:
+        idx, w = B.smoe_route(ctx, k, logits=dev(z), bias=None if b is None else dev(b), norm_topk=norm, routed_scale=rs)
+        ridx, rw = O.route(z.numpy(), None if b is None else b.numpy(), k, norm, rs)
+        assert np.array_equal(idx.cpu().numpy(), ridx)
+        np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=2e-5, atol=1e-7)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_route_from_activations(ctx, dt):
+    say("route from x", dt)
+    T, E, d, k = 33, 60, 2048, 4
+    x = synth.activations(5, T, d, dt)
+    wr = synth.router_weight(5, 0, E, d)
+    idx, w, z = B.smoe_route(ctx, k, x=dev(x), w_router=dev(wr), want_logits=True)
+    zg = z.cpu().numpy()
+    zr = O.router_logits(t2np(x), wr.numpy())
+    np.testing.assert_allclose(zg, zr, rtol=0, atol=2e-5 * np.abs(zr).max())
+    # indices are a function of an fp32 logits array: the oracle's top-k runs on the GPU's logits
+    ridx, rw = O.route(zg, None, k)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=2e-5, atol=1e-7)
+
+
+# ------------------------------------------------------------------------------ expert FFN
+def _run_layer_steps(ctx, wl: synth.Workload, pair: LayerPair, steps, masks, bias, logits, x_all, use_fused, wr=None,
+                     wsg=None, add_residual=False, tau=0.0):
+    shp = wl.layer
+    tol = TOL[shp.act]
+    worst = 0.0
+    for t in steps:
+        x = x_all[t]
+        mask = masks[t] if masks.ndim == 2 else masks
+        xd = dev(x)
+        md = dev(mask)
+        if use_fused:
+            idx_o = torch.empty(shp.top_k, dtype=torch.int32, device="cuda:0")
+            w_o = torch.empty(shp.top_k, dtype=torch.float32, device="cuda:0")
+            p_o = torch.empty(shp.top_k, dtype=torch.uint8, device="cuda:0")
+            y = B.smoe_decode_layer(ctx, pair.routed, pair.shared, xd, shp.top_k,
+                                    logits=None if logits is None else dev(logits[t]),
+                                    w_router=None if wr is None else dev(wr), bias=None if bias is None else dev(bias),
+                                    slice_mask=md, tau_head=tau, shared_gate_w=None if wsg is None else dev(wsg),
+                                    add_residual=add_residual, idx_out=idx_o, w_out=w_o, prec_out=p_o)
+            idx, w, prec = idx_o.cpu().numpy(), w_o.cpu().numpy(), p_o.cpu().numpy()
+            if logits is not None:
+                ridx, rw = O.route(logits[t].numpy()[None], None if bias is None else bias.numpy(), shp.top_k)
+            else:
+                _, _, zg = B.smoe_route(ctx, shp.top_k, x=xd[None], w_router=dev(wr), want_logits=True)
+                ridx, rw = O.route(zg.cpu().numpy(), None if bias is None else bias.numpy(), shp.top_k)
+            assert np.array_equal(idx, ridx[0]), (t, idx, ridx)
+            np.testing.assert_allclose(w, rw[0], rtol=2e-5, atol=1e-7)
+        else:
+            z = logits[t].numpy()[None] if logits is not None else O.router_logits(t2np(x), wr.numpy())
+            ridx, rw = O.route(z, None if bias is None else bias.numpy(), shp.top_k)
+            p_o = torch.empty(shp.top_k, dtype=torch.uint8, device="cuda:0")
+            y = B.smoe_expert_ffn(ctx, pair.routed, pair.shared, xd, dev(ridx[0]), dev(rw[0].astype(np.float32)), md,
+                                  tau_head=tau, shared_gate_w=None if wsg is None else dev(wsg),
+                                  add_residual=add_residual, prec_out=p_o)
+            prec = p_o.cpu().numpy()
+        # the oracle uses the gate weights the GPU path was given / produced in fp32
+        w_used = rw[0].astype(np.float32).astype(np.float64)
+        rprec = O.precision_select(ridx[0], w_used, mask, tau)
+        assert np.array_equal(prec, rprec), (t, prec, rprec)
+        yref = O.moe_layer(t2np(x).astype(np.float64), pair.oracle_routed(), ridx[0], w_used, rprec,
+                           pair.oracle_shared(), None if wsg is None else t2np(wsg), add_residual)
+        err = O.max_abs_rel(t2np(y), yref)
+        worst = max(worst, err)
+        assert err <= tol, (t, err)
+    return worst
+
+
+@pytest.mark.parametrize("use_fused", [False, True])
+def test_tiny_fp32_layer_all_steps(ctx, use_fused):
+    wl = synth.TINY
+    say("tiny fp32 layer, fused =", use_fused)
+    shp = wl.layer
+    pair = LayerPair(ctx, shp, seed=wl.seed)
+    x_all = synth.activations(wl.seed, wl.steps, shp.d_model, shp.act)
+    masks = synth.bernoulli_masks(wl.seed, wl.steps, shp.n_experts)
+    wr = synth.router_weight(wl.seed, 0, shp.n_experts, shp.d_model)
+    worst = _run_layer_steps(ctx, wl, pair, range(wl.steps), masks, None, None, x_all, use_fused, wr=wr)
+    say("  worst max-abs-rel", worst)
+
+
+def test_medium_bf16_layer_ragged(ctx):
+    # several row tiles, a ragged chunk count (d_ff = 352 -> 11 chunks, 3 groups of 128 with a
+    # 96-wide tail), shared expert wider than routed ones with a sigmoid gate, residual, threshold
+    say("medium bf16 ragged layer")
+    shp = synth.LayerShape(512, 12, 352, 3, 128, n_shared=1, shared_d_ff=2144, shared_gate=True, act="bf16")
+    wl = synth.Workload("medium", shp, steps=6, seed=11)
+    pair = LayerPair(ctx, shp, seed=wl.seed)
+    x_all = synth.activations(wl.seed, wl.steps, shp.d_model, shp.act)
+    masks = synth.bernoulli_masks(wl.seed, wl.steps, shp.n_experts)
+    masks[2, :] = 0          # everything missing: all LOW
+    masks[3, :] = 3          # everything resident: all HIGH
+    wr = synth.router_weight(wl.seed, 0, shp.n_experts, shp.d_model, std=0.05)
+    wsg = synth.shared_gate_weight(wl.seed, 0, shp.d_model, shp.act)
+    for fused in (False, True):
+        worst = _run_layer_steps(ctx, wl, pair, range(wl.steps), masks, None, None, x_all, fused, wr=wr, wsg=wsg,
+                                 add_residual=True, tau=0.0 if fused else 0.34)
+        say("  fused", fused, "worst max-abs-rel", worst)
+
+
+def test_dense_ffn_through_shared_bank(ctx):
+    # no routed bank at all: a dense SwiGLU run HIGH; K of the down projection is not a multiple
+    # of the group (416 = 3*128 + 32)
+    say("dense FFN via shared bank")
+    shp = synth.LayerShape(256, 0, 0, 0, 128, n_shared=1, shared_d_ff=416, act="bf16")
+    pair = LayerPair(ctx, shp, seed=5, routed=False)
+    x = synth.activations(5, 2, 256, "bf16")
+    for t in range(2):
+        y = B.smoe_expert_ffn(ctx, None, pair.shared, dev(x[t]), None, None, None)
+        yref = O.moe_layer(t2np(x[t]).astype(np.float64), [], [], [], [], pair.oracle_shared())
+        assert O.max_abs_rel(t2np(y), yref) <= TOL["bf16"]
+
+
+def test_determinism_and_high_low_differ(ctx):
+    say("determinism")
+    shp = synth.LayerShape(256, 4, 128, 2, 64, act="f32")
+    pair = LayerPair(ctx, shp, seed=2)
+    x = dev(synth.activations(2, 1, 256, "f32")[0])
+    idx = dev(np.array([1, 3], np.int32))
+    w = dev(np.array([0.6, 0.4], np.float32))
+    hi = dev(np.full(4, 3, np.uint8))
+    lo = dev(np.full(4, 1, np.uint8))
+    y1 = B.smoe_expert_ffn(ctx, pair.routed, None, x, idx, w, hi).clone()
+    y2 = B.smoe_expert_ffn(ctx, pair.routed, None, x, idx, w, hi).clone()
+    y3 = B.smoe_expert_ffn(ctx, pair.routed, None, x, idx, w, lo).clone()
+    assert torch.equal(y1, y2)
+    assert O.max_abs_rel(t2np(y3), t2np(y1)) > 1e-3
+
+
+def test_argument_errors_on_device(ctx):
+    say("argument errors")
+    import ctypes as C
+    lib = B.lib()
+    shp = synth.LayerShape(256, 4, 128, 2, 64, act="f32")
+    pair = LayerPair(ctx, shp, seed=2)
+    x = dev(synth.activations(2, 1, 256, "f32")[0])
+    y = torch.empty_like(x)
+    idx = dev(np.array([1, 3], np.int32))
+    w = dev(np.array([0.6, 0.4], np.float32))
+    p = lambda t: C.c_void_p(t.data_ptr())
+    call = lambda k, xx, yy, ii: lib.smoe_expert_ffn(ctx.h, pair.routed.h, None, xx, 0, k, ii, p(w), None,
+                                                     C.c_float(0), None, 0, yy, None)
+    assert call(2, p(x), p(x), p(idx)) == -1                      # y aliases x
+    assert call(5, p(x), p(y), p(idx)) == -2                      # k > E
+    assert call(2, C.c_void_p(x.data_ptr() + 4), p(y), p(idx)) == -3
+    assert call(2, p(x), p(y), None) == -1
+    assert lib.smoe_route(ctx.h, 1, 300, 2, 0, p(x), None, 0, None, None, 0, C.c_float(1), None, p(idx), p(w)) == -2
+    assert lib.smoe_quantize_slice(ctx.h, pair.routed.h, 3, 2, p(x), p(x), p(x)) == -2
+
+
+# ------------------------------------------------------------------------------ full-size layer
+def test_dsv2lite_layer_full_size_sampled_steps(ctx):
+    """The benchmark workload (64 experts of 2048x1408, top-6, 2 shared, bf16) in the launch
+    configuration the bench times; the oracle recomputes sampled steps and sampled experts."""
+    wl = synth.DSV2_LAYER
+    shp = wl.layer
+    say("dsv2-lite layer: quantising 66 experts on the GPU")
+    pair = LayerPair(ctx, shp, seed=wl.seed, gen_device="cuda:0", keep_dense=False)
+    x_all = synth.activations(wl.seed, wl.steps, shp.d_model, shp.act)
+    logits = synth.normal_logits(wl.seed, wl.steps, shp.n_experts)
+    mask, bias = synth.cached_set_mask(wl.seed, shp.n_experts, 32, 16, 1.0)
+    bias_t = torch.from_numpy(bias)
+    # routing decisions for every step: bit-exact
+    idx, w = B.smoe_route(ctx, shp.top_k, logits=dev(logits), bias=dev(bias_t))
+    ridx, rw = O.route(logits.numpy(), bias, shp.top_k)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=2e-5, atol=1e-7)
+    say("  routing of 1024 steps matches; checking sampled steps")
+    steps = [0, 517, 1023]
+    worst = _run_layer_steps(ctx, wl, pair, steps, mask, bias_t, logits, x_all, True)
+    say("  fused worst", worst)
+    # codes of one sampled routed expert and one shared expert: bit-exact at full size
+    for bank, slot, tag in ((pair.routed, int(ridx[0, 0]), int(ridx[0, 0])), (pair.shared, 1, 1001)):
+        ex = pair.oracle_expert(tag)
+        for mi, qm in enumerate((ex.gate, ex.up, ex.down)):
+            got = B.smoe_export_codes(ctx, bank, slot, mi)
+            assert np.array_equal(got["q"], qm.q) and np.array_equal(got["zp"], qm.zp)
+            assert np.array_equal(got["scale"].view(np.uint32), qm.scale.view(np.uint32))

@@ -1,0 +1,96 @@
+"""CPU-only tests of the library's host side: the C ABI loads and exports every declared symbol,
+argument validation that needs no GPU, and the host bookkeeping against the oracle."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import slicemoe_oracle as O
+from paper_2512_12990_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "slicemoe.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(smoe_[a-z_0-9]+)\s*\(", hdr))
+    assert len(declared) >= 20
+    lib = B.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(B.EXPORTS)
+
+
+def test_strerror_and_bank_bytes_validation():
+    lib = B.lib()
+    assert lib.smoe_strerror(0) == b"ok"
+    assert b"aligned" in lib.smoe_strerror(-3)
+    d = B.BankDesc(64, 2048, 1408, 128, 8, 4, B.BF16, B.BF16)
+    n = B.smoe_bank_bytes(d)
+    # two nibble planes (= one 8-bit copy, no duplication) + 3 bytes of metadata per group
+    weights = 64 * 3 * 2048 * 1408
+    groups = 64 * (2 * 1408 * 16 + 2048 * 11)
+    assert weights + 3 * groups <= n <= weights + 3 * groups + 8 * 256 + 64 * 64
+    nbytes = C.c_size_t()
+    for bad, rc in [(B.BankDesc(0, 2048, 1408, 128, 8, 4, 0, 0), -2), (B.BankDesc(4, 2040, 1408, 128, 8, 4, 0, 0), -2),
+                    (B.BankDesc(4, 2048, 1408, 100, 8, 4, 0, 0), -2), (B.BankDesc(4, 2048, 1408, 128, 6, 3, 0, 0), -6),
+                    (B.BankDesc(4, 2048, 1408, 128, 4, 4, 0, 0), -2), (B.BankDesc(4, 2048, 1408, 128, 8, 4, 7, 0), -1)]:
+        assert lib.smoe_bank_bytes(C.byref(bad), C.byref(nbytes)) == rc
+    assert lib.smoe_bank_bytes(None, C.byref(nbytes)) == -1
+    assert lib.smoe_bank_bytes(C.byref(d), None) == -1
+
+
+def test_topn_matches_oracle():
+    rng = np.random.default_rng(0)
+    for L, E in [(1, 4), (3, 5), (24, 60)]:
+        hist = rng.integers(0, 6, size=(L, E)).astype(np.uint32)
+        for n in [0, 1, L * E, L * E + 3, 2 * L * E, 2 * L * E + 10]:
+            assert np.array_equal(B.smoe_topn_slices(hist, n), O.topn_slices(hist, n))
+
+
+def test_cache_matches_oracle_in_lockstep():
+    rng = np.random.default_rng(1)
+    L, E, cap, k = 3, 16, 24, 4
+    c, o = B.Cache(L, E, cap), O.SliceLRU(L, E, cap)
+    hist = rng.integers(0, 9, size=(L, E)).astype(np.uint32)
+    ids = O.topn_slices(hist, cap // 2)
+    c.init_order(ids)
+    o.init_order(ids)
+    for step in range(300):
+        l = int(rng.integers(L))
+        idx = rng.choice(E, size=k, replace=False).astype(np.int32)
+        wh = rng.integers(0, 2, size=k).astype(np.uint8)
+        m1, b1 = c.snapshot(l, 1.0)
+        m2, b2 = o.snapshot(l, 1.0)
+        assert np.array_equal(m1, m2) and np.array_equal(b1, b2)
+        c.access(l, idx, wh)
+        o.access(l, idx, wh)
+        assert c.order() == o.order
+    assert c.stats() == o.stats
+    assert len(c.order()) <= cap
+
+
+def test_cache_argument_errors():
+    lib = B.lib()
+    h = C.c_void_p()
+    assert lib.smoe_cache_create(1, 4, 1, C.byref(h)) == -2
+    assert lib.smoe_cache_create(1, 4, 4, None) == -1
+    c = B.Cache(2, 4, 4)
+    bad = np.array([0, 9], np.int32)
+    assert lib.smoe_cache_access(c.h, 0, 2, bad.ctypes.data_as(C.c_void_p), None) == -2
+    assert lib.smoe_cache_access(c.h, 5, 1, bad.ctypes.data_as(C.c_void_p), None) == -2
+    dup = np.array([1, 1], np.uint32)
+    assert lib.smoe_cache_init_order(c.h, dup.ctypes.data_as(C.c_void_p), 2) == -1
+    assert c.order() == []
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2512_12990_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".cpp", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.replace("the CPU oracle's tests", ""), f
