@@ -1,0 +1,106 @@
+"""GPU parity of the prefill path: routing indices and the per-expert histogram bit-exact,
+grouped-GEMM outputs within the bf16 tolerance, top-N retention order from the GPU histogram."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import slicemoe_oracle as O
+from paper_2512_12990_amd import binding as B
+from paper_2512_12990_amd import synth
+from helpers import LayerPair, t2np
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available()
+    c = B.Ctx(0)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def _check_routing(ctx, x, wr, k, idx, w, hist, E):
+    _, _, z = B.smoe_route(ctx, k, x=x, w_router=wr, want_logits=True)
+    ridx, rw = O.route(z.cpu().numpy(), None, k)          # top-k of the GPU's own fp32 logits
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=2e-5, atol=1e-7)
+    h = hist.cpu().numpy().view(np.uint32)
+    assert np.array_equal(h, O.histogram(ridx, E)) and int(h.sum()) == ridx.size
+    zr = O.router_logits(t2np(x), t2np(wr))
+    np.testing.assert_allclose(z.cpu().numpy(), zr, rtol=0, atol=2e-5 * np.abs(zr).max())
+    return ridx, rw
+
+
+@pytest.mark.parametrize("T,E,k,d,f,G", [(200, 6, 2, 256, 128, 64), (37, 5, 3, 128, 192, 32), (450, 3, 1, 128, 64, 64)])
+def test_prefill_small_all_tokens(ctx, T, E, k, d, f, G):
+    # 200 tokens over 6 experts: one expert tile is ragged; 37 tokens: a single partial fragment;
+    # 450 tokens over 3 experts top-1: some expert gets more than one 192-row tile
+    say("prefill small", T, E, k, d, f, G)
+    shp = synth.LayerShape(d, E, f, k, G, act="bf16")
+    pair = LayerPair(ctx, shp, seed=21)
+    x = synth.activations(21, T, d, "bf16").cuda()
+    wr = synth.router_weight(21, 0, E, d, std=0.05).cuda()
+    for resid in (False, True):
+        y, idx, w, hist = B.smoe_prefill_histogram(ctx, pair.routed, None, x, k, w_router=wr, add_residual=resid)
+        ridx, rw = _check_routing(ctx, x, wr, k, idx, w, hist, E)
+        yref = O.prefill_layer(t2np(x).astype(np.float64), pair.oracle_routed(), ridx,
+                               rw.astype(np.float32).astype(np.float64), add_residual=resid)
+        yg = t2np(y)
+        for t in range(T):
+            assert O.max_abs_rel(yg[t], yref[t]) <= TOL, t
+        assert O.max_abs_rel(yg, yref) <= TOL
+
+
+def test_prefill_empty_expert_and_given_logits(ctx):
+    say("prefill with an expert nobody selects")
+    T, E, k, d, f, G = 64, 4, 2, 128, 64, 32
+    shp = synth.LayerShape(d, E, f, k, G, act="bf16")
+    pair = LayerPair(ctx, shp, seed=22)
+    x = synth.activations(22, T, d, "bf16").cuda()
+    z = synth.normal_logits(22, T, E)
+    z[:, 2] = -30.0
+    y, idx, w, hist = B.smoe_prefill_histogram(ctx, pair.routed, None, x, k, logits=z.cuda(), norm_topk=True)
+    ridx, rw = O.route(z.numpy(), None, k, norm_topk=True)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    h = hist.cpu().numpy().view(np.uint32)
+    assert h[2] == 0 and np.array_equal(h, O.histogram(ridx, E))
+    yref = O.prefill_layer(t2np(x).astype(np.float64), pair.oracle_routed(), ridx, rw)
+    assert O.max_abs_rel(t2np(y), yref) <= TOL
+
+
+def test_prefill_qwen_layer_full_size_sampled_tokens(ctx):
+    """2048 tokens through one Qwen1.5-MoE-shaped layer (60 experts of 2048x1408, top-4, all
+    high-bit): every index and the histogram exactly, sampled token rows against the oracle."""
+    wl = synth.QWEN_PREFILL
+    shp = wl.layer
+    T = wl.prefill_tokens
+    say("qwen prefill layer: quantising 60 experts")
+    pair = LayerPair(ctx, shp, seed=wl.seed, gen_device="cuda:0", keep_dense=False)
+    x = synth.activations(wl.seed, T, shp.d_model, "bf16").cuda()
+    wr = synth.router_weight(wl.seed, 0, shp.n_experts, shp.d_model).cuda()
+    y, idx, w, hist = B.smoe_prefill_histogram(ctx, pair.routed, None, x, shp.top_k, w_router=wr, add_residual=False)
+    torch.cuda.synchronize()
+    say("  prefill done; checking routing of all tokens")
+    ridx, rw = _check_routing(ctx, x, wr, shp.top_k, idx, w, hist, shp.n_experts)
+    hist_np = hist.cpu().numpy().view(np.uint32)
+    ids = B.smoe_topn_slices(hist_np[None, :], 30)
+    assert np.array_equal(ids, O.topn_slices(hist_np[None, :], 30))
+    yg = t2np(y)
+    assert np.isfinite(yg).all()
+    xs = t2np(x).astype(np.float64)
+    for t in (0, 1031, 2047):
+        say("  oracle token", t)
+        prec = np.ones(shp.top_k, np.uint8)
+        yref = O.moe_layer(xs[t], pair.oracle_routed(), ridx[t], rw[t].astype(np.float32).astype(np.float64), prec)
+        err = O.max_abs_rel(yg[t], yref)
+        say("    max-abs-rel", err)
+        assert err <= TOL
