@@ -74,6 +74,8 @@ static size_t layout(const smoe_bank_desc* d, BankDev* b, MatOff* ogu, MatOff* o
     m[i]->plane_stride = (size_t)m[i]->N * m[i]->K / 2;
     m[i]->zp_stride = up16((size_t)m[i]->N * m[i]->ng);
     m[i]->sc_stride = up16((size_t)m[i]->N * m[i]->ng * ssz);
+    m[i]->ps32 = (unsigned)m[i]->plane_stride; m[i]->zs32 = (unsigned)m[i]->zp_stride; m[i]->ss32 = (unsigned)m[i]->sc_stride;
+    m[i]->fits32 = (E * m[i]->plane_stride < 0xFFFF0000ull) ? 1u : 0u;
   }
   // MSB planes of both families first, then LSB planes, then metadata: a low-bit read never
   // touches the LSB region.

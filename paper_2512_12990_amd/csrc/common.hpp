@@ -19,6 +19,8 @@ struct MatDev {
   const uint8_t* msb; const uint8_t* lsb; const uint8_t* zp; const uint8_t* sc;
   unsigned long long plane_stride, zp_stride, sc_stride;   // bytes per expert
   int N, K, ng, cpg;                                       // cpg = 32-column chunks per group
+  unsigned ps32, zs32, ss32, fits32;                       // the strides as 32-bit numbers; fits32 = every
+                                                           // byte offset inside a section is below 2^32
 };
 
 struct BankDev {
@@ -42,26 +44,19 @@ struct smoe_bank {
   int device;
 };
 
-// ---- per-token slot table (device) ----------------------------------------------------------
-struct Slot {
-  const uint8_t *gu_msb, *gu_lsb, *gu_zp, *gu_sc;
-  const uint8_t *dn_msb, *dn_lsb, *dn_zp, *dn_sc;
-  int f;          // d_ff of this expert
-  int h_off;      // offset of its SwiGLU vector in the h buffer (floats) == first flat row pair
-  int prec;       // 1 = HIGH (MSB+LSB), 0 = LOW (MSB only)
-  float weight;   // gate weight w_j, or gamma for a shared expert
-  int gu_ng, gu_cpg, dn_ng, dn_cpg, sc_bf16, pad;
-};
-
-struct SlotTable {
-  int n_slots, total_f, pad0, pad1;
-  Slot s[SMOE_MAX_SLOTS];
+// ---- per-token routing record (device): written by the gate/up kernel, read by the down kernel
+struct RouteRec {
+  int sel[SMOE_MAX_TOPK];     // selected expert of every slot
+  int prec[SMOE_MAX_TOPK];    // 1 = HIGH (MSB+LSB), 0 = LOW (MSB only)
+  float w[SMOE_MAX_TOPK];     // gate weights
+  float gamma;                // weight of the shared experts
+  int pad[15];
 };
 
 // workspace layout (offsets in bytes)
-#define WS_TABLE_OFF 0                       // SlotTable
-#define WS_IDX_OFF (16 << 10)                // int32 [16], float [16], uint8 [16] routing scratch
-#define WS_H_OFF (64 << 10)                  // float h[total_f]   (<= 1M - 16K floats)
+#define WS_REC_OFF 0                         // RouteRec
+#define WS_IDX_OFF (16 << 10)                // routing scratch of smoe_decode_layer without given logits
+#define WS_H_OFF (64 << 10)                  // float h[total_f]
 
 #define HIPCHK(ctx, expr)                                  \
   do {                                                     \

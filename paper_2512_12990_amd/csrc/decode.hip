@@ -1,86 +1,127 @@
 // Decode-time expert FFN over bit-sliced weights (paper Section 4.1: full precision when both
 // slices of an expert are resident, MSB-only otherwise; Section 4.2: the MSB nibble with the
-// truncated zero-point IS the low-bit model).
+// truncated zero-point IS the low-bit model; Section 2.1: cache-aware top-k in the prologue).
 //
-// Three launches per token-layer:
-//   setup   1 work-group : (route,) precision select, gamma, slot table
-//   gateup  many waves   : h = silu(Wg x) * (Wu x) for every slot, one wave per row pair
-//   down    d_model/8 WGs: y = sum_slots weight * Wd h  (+ x), each wave owns two output rows
-// A lane always works on one 32-column chunk (16 bytes of a nibble plane, one 128-bit load); the
-// group-wise affine terms are applied per lane before the cross-lane sum:
-//   HIGH  s * (sum (16 m + l) x  -  zp * sum x)        LOW  16 s * (sum m x - (zp >> 4) * sum x)
+// Two launches per token-layer, both HBM-streaming kernels of 1024-thread work-groups:
+//   gateup  h = silu(Wg x) * (Wu x) for every slot.  Work-group b takes the row pairs
+//           r = b' + n_wg*q of EVERY slot (b' rotated per slot), so all work-groups move the same
+//           bytes whatever the precision mix, and nothing about the split depends on routing:
+//           loads of the shared experts are in flight while wave 0 routes the token.
+//   down    y = sum_slots weight * Wd h (+ x): a work-group owns 8 output rows, its 16 waves split
+//           the (slot, k-slice, row) units evenly; partial sums meet in LDS in a fixed order.
+// A lane always handles one 32-column chunk = 16 bytes of a nibble plane (one 128-bit load) and
+// a wave issues all loads of a batch before it touches the first result; row addresses are
+// wave-uniform (scalar registers), the only per-lane part is the constant lane*16.
+// The kernels are VALU-issue bound before they are HBM bound, so the inner product is integer:
+// with bf16 activations each 32-value chunk of x (or h) is rewritten once, in LDS, as 14-bit
+// integers times a power-of-two chunk scale, split into two signed byte digits (x = 256 xh + xl);
+// a plane word is unpacked with 3 instructions into 8 byte-sized nibbles and consumed by 4
+// four-way int8 dot instructions.  All sums are exact int32:
+//   HIGH  (s sx)    * (16 A_m + A_l - zp X)       LOW  (16 s sx) * (A_m - (zp >> 4) X)
+// with A_p = sum nibble_p * xint over the lane's chunk, X = sum xint, sx the chunk scale.
+// fp32 activations take a plain fp32 path (byte -> float conversions and FMAs).
 #include "route_device.hpp"
 
-// ---------------------------------------------------------------------------------- setup
-struct SetupArgs {
+#define DEC_NT 1024                 // threads per work-group
+#define DEC_NW (DEC_NT / 64)
+#define DEC_MAXP 3                  // row pairs per batch and wave (gate/up kernel)
+#define DEC_MAXU 5                  // units per batch and wave (down kernel)
+#define DEC_RPW 8                   // output rows per work-group (down kernel)
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+struct DecodeArgs {
   BankDev routed, shared;
   int has_routed, n_shared, k, do_route;
-  RouteArgs r;
+  int E, norm_topk;
+  float routed_scale, tau;
+  const float* logits; const float* bias;
   const int32_t* idx_in; const float* w_in;
-  const uint8_t* mask; float tau;
+  const uint8_t* mask;
   const void* x; const void* shared_gate_w;
-  SlotTable* tab;
+  RouteRec* rec;        // routing record (gate/up block 0 writes, down reads)
+  float* h;             // SwiGLU vectors: shared experts first, then the routed slots, fp32
   int32_t* idx_out; float* w_out; uint8_t* prec_out;
+  void* y;
+  int add_residual, d_model;
+  // static work split, worked out on the host
+  int f_r, f_s;                    // d_ff of the routed / shared bank (0 if absent)
+  int cap_r, cap_s;                // gate/up: row pairs per work-group and slot = ceil(f / n_wg)
+  int inv_cap_r, inv_cap_s;        // ceil(65536 / cap)
+  int rot;                         // gate/up: per-slot rotation of the work-group index
+  int gu_rw;                       // gate/up: waves [0, gu_rw) take routed slots, the rest shared experts
+  int ks_r, ks_s, inv_ks_r, inv_ks_s;   // down: 64-chunk k-slices per row, ceil(65536 / ks)
+  int dn_rw;                       // down: waves [0, dn_rw) take routed slots, the rest shared experts
+  int gu_sh_r, gu_sh_s, dn_sh_r, dn_sh_s;  // log2(32-column chunks per quantisation group)
 };
 
-__device__ __forceinline__ void fill_slot(Slot& s, const BankDev& b, int e, int prec, float weight, int h_off) {
-  const size_t ee = (size_t)e;
-  s.gu_msb = b.gu.msb + ee * b.gu.plane_stride; s.gu_lsb = b.gu.lsb + ee * b.gu.plane_stride;
-  s.gu_zp = b.gu.zp + ee * b.gu.zp_stride;      s.gu_sc = b.gu.sc + ee * b.gu.sc_stride;
-  s.dn_msb = b.dn.msb + ee * b.dn.plane_stride; s.dn_lsb = b.dn.lsb + ee * b.dn.plane_stride;
-  s.dn_zp = b.dn.zp + ee * b.dn.zp_stride;      s.dn_sc = b.dn.sc + ee * b.dn.sc_stride;
-  s.f = b.d_ff; s.h_off = h_off; s.prec = prec; s.weight = weight;
-  s.gu_ng = b.gu.ng; s.gu_cpg = b.gu.cpg; s.dn_ng = b.dn.ng; s.dn_cpg = b.dn.cpg; s.sc_bf16 = b.sc_bf16; s.pad = 0;
+__device__ __forceinline__ void lds_barrier() {
+  // orders LDS traffic only; outstanding global loads stay in flight across it
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-template <int ACT>
-__global__ __launch_bounds__(256) void decode_setup_kernel(SetupArgs a) {
-  __shared__ RouteShared sh;
-  __shared__ float red[4];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (a.k > 0) {
-    if (a.do_route) {
-      route_token<ACT>(a.r, 0, sh);
-    } else {
-      if (tid < a.k) { sh.sel[tid] = a.idx_in[tid]; sh.wsel[tid] = a.w_in[tid]; }
-      __syncthreads();
-    }
-  }
-  float gamma = 1.0f;
-  if (a.shared_gate_w) {
-    const int d = a.n_shared ? a.shared.d_model : a.routed.d_model;
-    float p = 0.0f;
-    for (int i = tid; i < d; i += 256) p = fmaf(load_act<ACT>(a.shared_gate_w, i), load_act<ACT>(a.x, i), p);
-    p = wave_sum(p);
-    if (lane == 0) red[wave] = p;
-    __syncthreads();
-    const float dot = (red[0] + red[1]) + (red[2] + red[3]);
-    gamma = 1.0f / (1.0f + expf(-dot));
-  }
-  const int k = a.has_routed ? a.k : 0;
-  const int n_slots = k + a.n_shared;
-  if (tid < k) {
-    int e = sh.sel[tid];
-    e = min(max(e, 0), a.routed.n_experts - 1);
-    const float w = sh.wsel[tid];
-    const int both = a.mask ? ((a.mask[e] & 3) == 3) : 1;
-    const int prec = both && (a.tau <= 0.0f || w >= a.tau);
-    fill_slot(a.tab->s[tid], a.routed, e, prec, w, tid * a.routed.d_ff);
-    if (a.prec_out) a.prec_out[tid] = (uint8_t)prec;
-    if (a.idx_out) a.idx_out[tid] = e;
-    if (a.w_out) a.w_out[tid] = w;
-  } else if (tid < n_slots) {
-    const int i = tid - k;
-    fill_slot(a.tab->s[tid], a.shared, i, 1, gamma, k * (a.has_routed ? a.routed.d_ff : 0) + i * a.shared.d_ff);
-  }
-  if (tid == 0) {
-    a.tab->n_slots = n_slots;
-    a.tab->total_f = k * (a.has_routed ? a.routed.d_ff : 0) + a.n_shared * (a.n_shared ? a.shared.d_ff : 0);
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename T> __device__ __forceinline__ const T* uni_ptr(const T* p) {
+  const unsigned long long v = (unsigned long long)p;
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)v);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v >> 32));
+  return (const T*)(((unsigned long long)hi << 32) | lo);
+}
+
+template <int CTRL, int ROWM, int BANKM> __device__ __forceinline__ float dpp_add(float v) {
+  return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROWM, BANKM, true));
+}
+// Sum over the wave; the total is valid in lane 63 only.  Every lane must take part.
+__device__ __forceinline__ float wave_sum_to63(float v) {
+  v = dpp_add<0xB1, 0xF, 0xF>(v);      // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E, 0xF, 0xF>(v);      // quad_perm [2,3,0,1]: every lane holds its quad's sum
+  v = dpp_add<0x114, 0xF, 0xE>(v);     // row_shr 4, banks 1..3
+  v = dpp_add<0x118, 0xF, 0xC>(v);     // row_shr 8, banks 2..3: lanes 12..15 hold the row sum
+  v = dpp_add<0x142, 0xA, 0xF>(v);     // row_bcast 15 into rows 1 and 3
+  v = dpp_add<0x143, 0xC, 0xF>(v);     // row_bcast 31 into rows 2 and 3
+  return v;
+}
+template <int CTRL> __device__ __forceinline__ int quad_xchg(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+
+// ---------------------------------------------------------------------------------- lane operands
+// The lane's 32 activations.
+//   BF16: p[4j..4j+3] = digits of the values that meet plane word j: high digits of columns
+//         8j+{0,2,4,6}, their low digits, high digits of columns 8j+{1,3,5,7}, their low digits
+//         (one signed byte each); sx = chunk scale, xs = sum of the chunk's integers.
+//   F32 : plain values and their sum.
+template <int ACT> struct XR;
+template <> struct XR<SMOE_BF16> { uint32_t p[16]; float sx; int xs; };
+template <> struct XR<SMOE_F32> { float v[32]; float xs; };
+
+__device__ __forceinline__ void dot_plane_i8(const uint4& m, const XR<SMOE_BF16>& x, int& ah, int& al) {
+  const uint32_t w[4] = {m.x, m.y, m.z, m.w};
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    const int e = (int)(w[j] & 0x0F0F0F0Fu), o = (int)((w[j] >> 4) & 0x0F0F0F0Fu);
+    ah = __builtin_amdgcn_sdot4(e, (int)x.p[4 * j + 0], ah, false);
+    al = __builtin_amdgcn_sdot4(e, (int)x.p[4 * j + 1], al, false);
+    ah = __builtin_amdgcn_sdot4(o, (int)x.p[4 * j + 2], ah, false);
+    al = __builtin_amdgcn_sdot4(o, (int)x.p[4 * j + 3], al, false);
   }
 }
 
-// ---------------------------------------------------------------------------------- nibble dots
-// 32 weights of one plane chunk against the lane's 32 activations (fp32).
+__device__ __forceinline__ float lane_value(const XR<SMOE_BF16>& x, const uint4& m, const uint4& l, int high, int zp,
+                                            float s) {
+  int ah = 0, al = 0;
+  dot_plane_i8(m, x, ah, al);
+  int t = (ah << 8) + al;
+  if (high) {
+    int bh = 0, bl = 0;
+    dot_plane_i8(l, x, bh, bl);
+    t = (t << 4) + (bh << 8) + bl - zp * x.xs;
+    return (s * x.sx) * (float)t;
+  }
+  t -= (zp >> 4) * x.xs;
+  return (16.0f * s * x.sx) * (float)t;
+}
+
 __device__ __forceinline__ float dot_bytes(uint32_t e, uint32_t o, const float* x, float acc0, float& acc1) {
   acc0 = fmaf((float)(e & 0xFF), x[0], acc0);
   acc1 = fmaf((float)(o & 0xFF), x[1], acc1);
@@ -93,154 +134,585 @@ __device__ __forceinline__ float dot_bytes(uint32_t e, uint32_t o, const float* 
   return acc0;
 }
 
-__device__ __forceinline__ float dot_low(const uint4& m, const float* x) {
-  const uint32_t w[4] = {m.x, m.y, m.z, m.w};
-  float a0 = 0.0f, a1 = 0.0f;
-#pragma unroll
-  for (int j = 0; j < 4; j++)
-    a0 = dot_bytes(w[j] & 0x0F0F0F0Fu, (w[j] >> 4) & 0x0F0F0F0Fu, x + 8 * j, a0, a1);
-  return a0 + a1;
-}
-
-__device__ __forceinline__ float dot_high(const uint4& m, const uint4& l, const float* x) {
+__device__ __forceinline__ float lane_value(const XR<SMOE_F32>& x, const uint4& m, const uint4& l, int high, int zp,
+                                            float s) {
   const uint32_t wm[4] = {m.x, m.y, m.z, m.w}, wl[4] = {l.x, l.y, l.z, l.w};
   float a0 = 0.0f, a1 = 0.0f;
+  if (high) {
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const uint32_t qe = ((wm[j] & 0x0F0F0F0Fu) << 4) | (wl[j] & 0x0F0F0F0Fu);     // codes of even columns
+      const uint32_t qo = (wm[j] & 0xF0F0F0F0u) | ((wl[j] >> 4) & 0x0F0F0F0Fu);    // codes of odd columns
+      a0 = dot_bytes(qe, qo, x.v + 8 * j, a0, a1);
+    }
+    return s * fmaf(-(float)zp, x.xs, a0 + a1);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; j++) a0 = dot_bytes(wm[j] & 0x0F0F0F0Fu, (wm[j] >> 4) & 0x0F0F0F0Fu, x.v + 8 * j, a0, a1);
+  return (16.0f * s) * fmaf(-(float)(zp >> 4), x.xs, a0 + a1);
+}
+
+// ---------------------------------------------------------------------------------- LDS staging
+// A vector of n = 32*C values is kept in LDS per 64-chunk k-slice as [piece][chunk][16 bytes] so
+// that the lanes of a wave read consecutive 16-byte pieces.  BF16: 4 pieces per chunk (64 B, the
+// digit words of XR), F32: 8 pieces of 4 floats (128 B).  cs[c] = (chunk scale, chunk sum).
+template <int ACT> struct StageTraits;
+template <> struct StageTraits<SMOE_BF16> { enum { BYTES_PER_VAL = 2 }; };
+template <> struct StageTraits<SMOE_F32> { enum { BYTES_PER_VAL = 4 }; };
+
+// Eight consecutive values as loaded (no arithmetic on them, so nothing waits for the load).
+struct Raw8 { uint4 a, b; };
+template <int SRC> __device__ __forceinline__ void load8_raw(const void* src, size_t i0, Raw8& r) {
+  if (SRC == SMOE_F32) {
+    r.a = *(const uint4*)((const float*)src + i0);
+    r.b = *(const uint4*)((const float*)src + i0 + 4);
+  } else {
+    r.a = *(const uint4*)((const uint16_t*)src + i0);
+  }
+}
+template <int SRC> __device__ __forceinline__ void unpack8(const Raw8& r, float* v) {
+  if (SRC == SMOE_F32) {
+    v[0] = __uint_as_float(r.a.x); v[1] = __uint_as_float(r.a.y); v[2] = __uint_as_float(r.a.z); v[3] = __uint_as_float(r.a.w);
+    v[4] = __uint_as_float(r.b.x); v[5] = __uint_as_float(r.b.y); v[6] = __uint_as_float(r.b.z); v[7] = __uint_as_float(r.b.w);
+  } else {
+    const uint32_t w[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
+#pragma unroll
+    for (int i = 0; i < 4; i++) { v[2 * i] = bf16_bits_to_f32(w[i] & 0xFFFF); v[2 * i + 1] = bf16_bits_to_f32(w[i] >> 16); }
+  }
+}
+
+__device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
+  return (uint32_t)(a & 255) | ((uint32_t)(b & 255) << 8) | ((uint32_t)(c & 255) << 16) | ((uint32_t)d << 24);
+}
+
+// Stages the 8 values v[0..8) = word j of chunk c of a vector with C chunks into dst (byte
+// address of that vector inside LDS) and its chunk figures into cs[c].  The four words of a chunk
+// must be handled by the four lanes of one quad in the same call.
+template <int ACT>
+__device__ __forceinline__ void stage_regs(float* v, int C, int c, int j, uint8_t* dst, float2* cs) {
+  const int ks = c >> 6, cw = min(64, C - ks * 64), cl = c & 63;
+  if (ACT == SMOE_BF16) {
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; i++) amax = fmaxf(amax, fabsf(v[i]));
+    amax = fmaxf(amax, __int_as_float(quad_xchg<0xB1>(__float_as_int(amax))));
+    amax = fmaxf(amax, __int_as_float(quad_xchg<0x4E>(__float_as_int(amax))));
+    // chunk scale 2^(e-13), e = exponent of the largest magnitude: integers stay below 2^14
+    const int be = (int)(__float_as_uint(amax) >> 23);
+    const bool live = be >= 20 && be < 255;
+    const float inv = live ? __uint_as_float((uint32_t)(267 - be) << 23) : 0.0f;
+    const float sx = live ? __uint_as_float((uint32_t)(be - 13) << 23) : 0.0f;
+    int xh[8], xl[8], part = 0;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      const int q = (int)rintf(v[i] * inv);
+      xl[i] = ((q + 128) & 255) - 128;          // balanced low digit in [-128, 127]
+      xh[i] = (q - xl[i]) >> 8;
+      part += q;
+    }
+    part += quad_xchg<0xB1>(part);
+    part += quad_xchg<0x4E>(part);
+    const uint4 o = make_uint4(pack4(xh[0], xh[2], xh[4], xh[6]), pack4(xl[0], xl[2], xl[4], xl[6]),
+                               pack4(xh[1], xh[3], xh[5], xh[7]), pack4(xl[1], xl[3], xl[5], xl[7]));
+    *(uint4*)(dst + (size_t)ks * 4096 + (size_t)(j * cw + cl) * 16) = o;
+    if (j == 0) cs[c] = make_float2(sx, __int_as_float(part));
+  } else {
+    float part = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; i++) part += v[i];
+    uint8_t* base = dst + (size_t)ks * 8192;
+    *(float4*)(base + (size_t)((2 * j) * cw + cl) * 16) = make_float4(v[0], v[1], v[2], v[3]);
+    *(float4*)(base + (size_t)((2 * j + 1) * cw + cl) * 16) = make_float4(v[4], v[5], v[6], v[7]);
+    part += __int_as_float(quad_xchg<0xB1>(__float_as_int(part)));
+    part += __int_as_float(quad_xchg<0x4E>(__float_as_int(part)));
+    if (j == 0) cs[c] = make_float2(1.0f, part);
+  }
+}
+
+template <int ACT>
+__device__ __forceinline__ void load_xr(XR<ACT>& x, const uint8_t* vec, const float2* cs, int ks, int cw, int lane) {
+  const float2 c = cs[ks * 64 + lane];
+  if (ACT == SMOE_BF16) {
+    const uint4* b = (const uint4*)(vec + (size_t)ks * 4096);
+    XR<SMOE_BF16>& xb = *(XR<SMOE_BF16>*)&x;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const uint4 q = b[j * cw + lane];
+      xb.p[4 * j] = q.x; xb.p[4 * j + 1] = q.y; xb.p[4 * j + 2] = q.z; xb.p[4 * j + 3] = q.w;
+    }
+    xb.sx = c.x; xb.xs = __float_as_int(c.y);
+  } else {
+    const float4* b = (const float4*)(vec + (size_t)ks * 8192);
+    XR<SMOE_F32>& xf = *(XR<SMOE_F32>*)&x;
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      const float4 q = b[j * cw + lane];
+      xf.v[4 * j] = q.x; xf.v[4 * j + 1] = q.y; xf.v[4 * j + 2] = q.z; xf.v[4 * j + 3] = q.w;
+    }
+    xf.xs = c.y;
+  }
+}
+
+// ---------------------------------------------------------------------------------- metadata addressing
+// Scale of element `elem + g` of an expert's scale block: a wave-uniform row pointer plus a small
+// per-lane offset.  16-bit scales are fetched as the aligned dword that contains them (a 16-bit
+// load would let the compiler pack two into one register, which forces it to wait for the load).
+template <int SCB>
+__device__ __forceinline__ uint32_t load_scale_raw(const uint8_t* sc, unsigned block_off, unsigned elem, int g, int& odd) {
+  if (SCB) {
+    const int t = (int)(elem & 1u) + g;
+    odd = t & 1;
+    return *(const uint32_t*)(sc + (block_off + (elem >> 1) * 4u + (unsigned)((t >> 1) << 2)));
+  }
+  odd = 0;
+  return *(const uint32_t*)(sc + (block_off + elem * 4u + (unsigned)(g << 2)));
+}
+template <int SCB> __device__ __forceinline__ float scale_val(uint32_t raw, int odd) {
+  return SCB ? __uint_as_float(odd ? (raw & 0xFFFF0000u) : (raw << 16)) : __uint_as_float(raw);
+}
+
+// ---------------------------------------------------------------------------------- routing by one wave
+template <int CTRL, int ROWM, int BANKM> __device__ __forceinline__ uint32_t dpp_umax(uint32_t v) {
+  const uint32_t t = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROWM, BANKM, true);
+  return t > v ? t : v;
+}
+// Unsigned maximum over the wave, returned in every lane.
+__device__ __forceinline__ uint32_t wave_umax(uint32_t v) {
+  v = dpp_umax<0xB1, 0xF, 0xF>(v);
+  v = dpp_umax<0x4E, 0xF, 0xF>(v);
+  v = dpp_umax<0x114, 0xF, 0xE>(v);
+  v = dpp_umax<0x118, 0xF, 0xC>(v);
+  v = dpp_umax<0x142, 0xA, 0xF>(v);
+  v = dpp_umax<0x143, 0xC, 0xF>(v);
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+__device__ __forceinline__ float wave_sum_all(float v) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wave_sum_to63(v)), 63));
+}
+__device__ __forceinline__ float unorderable(uint32_t o) {
+  return __uint_as_float((o & 0x80000000u) ? (o ^ 0x80000000u) : ~o);
+}
+
+// Same decision rule as route_token (route_device.hpp) -- k largest biased scores, ties to the
+// lower expert index, weights from the softmax of the unbiased logits -- executed by a single
+// wave with cross-lane DPP reductions only.  Lane e (+64j) holds logit, bias and slice mask of
+// expert e; the loads are issued by route_load so that they overlap other work.
+struct RouteRegs { float z[4]; float b[4]; int mk[4]; };
+
+__device__ __forceinline__ void route_load(const DecodeArgs& a, int lane, RouteRegs& r) {
 #pragma unroll
   for (int j = 0; j < 4; j++) {
-    const uint32_t qe = ((wm[j] & 0x0F0F0F0Fu) << 4) | (wl[j] & 0x0F0F0F0Fu);      // codes of even columns
-    const uint32_t qo = (wm[j] & 0xF0F0F0F0u) | ((wl[j] >> 4) & 0x0F0F0F0Fu);     // codes of odd columns
-    a0 = dot_bytes(qe, qo, x + 8 * j, a0, a1);
-  }
-  return a0 + a1;
-}
-
-// One matrix row chunk -> the lane's share of the dequantised dot product.
-__device__ __forceinline__ float row_chunk(const uint8_t* msb, const uint8_t* lsb, const uint8_t* zp, const uint8_t* sc,
-                                           int sc_bf16, size_t plane_off, size_t meta_idx, int prec,
-                                           const float* x, float xs) {
-  const uint4 m = *(const uint4*)(msb + plane_off);
-  const int z = zp[meta_idx];
-  const float s = load_scale(sc, sc_bf16, meta_idx);
-  if (prec) {
-    const uint4 l = *(const uint4*)(lsb + plane_off);
-    return s * fmaf(-(float)z, xs, dot_high(m, l, x));
-  }
-  return (16.0f * s) * fmaf(-(float)(z >> 4), xs, dot_low(m, x));
-}
-
-// ---------------------------------------------------------------------------------- gate/up
-// Flat row-pair space over all slots: pair p belongs to the slot with h_off <= p < h_off + f.
-// Wave gw handles pairs [gw*ppw, (gw+1)*ppw).  d_model <= 2048: one chunk per lane.
-template <int ACT>
-__global__ __launch_bounds__(256) void gateup_kernel(const SlotTable* __restrict__ tab, const void* __restrict__ x,
-                                                     float* __restrict__ h, int d_model, int ppw) {
-  const int lane = threadIdx.x & 63;
-  const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int total = tab->total_f, n_slots = tab->n_slots;
-  int p = gw * ppw;
-  if (p >= total) return;
-  const int pend = min(total, p + ppw);
-  const int C = d_model >> 5;
-  const bool act = lane < C;
-  float xr[32];
-  float xs = 0.0f;
-#pragma unroll
-  for (int i = 0; i < 32; i++) { xr[i] = act ? load_act<ACT>(x, (size_t)lane * 32 + i) : 0.0f; }
-#pragma unroll
-  for (int i = 0; i < 32; i++) xs += xr[i];
-  int si = 0;
-  const size_t rowb = (size_t)d_model >> 1;
-  for (; p < pend; p++) {
-    while (si + 1 < n_slots && p >= tab->s[si + 1].h_off) si++;
-    const Slot& s = tab->s[si];
-    const int r = p - s.h_off;
-    float a = 0.0f, u = 0.0f;
-    if (act) {
-      const int g = lane / s.gu_cpg;
-      a = row_chunk(s.gu_msb, s.gu_lsb, s.gu_zp, s.gu_sc, s.sc_bf16, (size_t)(2 * r) * rowb + lane * 16,
-                    (size_t)(2 * r) * s.gu_ng + g, s.prec, xr, xs);
-      u = row_chunk(s.gu_msb, s.gu_lsb, s.gu_zp, s.gu_sc, s.sc_bf16, (size_t)(2 * r + 1) * rowb + lane * 16,
-                    (size_t)(2 * r + 1) * s.gu_ng + g, s.prec, xr, xs);
-    }
-    a = wave_sum(a);
-    u = wave_sum(u);
-    if (lane == 0) h[p] = a / (1.0f + __expf(-a)) * u;
+    const int e = lane + 64 * j;
+    const bool ok = e < a.E;
+    r.z[j] = (ok && a.do_route) ? a.logits[e] : 0.0f;
+    r.b[j] = (ok && a.do_route && a.bias) ? a.bias[e] : 0.0f;
+    r.mk[j] = (ok && a.mask) ? a.mask[e] : 3;
   }
 }
 
-// ---------------------------------------------------------------------------------- down + combine
-// Work-group of 4 waves owns 8 output rows (2 per wave) and walks every slot.  The weighted
-// SwiGLU vectors of all slots are staged in LDS, chunk-interleaved inside each 64-chunk k-slice
-// so that a lane's 8 x 16-byte reads are conflict free.
-template <int ACT>
-__global__ __launch_bounds__(256) void down_kernel(const SlotTable* __restrict__ tab, const float* __restrict__ h,
-                                                   const void* __restrict__ x, void* __restrict__ y, int d_model,
-                                                   int add_residual) {
-  extern __shared__ float lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int total = tab->total_f, n_slots = tab->n_slots;
-  float* hs = lds;                 // [total] staged, permuted
-  float* cs = lds + total;         // [total/32] per-chunk sums
-  for (int si = 0; si < n_slots; si++) {
-    const Slot& s = tab->s[si];
-    const int C = s.f >> 5;
-    for (int i = tid; i < s.f; i += 256) {
-      const int c = i >> 5, j = (i >> 2) & 7, e = i & 3;
-      const int ks = c >> 6, cw = min(64, C - ks * 64), cl = c & 63;
-      hs[s.h_off + ks * 2048 + (j * cw + cl) * 4 + e] = s.weight * h[s.h_off + i];
-    }
-  }
-  __syncthreads();
-  for (int si = 0; si < n_slots; si++) {
-    const Slot& s = tab->s[si];
-    const int C = s.f >> 5;
-    for (int c = tid; c < C; c += 256) {
-      const int ks = c >> 6, cw = min(64, C - ks * 64), cl = c & 63;
-      float t = 0.0f;
-      for (int j = 0; j < 8; j++)
-        for (int e = 0; e < 4; e++) t += hs[s.h_off + ks * 2048 + (j * cw + cl) * 4 + e];
-      cs[(s.h_off >> 5) + c] = t;
-    }
-  }
-  __syncthreads();
-  const int n0 = blockIdx.x * 8 + wave * 2;
-  float acc0 = 0.0f, acc1 = 0.0f;
-  for (int si = 0; si < n_slots; si++) {
-    const Slot& s = tab->s[si];
-    const int C = s.f >> 5;
-    const size_t rowb = (size_t)s.f >> 1;
-    for (int ks = 0; ks * 64 < C; ks++) {
-      const int cw = min(64, C - ks * 64);
-      if (lane < cw) {
-        const int c = ks * 64 + lane;
-        float xr[32];
-        const float4* src = (const float4*)(hs + s.h_off + ks * 2048);
+// Fills rec.sel / rec.prec / rec.w (LDS) for the k routed slots.  NJ = experts per lane.
+template <int NJ>
+__device__ void route_compute(const DecodeArgs& a, int lane, RouteRegs& rr, RouteRec& rec) {
+  const int E = a.E, k = a.k;
+  int mysel = 0, mymask = 3;
+  float myw = 0.0f;
+  if (a.do_route) {
+    uint32_t ord[NJ];              // orderable biased score; 0 = absent or already taken
+    float p[NJ];
+    uint32_t zmax_o = 0;
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-          const float4 v = src[j * cw + lane];
-          xr[4 * j] = v.x; xr[4 * j + 1] = v.y; xr[4 * j + 2] = v.z; xr[4 * j + 3] = v.w;
-        }
-        const float xs = cs[(s.h_off >> 5) + c];
-        const int g = c / s.dn_cpg;
-        acc0 += row_chunk(s.dn_msb, s.dn_lsb, s.dn_zp, s.dn_sc, s.sc_bf16, (size_t)n0 * rowb + c * 16,
-                          (size_t)n0 * s.dn_ng + g, s.prec, xr, xs);
-        acc1 += row_chunk(s.dn_msb, s.dn_lsb, s.dn_zp, s.dn_sc, s.sc_bf16, (size_t)(n0 + 1) * rowb + c * 16,
-                          (size_t)(n0 + 1) * s.dn_ng + g, s.prec, xr, xs);
+    for (int j = 0; j < NJ; j++) {
+      const bool ok = lane + 64 * j < E;
+      ord[j] = ok ? orderable(rr.z[j] + rr.b[j]) : 0u;
+      const uint32_t zo = ok ? orderable(rr.z[j]) : 0u;
+      zmax_o = zo > zmax_o ? zo : zmax_o;
+    }
+    const float m = unorderable(wave_umax(zmax_o));
+    float den = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) { p[j] = (lane + 64 * j < E) ? expf(rr.z[j] - m) : 0.0f; den += p[j]; }
+    den = wave_sum_all(den);
+    float psum = 0.0f, myp = 0.0f;
+    for (int r = 0; r < k; r++) {
+      uint32_t best = ord[0];
+      int jb = 0;
+#pragma unroll
+      for (int j = 1; j < NJ; j++) if (ord[j] > best) { best = ord[j]; jb = j; }
+      const uint32_t top = wave_umax(best);
+      int ls, js;
+      if (NJ == 1) {                                            // lowest lane among equal scores
+        ls = (int)__builtin_ctzll(__ballot(best == top)); js = 0;
+      } else {
+        const uint32_t cand = best == top ? (uint32_t)(lane + 64 * jb) : 0xFFFFFFFFu;
+        const int e_star = (int)~wave_umax(~cand);              // lowest index among equal scores
+        ls = e_star & 63; js = e_star >> 6;
       }
+      float pw = 0.0f;
+      int mk = 3;
+#pragma unroll
+      for (int j = 0; j < NJ; j++) {
+        const float t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p[j]), ls));
+        const int u = __builtin_amdgcn_readlane(rr.mk[j], ls);
+        if (js == j) { pw = t; mk = u; }
+        if (js == j && lane == ls) ord[j] = 0u;
+      }
+      psum += pw;
+      if (lane == r) { myp = pw; mysel = ls + 64 * js; mymask = mk; }
+    }
+    myw = myp / den;
+    if (a.norm_topk) myw = myw / (psum / den);
+    myw *= a.routed_scale;
+  } else if (lane < k) {
+    mysel = min(max(a.idx_in[lane], 0), E - 1);
+    myw = a.w_in[lane];
+    mymask = a.mask ? a.mask[mysel] : 3;
+  }
+  if (lane < k) {
+    rec.sel[lane] = mysel;
+    rec.w[lane] = myw;
+    rec.prec[lane] = ((mymask & 3) == 3) && (a.tau <= 0.0f || myw >= a.tau);
+  }
+}
+
+// ---------------------------------------------------------------------------------- gate/up kernel
+// A work-group takes the row pairs r = b' + n_wg*q (q < cap) of every slot, b' = (block + slot*rot)
+// mod n_wg.  Its waves are specialised: waves [0, gu_rw) work on the routed slots (entry e ->
+// slot e / cap_r, q = e % cap_r) and must wait for the routing decision; the other waves work on
+// the shared experts (entry e -> expert e / cap_s) and have their loads in flight from the first
+// instruction.  A wave of a group of n takes entries first, first + n, ...
+struct PairRef { int valid, slot, r; };
+
+__device__ __forceinline__ PairRef pair_ref(int e, int n_entries, int cap, int inv_cap, int slot_base, int rot, int f) {
+  PairRef p;
+  p.slot = (e * inv_cap) >> 16;
+  const int q = e - p.slot * cap;
+  int bp = (int)blockIdx.x + (slot_base + p.slot) * rot;
+  bp = bp >= (int)gridDim.x ? bp - (int)gridDim.x : bp;
+  p.r = bp + (int)gridDim.x * q;
+  p.valid = e < n_entries && p.r < f;
+  return p;
+}
+
+template <int ACT, int SCB>
+__global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
+  __shared__ RouteRec rec;
+  __shared__ __align__(16) uint8_t xvec[2048 * StageTraits<ACT>::BYTES_PER_VAL];
+  __shared__ float2 xcs[64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
+  const int d = a.d_model, C = d >> 5;
+  const int k = a.has_routed ? a.k : 0;
+  const unsigned rowb32 = (unsigned)d >> 1;
+  const unsigned voff = (unsigned)lane * 16u;
+  const bool routed_wave = wave < a.gu_rw;
+
+  uint4 gm[DEC_MAXP], um[DEC_MAXP], gl[DEC_MAXP], ul[DEC_MAXP];
+  uint32_t zg[DEC_MAXP], zu[DEC_MAXP], sg[DEC_MAXP], su[DEC_MAXP];      // raw zero-points and scale bits
+  int og[DEC_MAXP], ou[DEC_MAXP];                                        // position of a 16-bit scale in its dword
+
+  // every address is a section base (kernel argument, scalar) plus a 32-bit offset whose only
+  // per-lane part is lane*16 (planes) or the lane's group number (metadata)
+  auto issue = [&](int j, int r, const MatDev& md, int e, int prec, int sh) {
+    const unsigned ng = (unsigned)md.ng;
+    const unsigned po = (unsigned)e * md.ps32 + (unsigned)(2 * r) * rowb32;
+    gm[j] = *(const uint4*)(md.msb + (po + voff));
+    um[j] = *(const uint4*)(md.msb + (po + rowb32 + voff));
+    if (prec) {
+      gl[j] = *(const uint4*)(md.lsb + (po + voff));
+      ul[j] = *(const uint4*)(md.lsb + (po + rowb32 + voff));
+    }
+    const int g = lane >> sh;
+    const unsigned zo = (unsigned)e * md.zs32 + (unsigned)(2 * r) * ng;
+    zg[j] = md.zp[zo + (unsigned)g];
+    zu[j] = md.zp[zo + ng + (unsigned)g];
+    sg[j] = load_scale_raw<SCB>(md.sc, (unsigned)e * md.ss32, (unsigned)(2 * r) * ng, g, og[j]);
+    su[j] = load_scale_raw<SCB>(md.sc, (unsigned)e * md.ss32, (unsigned)(2 * r + 1) * ng, g, ou[j]);
+  };
+  auto finish = [&](int j, int prec, const XR<ACT>& x, int hidx) {
+    float av = 0.0f, uv = 0.0f;
+    if (lane < C) {
+      av = lane_value(x, gm[j], gl[j], prec, (int)zg[j], scale_val<SCB>(sg[j], og[j]));
+      uv = lane_value(x, um[j], ul[j], prec, (int)zu[j], scale_val<SCB>(su[j], ou[j]));
+    }
+    av = wave_sum_to63(av);
+    uv = wave_sum_to63(uv);
+    if (lane == 63) a.h[hidx] = av / (1.0f + __expf(-av)) * uv;
+  };
+
+  // ---- loads that depend on nothing: x (staged by the waves after wave 0, which has the routing to
+  // do), the routing inputs (wave 0) and, in the shared-expert waves, the first batch of rows
+  const int xt = tid - 64;
+  Raw8 xraw;
+  if (xt >= 0 && xt < 4 * C) load8_raw<ACT>(a.x, (size_t)xt * 8, xraw);
+  RouteRegs rr;
+  if (wave == 0 && k > 0) route_load(a, lane, rr);
+
+  // entry t of this wave: index first + t * n, n = number of waves of its kind
+  const int n_se = a.n_shared * a.cap_s, n_re = k * a.cap_r;
+  const int my_first = routed_wave ? wave : wave - a.gu_rw, my_n = routed_wave ? a.gu_rw : DEC_NW - a.gu_rw;
+  const int my_cnt = routed_wave ? n_re : n_se;
+  auto entry = [&](int t) {
+    return routed_wave ? pair_ref(my_first + t * my_n, n_re, a.cap_r, a.inv_cap_r, a.n_shared, a.rot, a.f_r)
+                       : pair_ref(my_first + t * my_n, n_se, a.cap_s, a.inv_cap_s, 0, a.rot, a.f_s);
+  };
+  auto hidx_of = [&](const PairRef& p) {
+    return routed_wave ? a.n_shared * a.f_s + p.slot * a.f_r + p.r : p.slot * a.f_s + p.r;
+  };
+
+  if (!routed_wave) {
+#pragma unroll
+    for (int j = 0; j < DEC_MAXP; j++) {
+      const PairRef p = entry(j);
+      if (p.valid && lane < C) issue(j, p.r, a.shared.gu, p.slot, 1, a.gu_sh_s);
     }
   }
-  acc0 = wave_sum(acc0);
-  acc1 = wave_sum(acc1);
-  if (lane == 0) {
-    if (add_residual) { acc0 += load_act<ACT>(x, n0); acc1 += load_act<ACT>(x, n0 + 1); }
-    store_act<ACT>(y, n0, acc0);
-    store_act<ACT>(y, n0 + 1, acc1);
+
+  // ---- x into LDS, routing decision into LDS
+  if (xt >= 0 && xt < 4 * C) {
+    float xv[8];
+    unpack8<ACT>(xraw, xv);
+    stage_regs<ACT>(xv, C, xt >> 2, xt & 3, xvec, xcs);
+  }
+  if (wave == 0 && k > 0) {
+    if (a.E <= 64) route_compute<1>(a, lane, rr, rec);
+    else route_compute<4>(a, lane, rr, rec);
+  }
+  if (blockIdx.x == 0 && wave == DEC_NW - 1) {          // weight of the shared experts
+    float g = 1.0f;
+    if (a.shared_gate_w) {
+      float p = 0.0f;
+      for (int i = lane; i < d; i += 64) p = fmaf(load_act<ACT>(a.shared_gate_w, i), load_act<ACT>(a.x, i), p);
+      g = 1.0f / (1.0f + expf(-wave_sum(p)));
+    }
+    if (lane == 0) rec.gamma = g;
+  }
+  lds_barrier();
+  if (blockIdx.x == 0 && tid < 64) {                      // publish for the down kernel and the caller
+    if (tid < k) {
+      a.rec->sel[tid] = rec.sel[tid]; a.rec->prec[tid] = rec.prec[tid]; a.rec->w[tid] = rec.w[tid];
+      if (a.prec_out) a.prec_out[tid] = (uint8_t)rec.prec[tid];
+      if (a.idx_out) a.idx_out[tid] = rec.sel[tid];
+      if (a.w_out) a.w_out[tid] = rec.w[tid];
+    }
+    if (tid == 0) a.rec->gamma = rec.gamma;
+  }
+
+  int pr[DEC_MAXP], hidx[DEC_MAXP];
+#pragma unroll
+  for (int j = 0; j < DEC_MAXP; j++) {
+    const PairRef p = entry(j);
+    hidx[j] = p.valid ? hidx_of(p) : -1;
+    pr[j] = 1;
+    if (routed_wave && p.valid) {
+      pr[j] = uni(rec.prec[p.slot]);
+      if (lane < C) issue(j, p.r, a.routed.gu, uni(rec.sel[p.slot]), pr[j], a.gu_sh_r);
+    }
+  }
+  XR<ACT> x;
+  if (lane < C) load_xr<ACT>(x, xvec, xcs, 0, C, lane);
+#pragma unroll
+  for (int j = 0; j < DEC_MAXP; j++)
+    if (hidx[j] >= 0) finish(j, pr[j], x, hidx[j]);
+
+  // layers with more than DEC_MAXP entries per wave: the rest one at a time
+  for (int t = DEC_MAXP; my_first + t * my_n < my_cnt; t++) {
+    const PairRef p = entry(t);
+    if (!p.valid) continue;
+    const int prec = routed_wave ? uni(rec.prec[p.slot]) : 1;
+    if (lane < C) {
+      if (routed_wave) issue(0, p.r, a.routed.gu, uni(rec.sel[p.slot]), prec, a.gu_sh_r);
+      else issue(0, p.r, a.shared.gu, p.slot, 1, a.gu_sh_s);
+    }
+    finish(0, prec, x, hidx_of(p));
+  }
+}
+
+// ---------------------------------------------------------------------------------- down kernel
+// A work-group owns DEC_RPW output rows.  Units = (slot, k-slice, row); unit u of a list: row =
+// u % 8, combo = u / 8 -> (slot, k-slice) = (combo / ks, combo % ks).  Waves [0, dn_rw) take the
+// routed list (and wait for the routing record), the other waves the shared-expert list, whose
+// loads are in flight from the first instruction.  A wave of a group of n takes a contiguous
+// share of its list, so that consecutive units mostly reuse the same h chunk.
+struct UnitRef { int slot, ks, row; };
+
+__device__ __forceinline__ UnitRef unit_ref(int u, int ks_n, int inv_ks) {
+  UnitRef r;
+  r.row = u & (DEC_RPW - 1);
+  const int combo = u / DEC_RPW;
+  r.slot = (combo * inv_ks) >> 16;
+  r.ks = combo - r.slot * ks_n;
+  return r;
+}
+
+template <int ACT, int SCB>
+__global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_bytes) {
+  extern __shared__ __align__(16) uint8_t dyn[];     // [h vectors][chunk figures][unit partials]
+  __shared__ RouteRec rec;
+  const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
+  const int k = a.has_routed ? a.k : 0;
+  const int nsf = a.n_shared * a.f_s;
+  const int total_f = nsf + k * a.f_r;
+  uint8_t* hvec = dyn;
+  float2* hcs = (float2*)(dyn + lds_vec_bytes);
+  float* part = (float*)(hcs + (total_f >> 5));     // shared-expert units first, then routed units
+  const int n0 = blockIdx.x * DEC_RPW;
+  const unsigned voff = (unsigned)lane * 16u;
+  const bool routed_wave = wave < a.dn_rw;
+  const int n_su = a.n_shared * a.ks_s * DEC_RPW, n_ru = k * a.ks_r * DEC_RPW, n_sw = DEC_NW - a.dn_rw;
+
+  uint4 wm[DEC_MAXU], wl[DEC_MAXU];
+  uint32_t zz[DEC_MAXU], ss[DEC_MAXU];      // raw zero-points and scale bits
+  int so[DEC_MAXU];
+
+  auto issue = [&](int j, const UnitRef& u, int f, const MatDev& md, int e, int prec, int sh) {
+    const int cw = min(64, (f >> 5) - u.ks * 64);
+    if (lane < cw) {
+      const unsigned po = (unsigned)e * md.ps32 + (unsigned)(n0 + u.row) * ((unsigned)f >> 1) + (unsigned)u.ks * 1024u;
+      wm[j] = *(const uint4*)(md.msb + (po + voff));
+      if (prec) wl[j] = *(const uint4*)(md.lsb + (po + voff));
+      const int g = lane >> sh;
+      const unsigned elem = (unsigned)(n0 + u.row) * (unsigned)md.ng + (unsigned)((u.ks * 64) >> sh);
+      zz[j] = md.zp[(unsigned)e * md.zs32 + elem + (unsigned)g];
+      ss[j] = load_scale_raw<SCB>(md.sc, (unsigned)e * md.ss32, elem, g, so[j]);
+    }
+  };
+  // consumes the units [b0, b0 + DEC_MAXU) of a list; h chunk registers are reloaded on a new combo
+  auto finish = [&](int j, const UnitRef& u, int f, int hoff, int prec, float wt, XR<ACT>& x, int& cur, int combo, int pidx) {
+    const int cw = min(64, (f >> 5) - u.ks * 64);
+    if (combo != cur) {
+      cur = combo;
+      if (lane < cw) load_xr<ACT>(x, hvec + (size_t)hoff * StageTraits<ACT>::BYTES_PER_VAL, hcs + (hoff >> 5), u.ks, cw, lane);
+    }
+    float v = 0.0f;
+    if (lane < cw) v = lane_value(x, wm[j], wl[j], prec, (int)zz[j], scale_val<SCB>(ss[j], so[j]));
+    v = wave_sum_to63(v);
+    if (lane == 63) part[pidx] = wt * v;
+  };
+
+  // ---- loads that depend on nothing: the routing record, h, and (shared-expert waves) plane rows
+  int rec_word = 0;
+  if (tid < (int)(sizeof(RouteRec) / 4)) rec_word = ((const int*)a.rec)[tid];
+  Raw8 hraw[2];
+  int hitem[2];
+#pragma unroll
+  for (int q = 0; q < 2; q++) {
+    hitem[q] = tid + q * DEC_NT;
+    if (hitem[q] < (total_f >> 3)) load8_raw<SMOE_F32>(a.h, (size_t)hitem[q] * 8, hraw[q]);
+  }
+  // my units: a contiguous share [u_lo, u_hi) of my kind's list
+  const int my_w = routed_wave ? wave : wave - a.dn_rw, my_nw = routed_wave ? a.dn_rw : n_sw;
+  const int my_total = routed_wave ? n_ru : n_su;
+  const int u_lo = my_total * my_w / my_nw, u_hi = my_total * (my_w + 1) / my_nw;
+  const int my_ks = routed_wave ? a.ks_r : a.ks_s, my_inv = routed_wave ? a.inv_ks_r : a.inv_ks_s;
+  const int my_f = routed_wave ? a.f_r : a.f_s, my_hbase = routed_wave ? nsf : 0, my_pbase = routed_wave ? n_su : 0;
+  if (!routed_wave) {
+#pragma unroll
+    for (int j = 0; j < DEC_MAXU; j++)
+      if (u_lo + j < u_hi) {
+        const UnitRef u = unit_ref(u_lo + j, my_ks, my_inv);
+        issue(j, u, a.f_s, a.shared.dn, u.slot, 1, a.dn_sh_s);
+      }
+  }
+
+  // ---- routing record and h into LDS
+  if (tid < (int)(sizeof(RouteRec) / 4)) ((int*)&rec)[tid] = rec_word;
+  auto stage_h = [&](const Raw8& raw, int item) {
+    const int i0 = item * 8;
+    int voffs, f;                                      // which vector: shared experts first, then routed slots
+    if (i0 < nsf) { const int s = i0 / a.f_s; voffs = s * a.f_s; f = a.f_s; }
+    else { const int s = (i0 - nsf) / a.f_r; voffs = nsf + s * a.f_r; f = a.f_r; }
+    const int local = i0 - voffs;
+    float hv[8];
+    unpack8<SMOE_F32>(raw, hv);
+    stage_regs<ACT>(hv, f >> 5, local >> 5, (local >> 3) & 3, hvec + (size_t)voffs * StageTraits<ACT>::BYTES_PER_VAL,
+                    hcs + (voffs >> 5));
+  };
+#pragma unroll
+  for (int q = 0; q < 2; q++)
+    if (hitem[q] < (total_f >> 3)) stage_h(hraw[q], hitem[q]);
+  for (int item = tid + 2 * DEC_NT; item < (total_f >> 3); item += DEC_NT) {      // very wide layers only
+    Raw8 raw;
+    load8_raw<SMOE_F32>(a.h, (size_t)item * 8, raw);
+    stage_h(raw, item);
+  }
+  lds_barrier();
+
+  int pr[DEC_MAXU];
+  float wt[DEC_MAXU];
+  const float gamma = __int_as_float(uni(__float_as_int(rec.gamma)));
+#pragma unroll
+  for (int j = 0; j < DEC_MAXU; j++) {
+    pr[j] = 1; wt[j] = gamma;
+    if (routed_wave && u_lo + j < u_hi) {
+      const UnitRef u = unit_ref(u_lo + j, my_ks, my_inv);
+      pr[j] = uni(rec.prec[u.slot]);
+      wt[j] = __int_as_float(uni(__float_as_int(rec.w[u.slot])));
+      issue(j, u, a.f_r, a.routed.dn, uni(rec.sel[u.slot]), pr[j], a.dn_sh_r);
+    }
+  }
+  XR<ACT> x;
+  int cur = -1;
+#pragma unroll
+  for (int j = 0; j < DEC_MAXU; j++)
+    if (u_lo + j < u_hi) {
+      const UnitRef u = unit_ref(u_lo + j, my_ks, my_inv);
+      finish(j, u, my_f, my_hbase + u.slot * my_f, pr[j], wt[j], x, cur, (u_lo + j) / DEC_RPW, my_pbase + u_lo + j);
+    }
+  // layers with more than DEC_MAXU units per wave: the rest one at a time
+  for (int uu = u_lo + DEC_MAXU; uu < u_hi; uu++) {
+    const UnitRef u = unit_ref(uu, my_ks, my_inv);
+    int prec = 1;
+    float w1 = gamma;
+    if (routed_wave) {
+      prec = uni(rec.prec[u.slot]);
+      w1 = __int_as_float(uni(__float_as_int(rec.w[u.slot])));
+      issue(0, u, a.f_r, a.routed.dn, uni(rec.sel[u.slot]), prec, a.dn_sh_r);
+    } else {
+      issue(0, u, a.f_s, a.shared.dn, u.slot, 1, a.dn_sh_s);
+    }
+    finish(0, u, my_f, my_hbase + u.slot * my_f, prec, w1, x, cur, uu / DEC_RPW, my_pbase + uu);
+  }
+  __syncthreads();
+  if (tid < DEC_RPW) {
+    float acc = 0.0f;
+    for (int c = 0; c < n_ru / DEC_RPW; c++) acc += part[n_su + c * DEC_RPW + tid];   // routed slots in slot order
+    for (int c = 0; c < n_su / DEC_RPW; c++) acc += part[c * DEC_RPW + tid];          // then the shared experts
+    const int n = n0 + tid;
+    if (a.add_residual) acc += load_act<ACT>(a.x, n);
+    store_act<ACT>(a.y, n, acc);
   }
 }
 
 // ---------------------------------------------------------------------------------- host entry
-static int check_bank_pair(const smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, int k, int* d_model,
-                           int* total_f) {
+static int ilog2_exact(int v) {
+  int s = 0;
+  while ((1 << s) < v) s++;
+  return (1 << s) == v ? s : -1;
+}
+
+template <int ACT, int SCB>
+static int launch_decode_t(smoe_ctx* ctx, DecodeArgs& a, int total_f, int n_wg) {
+  const size_t vec_bytes = (size_t)total_f * StageTraits<ACT>::BYTES_PER_VAL;
+  const size_t n_units = (size_t)(a.n_shared * a.ks_s + a.k * a.ks_r) * DEC_RPW;
+  const size_t lds = vec_bytes + (size_t)(total_f / 32) * 8 + n_units * 4;
+  if (lds + sizeof(RouteRec) + 256 > 160u * 1024u) return SMOE_ESIZE;
+  if (lds > 64u * 1024u) {       // beyond the default per-work-group limit: ask for the larger carve-out
+    static size_t granted = 0;
+    if (lds > granted) {
+      if (hipFuncSetAttribute((const void*)down_kernel<ACT, SCB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+        (void)hipGetLastError();
+        return SMOE_ESIZE;
+      }
+      granted = lds;
+    }
+  }
+  gateup_kernel<ACT, SCB><<<n_wg, DEC_NT, 0, ctx->stream>>>(a);
+  down_kernel<ACT, SCB><<<a.d_model / DEC_RPW, DEC_NT, lds, ctx->stream>>>(a, (int)vec_bytes);
+  HIPCHK(ctx, hipGetLastError());
+  return SMOE_OK;
+}
+
+static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, int act_dtype, int k,
+                         DecodeArgs& a) {
   if (!routed && !shared) return SMOE_EINVAL;
   if (routed && routed->device != ctx->device) return SMOE_EINVAL;
   if (shared && shared->device != ctx->device) return SMOE_EINVAL;
@@ -250,45 +722,62 @@ static int check_bank_pair(const smoe_ctx* ctx, const smoe_bank* routed, const s
   if (routed && routed->desc.n_experts > SMOE_MAX_EXPERTS) return SMOE_ESHAPE;
   const int ns = shared ? shared->desc.n_experts : 0;
   if (k + ns > SMOE_MAX_SLOTS) return SMOE_ESHAPE;
-  *d_model = routed ? routed->desc.d_model : shared->desc.d_model;
-  if (*d_model > 2048) return SMOE_ENOTIMPL;       // gate/up keeps one 32-column chunk per lane
-  if (*d_model % 8) return SMOE_ESHAPE;
-  *total_f = (routed ? k * routed->desc.d_ff : 0) + (shared ? ns * shared->desc.d_ff : 0);
-  if ((size_t)*total_f * 4 + WS_H_OFF > SMOE_WORKSPACE_BYTES) return SMOE_ESIZE;
-  if ((size_t)*total_f * 4 + (size_t)*total_f / 8 > 160u * 1024u) return SMOE_ESIZE;   // LDS staging of h
-  return SMOE_OK;
-}
-
-static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x, int act_dtype,
-                         int k, SetupArgs& sa, int add_residual, void* y) {
-  int d_model = 0, total_f = 0;
-  int rc = check_bank_pair(ctx, routed, shared, k, &d_model, &total_f);
-  if (rc) return rc;
+  const int d_model = routed ? routed->desc.d_model : shared->desc.d_model;
+  if (d_model > 2048) return SMOE_ENOTIMPL;       // gate/up keeps one 32-column chunk per lane
+  if (d_model % DEC_RPW) return SMOE_ESHAPE;
+  a.f_r = routed ? routed->desc.d_ff : 0;
+  a.f_s = shared ? shared->desc.d_ff : 0;
+  const int total_f = k * a.f_r + ns * a.f_s;
+  if ((size_t)total_f * 4 + WS_H_OFF > SMOE_WORKSPACE_BYTES) return SMOE_ESIZE;
+  a.gu_sh_r = a.dn_sh_r = routed ? ilog2_exact(routed->desc.group / 32) : 0;
+  a.gu_sh_s = a.dn_sh_s = shared ? ilog2_exact(shared->desc.group / 32) : 0;
+  if (a.gu_sh_r < 0 || a.gu_sh_s < 0) return SMOE_ENOTIMPL;   // group must be 32 * 2^n for the decode kernels
+  if ((routed && !(routed->dev.gu.fits32 && routed->dev.dn.fits32)) || (shared && !(shared->dev.gu.fits32 && shared->dev.dn.fits32)))
+    return SMOE_ENOTIMPL;                                      // decode kernels address a bank section with 32-bit offsets
   HIPCHK(ctx, hipSetDevice(ctx->device));
-  SlotTable* tab = (SlotTable*)(ctx->ws + WS_TABLE_OFF);
-  float* h = (float*)(ctx->ws + WS_H_OFF);
-  if (routed) sa.routed = routed->dev;
-  if (shared) sa.shared = shared->dev;
-  sa.has_routed = routed != nullptr; sa.n_shared = shared ? shared->desc.n_experts : 0; sa.k = k;
-  sa.x = x; sa.tab = tab;
-  const int ppw = 2;
-  const int n_wg = (total_f + 4 * ppw - 1) / (4 * ppw);
-  const size_t lds = (size_t)total_f * 4 + (size_t)(total_f / 32) * 4;
-  if (act_dtype == SMOE_F32) {
-    static bool attr_done = false;
-    if (!attr_done) { HIPCHK(ctx, hipFuncSetAttribute((const void*)down_kernel<SMOE_F32>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_done = true; }
-    decode_setup_kernel<SMOE_F32><<<1, 256, 0, ctx->stream>>>(sa);
-    gateup_kernel<SMOE_F32><<<n_wg, 256, 0, ctx->stream>>>(tab, x, h, d_model, ppw);
-    down_kernel<SMOE_F32><<<d_model / 8, 256, lds, ctx->stream>>>(tab, h, x, y, d_model, add_residual);
-  } else {
-    static bool attr_done = false;
-    if (!attr_done) { HIPCHK(ctx, hipFuncSetAttribute((const void*)down_kernel<SMOE_BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_done = true; }
-    decode_setup_kernel<SMOE_BF16><<<1, 256, 0, ctx->stream>>>(sa);
-    gateup_kernel<SMOE_BF16><<<n_wg, 256, 0, ctx->stream>>>(tab, x, h, d_model, ppw);
-    down_kernel<SMOE_BF16><<<d_model / 8, 256, lds, ctx->stream>>>(tab, h, x, y, d_model, add_residual);
-  }
-  HIPCHK(ctx, hipGetLastError());
-  return SMOE_OK;
+  if (routed) a.routed = routed->dev;
+  if (shared) a.shared = shared->dev;
+  a.has_routed = routed != nullptr; a.n_shared = ns; a.k = k;
+  a.E = routed ? routed->desc.n_experts : 0;
+  a.rec = (RouteRec*)(ctx->ws + WS_REC_OFF);
+  a.h = (float*)(ctx->ws + WS_H_OFF);
+  a.d_model = d_model;
+  // gate/up split: n_wg work-groups, each takes ceil(f / n_wg) row pairs of every slot
+  int n_wg = (total_f + DEC_NW - 1) / DEC_NW;              // at least one row pair per wave
+  n_wg = n_wg < 1 ? 1 : (n_wg > ctx->n_cu ? ctx->n_cu : n_wg);
+  a.cap_r = a.f_r ? (a.f_r + n_wg - 1) / n_wg : 1;
+  a.cap_s = a.f_s ? (a.f_s + n_wg - 1) / n_wg : 1;
+  a.inv_cap_r = (65536 + a.cap_r - 1) / a.cap_r;
+  a.inv_cap_s = (65536 + a.cap_s - 1) / a.cap_s;
+  a.rot = n_wg / (k + ns);
+  if (ns * a.cap_s >= 8192 || k * a.cap_r >= 8192) return SMOE_ESIZE;
+  // split of the 16 waves between routed work items and shared-expert work items: the split with
+  // the smallest worst per-wave cost (a routed item is HIGH or LOW, 1.5 planes on average; shared
+  // experts are always HIGH, 2 planes); among equals the one that is lightest on the routed waves,
+  // which start later because they wait for the routing decision
+  auto split = [&](int n_routed, int n_shared_items) {
+    if (ns == 0 || n_shared_items == 0) return DEC_NW;
+    if (k == 0 || n_routed == 0) return 0;
+    int best = 1;
+    double best_max = 1e30, best_r = 1e30;
+    for (int rw = 1; rw < DEC_NW; rw++) {
+      const double cr = 1.5 * ((n_routed + rw - 1) / rw), cs = 2.0 * ((n_shared_items + (DEC_NW - rw) - 1) / (DEC_NW - rw));
+      const double mx = cr > cs ? cr : cs;
+      if (mx < best_max - 1e-9 || (mx < best_max + 1e-9 && cr < best_r - 1e-9)) { best = rw; best_max = mx; best_r = cr; }
+    }
+    return best;
+  };
+  a.gu_rw = split(k * a.cap_r, ns * a.cap_s);
+  // down split
+  a.ks_r = a.f_r ? (a.f_r / 32 + 63) / 64 : 1;
+  a.ks_s = a.f_s ? (a.f_s / 32 + 63) / 64 : 1;
+  a.inv_ks_r = (65536 + a.ks_r - 1) / a.ks_r;
+  a.inv_ks_s = (65536 + a.ks_s - 1) / a.ks_s;
+  a.dn_rw = split(k * a.ks_r * DEC_RPW, ns * a.ks_s * DEC_RPW);
+  const int scb = routed ? routed->dev.sc_bf16 : shared->dev.sc_bf16;
+  if (routed && shared && routed->dev.sc_bf16 != shared->dev.sc_bf16) return SMOE_ENOTIMPL;   // one scale dtype per layer
+  if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1>(ctx, a, total_f, n_wg) : launch_decode_t<SMOE_F32, 0>(ctx, a, total_f, n_wg);
+  return scb ? launch_decode_t<SMOE_BF16, 1>(ctx, a, total_f, n_wg) : launch_decode_t<SMOE_BF16, 0>(ctx, a, total_f, n_wg);
 }
 
 extern "C" int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
@@ -300,10 +789,10 @@ extern "C" int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smo
   if (routed && (!idx_dev || !w_dev)) return SMOE_EINVAL;
   if (!aligned16(x_dev) || !aligned16(y_dev) || !aligned16(idx_dev) || !aligned16(w_dev) || !aligned16(shared_gate_w_dev))
     return SMOE_EALIGN;
-  SetupArgs sa{};
-  sa.do_route = 0; sa.idx_in = idx_dev; sa.w_in = w_dev; sa.mask = slice_mask_dev; sa.tau = tau_head;
-  sa.shared_gate_w = shared_gate_w_dev; sa.prec_out = prec_out_dev;
-  return launch_decode(ctx, routed, shared, x_dev, act_dtype, k, sa, add_residual, y_dev);
+  DecodeArgs a{};
+  a.do_route = 0; a.idx_in = idx_dev; a.w_in = w_dev; a.mask = slice_mask_dev; a.tau = tau_head;
+  a.x = x_dev; a.shared_gate_w = shared_gate_w_dev; a.prec_out = prec_out_dev; a.y = y_dev; a.add_residual = add_residual;
+  return launch_decode(ctx, routed, shared, act_dtype, k, a);
 }
 
 extern "C" int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
@@ -318,13 +807,20 @@ extern "C" int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const s
   if (!aligned16(x_dev) || !aligned16(y_dev) || !aligned16(logits_dev) || !aligned16(w_router_dev) ||
       !aligned16(bias_dev) || !aligned16(shared_gate_w_dev))
     return SMOE_EALIGN;
-  SetupArgs sa{};
-  sa.do_route = 1;
-  int32_t* ws_idx = (int32_t*)(ctx->ws + WS_IDX_OFF);
-  float* ws_w = (float*)(ctx->ws + WS_IDX_OFF + 256);
-  sa.r = RouteArgs{routed->desc.n_experts, k, routed->desc.d_model, logits_dev, x_dev, w_router_dev, bias_dev,
-                   norm_topk, routed_scale, nullptr, ws_idx, ws_w};
-  sa.mask = slice_mask_dev; sa.tau = tau_head; sa.shared_gate_w = shared_gate_w_dev;
-  sa.idx_out = idx_out_dev; sa.w_out = w_out_dev; sa.prec_out = prec_out_dev;
-  return launch_decode(ctx, routed, shared, x_dev, act_dtype, k, sa, add_residual, y_dev);
+  const float* logits = logits_dev;
+  if (!logits) {
+    // router mat-vec into the workspace, then the gate/up prologue selects from those logits
+    float* zws = (float*)(ctx->ws + WS_IDX_OFF + 1024);
+    int32_t* ws_idx = (int32_t*)(ctx->ws + WS_IDX_OFF);
+    float* ws_w = (float*)(ctx->ws + WS_IDX_OFF + 256);
+    int rc = smoe_route(ctx, 1, routed->desc.n_experts, k, routed->desc.d_model, nullptr, x_dev, act_dtype, w_router_dev,
+                        bias_dev, norm_topk, routed_scale, zws, ws_idx, ws_w);
+    if (rc) return rc;
+    logits = zws;
+  }
+  DecodeArgs a{};
+  a.do_route = 1; a.logits = logits; a.bias = bias_dev; a.norm_topk = norm_topk; a.routed_scale = routed_scale;
+  a.mask = slice_mask_dev; a.tau = tau_head; a.x = x_dev; a.shared_gate_w = shared_gate_w_dev;
+  a.idx_out = idx_out_dev; a.w_out = w_out_dev; a.prec_out = prec_out_dev; a.y = y_dev; a.add_residual = add_residual;
+  return launch_decode(ctx, routed, shared, act_dtype, k, a);
 }
