@@ -65,12 +65,18 @@ typedef struct {
 
 /* ---- context ---------------------------------------------------------------------------- */
 /* Creates a context bound to `device` and to `hip_stream` (a hipStream_t, NULL = default
- * stream).  Allocates a fixed 4 MiB device workspace (slot table, SwiGLU intermediates); this
+ * stream).  Allocates a fixed 4 MiB device workspace (routing record, SwiGLU intermediates); this
  * is the only device allocation the library ever makes.  smoe_ctx_destroy frees it. */
 int smoe_ctx_create(int device, void* hip_stream, smoe_ctx** out);
 int smoe_ctx_destroy(smoe_ctx* ctx);
 const char* smoe_strerror(int status);
 int smoe_last_hip_error(const smoe_ctx* ctx); /* hipError_t of the last failing HIP call, else 0 */
+/* Measurement aid, no part of the method.  While enabled, smoe_expert_ffn / smoe_decode_layer record
+ * a start and a stop HIP event with each of their two kernel dispatches (gate/up, down) on the ctx stream.
+ * smoe_ctx_timing_read synchronises the stream, returns the summed durations in microseconds and the
+ * number of calls recorded since the last read, and releases the events. */
+int smoe_ctx_timing(smoe_ctx* ctx, int enable);
+int smoe_ctx_timing_read(smoe_ctx* ctx, double* gateup_us, double* down_us, int* n_calls);
 
 /* ---- quantize / slice (Section 4.2; Table 1 note 1) ------------------------------------- */
 /* Bytes of device memory a bank's store needs. */

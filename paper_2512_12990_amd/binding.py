@@ -36,7 +36,8 @@ class CacheStats(C.Structure):
 _lib = None
 
 EXPORTS = [
-    "smoe_ctx_create", "smoe_ctx_destroy", "smoe_strerror", "smoe_last_hip_error",
+    "smoe_ctx_create", "smoe_ctx_destroy", "smoe_strerror", "smoe_last_hip_error", "smoe_ctx_timing",
+    "smoe_ctx_timing_read",
     "smoe_bank_bytes", "smoe_bank_create", "smoe_bank_destroy", "smoe_quantize_slice", "smoe_export_codes",
     "smoe_route", "smoe_expert_ffn", "smoe_decode_layer",
     "smoe_prefill_bytes", "smoe_prefill_histogram", "smoe_topn_slices",
@@ -81,6 +82,15 @@ class Ctx:
         self._stream = s
         self.h = C.c_void_p()
         _chk(lib().smoe_ctx_create(C.c_int(device), C.c_void_p(s.cuda_stream), C.byref(self.h)), "smoe_ctx_create")
+
+    def timing(self, enable: bool):
+        _chk(lib().smoe_ctx_timing(self.h, C.c_int(int(enable))), "smoe_ctx_timing")
+
+    def timing_read(self):
+        """(gateup_us_sum, down_us_sum, n_calls) since the last read; synchronises."""
+        g, d, n = C.c_double(), C.c_double(), C.c_int()
+        _chk(lib().smoe_ctx_timing_read(self.h, C.byref(g), C.byref(d), C.byref(n)), "smoe_ctx_timing_read", self.h)
+        return g.value, d.value, n.value
 
     def close(self):
         if self.h:

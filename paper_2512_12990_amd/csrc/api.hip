@@ -22,7 +22,7 @@ extern "C" int smoe_ctx_create(int device, void* hip_stream, smoe_ctx** out) {
   *out = nullptr;
   smoe_ctx* c = new (std::nothrow) smoe_ctx();
   if (!c) return SMOE_EINVAL;
-  c->device = device; c->stream = (hipStream_t)hip_stream; c->ws = nullptr; c->last_hip = 0; c->n_cu = 256;
+  c->device = device; c->stream = (hipStream_t)hip_stream; c->ws = nullptr; c->last_hip = 0; c->n_cu = 256; c->timing = 0; c->timing_events = nullptr;
   hipError_t e = hipSetDevice(device);
   if (e == hipSuccess) e = hipMalloc((void**)&c->ws, SMOE_WORKSPACE_BYTES);
   if (e == hipSuccess) {
@@ -38,11 +38,42 @@ extern "C" int smoe_ctx_create(int device, void* hip_stream, smoe_ctx** out) {
 extern "C" int smoe_ctx_destroy(smoe_ctx* ctx) {
   if (!ctx) return SMOE_EINVAL;
   if (ctx->ws) { (void)hipSetDevice(ctx->device); (void)hipFree(ctx->ws); }
+  if (ctx->timing_events) {
+    std::vector<hipEvent_t>* ev = (std::vector<hipEvent_t>*)ctx->timing_events;
+    for (hipEvent_t e : *ev) (void)hipEventDestroy(e);
+    delete ev;
+  }
   delete ctx;
   return SMOE_OK;
 }
 
 extern "C" int smoe_last_hip_error(const smoe_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+extern "C" int smoe_ctx_timing(smoe_ctx* ctx, int enable) {
+  if (!ctx) return SMOE_EINVAL;
+  if (!ctx->timing_events) ctx->timing_events = new (std::nothrow) std::vector<hipEvent_t>();
+  if (!ctx->timing_events) return SMOE_EINVAL;
+  ctx->timing = enable ? 1 : 0;
+  return SMOE_OK;
+}
+
+extern "C" int smoe_ctx_timing_read(smoe_ctx* ctx, double* gateup_us, double* down_us, int* n_calls) {
+  if (!ctx || !gateup_us || !down_us || !n_calls) return SMOE_EINVAL;
+  *gateup_us = *down_us = 0.0; *n_calls = 0;
+  if (!ctx->timing_events) return SMOE_OK;
+  std::vector<hipEvent_t>* ev = (std::vector<hipEvent_t>*)ctx->timing_events;
+  HIPCHK(ctx, hipSetDevice(ctx->device));
+  HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+  for (size_t i = 0; i + 3 < ev->size(); i += 4) {
+    float a = 0.0f, b = 0.0f;
+    HIPCHK(ctx, hipEventElapsedTime(&a, (*ev)[i], (*ev)[i + 1]));
+    HIPCHK(ctx, hipEventElapsedTime(&b, (*ev)[i + 2], (*ev)[i + 3]));
+    *gateup_us += 1e3 * a; *down_us += 1e3 * b; ++*n_calls;
+  }
+  for (hipEvent_t e : *ev) (void)hipEventDestroy(e);
+  ev->clear();
+  return SMOE_OK;
+}
 
 // ---- bank layout ------------------------------------------------------------------------------
 static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }

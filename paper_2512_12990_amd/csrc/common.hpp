@@ -34,6 +34,9 @@ struct smoe_ctx {
   uint8_t* ws;          // SMOE_WORKSPACE_BYTES of device memory
   int last_hip;
   int n_cu;
+  // measurement aid (smoe_ctx_timing): events around the two decode launches of every call
+  int timing;
+  void* timing_events;   // std::vector<hipEvent_t>*, four events per decode call
 };
 
 struct smoe_bank {

@@ -21,6 +21,8 @@
 // with A_p = sum nibble_p * xint over the lane's chunk, X = sum xint, sx the chunk scale.
 // fp32 activations take a plain fp32 path (byte -> float conversions and FMAs).
 #include "route_device.hpp"
+#include <hip/hip_ext.h>
+#include <vector>
 
 #define DEC_NT 1024                 // threads per work-group
 #define DEC_NW (DEC_NT / 64)
@@ -705,8 +707,18 @@ static int launch_decode_t(smoe_ctx* ctx, DecodeArgs& a, int total_f, int n_wg) 
       granted = lds;
     }
   }
-  gateup_kernel<ACT, SCB><<<n_wg, DEC_NT, 0, ctx->stream>>>(a);
-  down_kernel<ACT, SCB><<<a.d_model / DEC_RPW, DEC_NT, lds, ctx->stream>>>(a, (int)vec_bytes);
+  std::vector<hipEvent_t>* evs = (ctx->timing && ctx->timing_events) ? (std::vector<hipEvent_t>*)ctx->timing_events : nullptr;
+  const dim3 g1(n_wg), g2(a.d_model / DEC_RPW), blk(DEC_NT);
+  if (evs) {
+    // measurement aid: the dispatches themselves carry start/stop events (no extra marker packets)
+    hipEvent_t ev[4];
+    for (int i = 0; i < 4; i++) { HIPCHK(ctx, hipEventCreate(&ev[i])); evs->push_back(ev[i]); }
+    hipExtLaunchKernelGGL((gateup_kernel<ACT, SCB>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, a);
+    hipExtLaunchKernelGGL((down_kernel<ACT, SCB>), g2, blk, (unsigned)lds, ctx->stream, ev[2], ev[3], 0, a, (int)vec_bytes);
+  } else {
+    gateup_kernel<ACT, SCB><<<g1, blk, 0, ctx->stream>>>(a);
+    down_kernel<ACT, SCB><<<g2, blk, lds, ctx->stream>>>(a, (int)vec_bytes);
+  }
   HIPCHK(ctx, hipGetLastError());
   return SMOE_OK;
 }
