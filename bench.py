@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=4)
+    ap.add_argument("--workload", choices=["decode", "prefill"], default="decode",
+                    help="decode (default, the headline metric) or the prefill grouped GEMM of one Qwen-shaped layer")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (the decode layer of one token has no second-GPU path); "
@@ -52,6 +54,8 @@ def main():
         from paper_2512_12990_amd import build as _b
         _b.build()
     assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU fallback)"
+    if args.workload == "prefill":
+        return prefill_bench(args)
     wl = synth.DSV2_LAYER
     shp = wl.layer
     dev = "cuda:0"
@@ -153,6 +157,48 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_steps, idx.cpu().numpy(), prec_np)
     print(json.dumps(out))
+
+
+def prefill_bench(args):
+    """One Qwen1.5-MoE-shaped layer, 2048 tokens, 60 experts top-4, all high-bit: route + histogram +
+    grouped expert GEMMs on MFMA + combine.  A step is one such layer pass."""
+    import torch
+    from paper_2512_12990_amd import binding as B, synth
+    wl = synth.QWEN_PREFILL
+    shp = wl.layer
+    T, dev = wl.prefill_tokens, "cuda:0"
+    ctx = B.Ctx(0)
+    routed = B.Bank(ctx, shp.n_experts, shp.d_model, shp.d_ff, shp.group, "bf16", "bf16")
+    for e in range(shp.n_experts):
+        wg, wu, wd = synth.expert_weights(wl.seed, 0, e, shp.d_model, shp.d_ff, "bf16", dev)
+        B.smoe_quantize_slice(ctx, routed, e, wg[None], wu[None], wd[None])
+    x = synth.activations(wl.seed, T, shp.d_model, "bf16").to(dev)
+    wr = synth.router_weight(wl.seed, 0, shp.n_experts, shp.d_model).to(dev)
+    scratch = torch.empty(B.smoe_prefill_bytes(T, shp.n_experts, shp.top_k, shp.d_model, shp.d_ff), dtype=torch.uint8, device=dev)
+    steps = min(args.steps, 50)
+    for _ in range(3):
+        B.smoe_prefill_histogram(ctx, routed, None, x, shp.top_k, w_router=wr, add_residual=True, scratch=scratch)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(steps):
+        B.smoe_prefill_histogram(ctx, routed, None, x, shp.top_k, w_router=wr, add_residual=True, scratch=scratch)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / steps
+    flops = 2.0 * T * shp.top_k * 3 * shp.d_model * shp.d_ff
+    wbytes = shp.n_experts * sum(slot_bytes(shp.d_model, shp.d_ff, shp.group, 1))
+    print(json.dumps({
+        "metric": "prefill MoE-layer ms (2048 tokens, grouped expert GEMM + histogram)", "value": ms, "unit": "ms/layer",
+        "n_gpus": 1, "steps": steps, "warmup": 3, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 MFMA, fp32 accumulate, u4+u4 sliced weights", "data": "synthetic",
+        "config": {"workload": "Qwen1.5-MoE-shaped prefill layer (BASELINE configs[4], one layer)", "tokens": T,
+                   "n_experts": shp.n_experts, "top_k": shp.top_k, "d_model": shp.d_model, "d_ff": shp.d_ff},
+        "tokens_per_s": T / (ms * 1e-3),
+        "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": flops / (ms * 1e-3) / 1e12 / 2500.0, "flops_per_step": flops,
+                     "weight_bytes_per_step": wbytes, "weight_gbps": wbytes / (ms * 1e-3) / 1e9, "traffic": None,
+                     "kernel": "whole layer pass (route_hist, scan, permute, grouped_gemm<0>, grouped_gemm<1>, combine)"}}))
 
 
 def cpu_baseline(wl, n_steps, idx_np, prec_np):

@@ -295,7 +295,7 @@ __device__ __forceinline__ float unorderable(uint32_t o) {
   return __uint_as_float((o & 0x80000000u) ? (o ^ 0x80000000u) : ~o);
 }
 
-// Same decision rule as route_token (route_device.hpp) -- k largest biased scores, ties to the
+// Same decision rule as select_topk_wave (route_device.hpp) -- k largest biased scores, ties to the
 // lower expert index, weights from the softmax of the unbiased logits -- executed by a single
 // wave with cross-lane DPP reductions only.  Lane e (+64j) holds logit, bias and slice mask of
 // expert e; the loads are issued by route_load so that they overlap other work.
@@ -332,7 +332,7 @@ __device__ void route_compute(const DecodeArgs& a, int lane, RouteRegs& rr, Rout
     const float m = unorderable(wave_umax(zmax_o));
     float den = 0.0f;
 #pragma unroll
-    for (int j = 0; j < NJ; j++) { p[j] = (lane + 64 * j < E) ? expf(rr.z[j] - m) : 0.0f; den += p[j]; }
+    for (int j = 0; j < NJ; j++) { p[j] = (lane + 64 * j < E) ? __expf(rr.z[j] - m) : 0.0f; den += p[j]; }
     den = wave_sum_all(den);
     float psum = 0.0f, myp = 0.0f;
     for (int r = 0; r < k; r++) {
@@ -822,11 +822,9 @@ extern "C" int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const s
   const float* logits = logits_dev;
   if (!logits) {
     // router mat-vec into the workspace, then the gate/up prologue selects from those logits
-    float* zws = (float*)(ctx->ws + WS_IDX_OFF + 1024);
-    int32_t* ws_idx = (int32_t*)(ctx->ws + WS_IDX_OFF);
-    float* ws_w = (float*)(ctx->ws + WS_IDX_OFF + 256);
-    int rc = smoe_route(ctx, 1, routed->desc.n_experts, k, routed->desc.d_model, nullptr, x_dev, act_dtype, w_router_dev,
-                        bias_dev, norm_topk, routed_scale, zws, ws_idx, ws_w);
+    float* zws = (float*)(ctx->ws + WS_IDX_OFF);
+    HIPCHK(ctx, hipSetDevice(ctx->device));
+    int rc = smoe_launch_router_logits(ctx, routed->desc.n_experts, routed->desc.d_model, x_dev, act_dtype, w_router_dev, zws);
     if (rc) return rc;
     logits = zws;
   }

@@ -1,5 +1,5 @@
 // Prefill (paper Section 4.3: token-parallel, every expert high-bit, per-expert access counts):
-//   route_hist   one work-group per token: cache-unaware top-k + integer-atomic histogram
+//   route        eight tokens per work-group: router mat-vec, top-k, integer-atomic histogram (route.hip)
 //   scan         exclusive scan of the histogram -> row offset of every expert
 //   permute      one work-group per expert: stable list of its (token, slot) pairs
 //   gemm<0>      grouped GEMM  H = silu(X Wg^T) * (X Wu^T)     (bf16 MFMA, fp32 accumulate)
@@ -23,13 +23,6 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 __global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
-}
-
-template <int ACT>
-__global__ __launch_bounds__(256) void route_hist_kernel(RouteArgs a, uint32_t* hist) {
-  __shared__ RouteShared sh;
-  route_token<ACT>(a, blockIdx.x, sh);
-  if ((int)threadIdx.x < a.k) atomicAdd(&hist[sh.sel[threadIdx.x]], 1u);
 }
 
 __global__ void scan_kernel(const uint32_t* hist, int E, int32_t* offsets) {
@@ -297,7 +290,7 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
 
   fill_u32_kernel<<<(E + 255) / 256, 256, 0, st>>>(hist_dev, E, 0u);
   RouteArgs ra{E, k, d, logits_dev, x_dev, w_router_dev, nullptr, norm_topk, routed_scale, nullptr, idx_dev, w_dev};
-  route_hist_kernel<SMOE_BF16><<<T, 256, 0, st>>>(ra, hist_dev);
+  { const int rc = smoe_launch_route(ctx, ra, T, SMOE_BF16, hist_dev); if (rc) return rc; }
   scan_kernel<<<1, 64, 0, st>>>(hist_dev, E, offsets);
   permute_kernel<<<E, 256, 0, st>>>(idx_dev, T * k, offsets, rows, pos);
 

@@ -1,10 +1,46 @@
-// smoe_route: cache-aware top-k routing for T tokens (paper Section 2.1), one work-group per token.
+// smoe_route: cache-aware top-k routing for T tokens (paper Section 2.1), and the router mat-vec
+// alone for the one-token decode path.
 #include "route_device.hpp"
 
+template <int ACT, int NT>
+__global__ __launch_bounds__(RT_THREADS) void route_batch_kernel(RouteArgs a, int T, uint32_t* hist) {
+  extern __shared__ __align__(16) uint8_t rdyn[];
+  route_tokens_block<ACT, NT>(a, T, hist, rdyn);
+}
+
+// z[e] = w_router[e, :] . x for one token: one wave per expert, so the mat-vec of a single token is
+// spread over E/4 work-groups instead of one.
 template <int ACT>
-__global__ __launch_bounds__(256) void route_kernel(RouteArgs a) {
-  __shared__ RouteShared sh;
-  route_token<ACT>(a, blockIdx.x, sh);
+__global__ __launch_bounds__(256) void router_logits_kernel(const float* __restrict__ w_router, const void* __restrict__ x,
+                                                            int E, int d, float* __restrict__ z) {
+  const int lane = threadIdx.x & 63, e = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (e >= E) return;
+  float p[1];
+  router_row_dots<1>(w_router + (size_t)e * d, d, lane, [&](int, int i) { return load_act<ACT>(x, i); }, p);
+  if (lane == 0) z[e] = p[0];
+}
+
+int smoe_launch_router_logits(smoe_ctx* ctx, int E, int d, const void* x, int act_dtype, const float* w_router, float* z) {
+  const int n_wg = (E + 3) / 4;
+  if (act_dtype == SMOE_F32) router_logits_kernel<SMOE_F32><<<n_wg, 256, 0, ctx->stream>>>(w_router, x, E, d, z);
+  else router_logits_kernel<SMOE_BF16><<<n_wg, 256, 0, ctx->stream>>>(w_router, x, E, d, z);
+  HIPCHK(ctx, hipGetLastError());
+  return SMOE_OK;
+}
+
+int smoe_launch_route(smoe_ctx* ctx, const RouteArgs& a, int T, int act_dtype, uint32_t* hist) {
+  const bool given = a.logits != nullptr;
+  if (act_dtype == SMOE_BF16) {
+    const size_t lds = RouteLds<SMOE_BF16, 8>::bytes(a.E, a.d_model, given);
+    if (lds > 64u * 1024u) return SMOE_ESIZE;
+    route_batch_kernel<SMOE_BF16, 8><<<(T + 7) / 8, RT_THREADS, lds, ctx->stream>>>(a, T, hist);
+  } else {
+    const size_t lds = RouteLds<SMOE_F32, 4>::bytes(a.E, a.d_model, given);
+    if (lds > 64u * 1024u) return SMOE_ESIZE;
+    route_batch_kernel<SMOE_F32, 4><<<(T + 3) / 4, RT_THREADS, lds, ctx->stream>>>(a, T, hist);
+  }
+  HIPCHK(ctx, hipGetLastError());
+  return SMOE_OK;
 }
 
 extern "C" int smoe_route(smoe_ctx* ctx, int T, int E, int k, int d_model, const float* logits_dev,
@@ -22,8 +58,5 @@ extern "C" int smoe_route(smoe_ctx* ctx, int T, int E, int k, int d_model, const
   HIPCHK(ctx, hipSetDevice(ctx->device));
   RouteArgs a{E, k, d_model, logits_dev, x_dev, w_router_dev, bias_dev, norm_topk, routed_scale,
               logits_out_dev, idx_dev, w_dev};
-  if (act_dtype == SMOE_F32) route_kernel<SMOE_F32><<<T, 256, 0, ctx->stream>>>(a);
-  else route_kernel<SMOE_BF16><<<T, 256, 0, ctx->stream>>>(a);
-  HIPCHK(ctx, hipGetLastError());
-  return SMOE_OK;
+  return smoe_launch_route(ctx, a, T, act_dtype, nullptr);
 }

@@ -1,5 +1,5 @@
-// Cache-aware top-k routing of one token by one 256-thread work-group (paper Section 2.1:
-// experts whose slices are resident get their gating score boosted before selection).
+// Cache-aware top-k routing (paper Section 2.1: experts whose slices are resident get their
+// gating score boosted before selection): device routines shared by the routing entry points.
 #pragma once
 #include "common.hpp"
 
@@ -14,13 +14,6 @@ struct RouteArgs {
   float* logits_out;       // [T, E] or null
   int32_t* idx;            // [T, k]
   float* w;                // [T, k]
-};
-
-struct RouteShared {
-  float z[SMOE_MAX_EXPERTS];
-  unsigned long long key[SMOE_MAX_EXPERTS];
-  int sel[SMOE_MAX_TOPK];
-  float wsel[SMOE_MAX_TOPK];
 };
 
 // Monotone map float -> uint32 (a < b  <=>  map(a) < map(b)); -0 is first folded onto +0 so
@@ -40,59 +33,130 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
   return v;
 }
 
-// All 256 threads of the block call this.  On return sh.sel[0..k) and sh.wsel[0..k) hold the
-// decision (also written to a.idx / a.w for token t) and the block is synchronised.
-template <int ACT>
-__device__ void route_token(const RouteArgs& a, int t, RouteShared& sh) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// Top-k selection of one token by ONE wave.  z[0..E) are the token's logits (LDS), key[0..E) is
+// scratch (LDS).  Writes a.idx / a.w for token t and leaves the decision in sel[] / wsel[] (LDS).
+// Rule: k largest z + bias from the highest down, equal scores to the lower expert index; weights
+// = softmax of the unbiased logits at the selected experts (optionally renormalised), * scale.
+__device__ __forceinline__ void select_topk_wave(const RouteArgs& a, int t, const float* z, unsigned long long* key,
+                                                 int* sel, float* wsel, int lane) {
   const int E = a.E;
-  if (a.logits) {
-    if (tid < E) sh.z[tid] = a.logits[(size_t)t * E + tid];
-  } else {
-    for (int e = wave; e < E; e += 4) {
-      float p = 0.0f;
-      for (int i = lane; i < a.d_model; i += 64)
-        p = fmaf(a.w_router[(size_t)e * a.d_model + i], load_act<ACT>(a.x, (size_t)t * a.d_model + i), p);
-      p = wave_sum(p);
-      if (lane == 0) sh.z[e] = p;
-    }
+  for (int e = lane; e < E; e += 64) {
+    const float score = z[e] + (a.bias ? a.bias[e] : 0.0f);          // one fp32 add
+    key[e] = ((unsigned long long)orderable(score) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e);
   }
-  __syncthreads();
-  if (tid < E) {
-    const float z = sh.z[tid];
-    if (a.logits_out) a.logits_out[(size_t)t * E + tid] = z;
-    const float score = z + (a.bias ? a.bias[tid] : 0.0f);          // one fp32 add
-    // larger score first; equal scores -> lower expert index
-    sh.key[tid] = ((unsigned long long)orderable(score) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)tid);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  float m = -INFINITY;
+  for (int e = lane; e < E; e += 64) m = fmaxf(m, z[e]);
+  for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
+  float den = 0.0f;
+  for (int e = lane; e < E; e += 64) den += expf(z[e] - m);
+  den = wave_sum(den);
+  float wsum = 0.0f;
+  for (int j = 0; j < a.k; j++) {
+    unsigned long long best = 0;
+    for (int e = lane; e < E; e += 64) best = key[e] > best ? key[e] : best;
+    best = wave_max_u64(best);
+    const int e_star = (int)(0xFFFFFFFFu - (uint32_t)best);
+    const float wj = expf(z[e_star] - m) / den;
+    wsum += wj;
+    if (lane == 0) { sel[j] = e_star; wsel[j] = wj; key[e_star] = 0; }
+    // the key write must be visible to the whole wave before the next scan
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
   }
-  __syncthreads();
-  if (wave == 0) {
-    float m = -INFINITY;
-    for (int e = lane; e < E; e += 64) m = fmaxf(m, sh.z[e]);
-    for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s));
-    float den = 0.0f;
-    for (int e = lane; e < E; e += 64) den += expf(sh.z[e] - m);
-    den = wave_sum(den);
-    float wsum = 0.0f;
-    for (int j = 0; j < a.k; j++) {
-      unsigned long long best = 0;
-      for (int e = lane; e < E; e += 64) best = sh.key[e] > best ? sh.key[e] : best;
-      best = wave_max_u64(best);
-      const int e_star = (int)(0xFFFFFFFFu - (uint32_t)best);
-      const float wj = expf(sh.z[e_star] - m) / den;
-      wsum += wj;
-      if (lane == 0) { sh.sel[j] = e_star; sh.wsel[j] = wj; sh.key[e_star] = 0; }
-      // the key write must be visible to the whole wave before the next scan
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-      __builtin_amdgcn_wave_barrier();
-    }
-    const float mul = (a.norm_topk ? 1.0f / wsum : 1.0f) * a.routed_scale;
-    if (lane < a.k) {
-      const float wj = sh.wsel[lane] * mul;
-      sh.wsel[lane] = wj;
-      a.idx[(size_t)t * a.k + lane] = sh.sel[lane];
-      a.w[(size_t)t * a.k + lane] = wj;
-    }
+  const float mul = (a.norm_topk ? 1.0f / wsum : 1.0f) * a.routed_scale;
+  if (lane < a.k) {
+    const float wj = wsel[lane] * mul;
+    wsel[lane] = wj;
+    a.idx[(size_t)t * a.k + lane] = sel[lane];
+    a.w[(size_t)t * a.k + lane] = wj;
   }
-  __syncthreads();
 }
+
+// Dot products of one router row with NT activation vectors by one wave.  Lane l sums columns
+// l, l+64, l+128, ... in that order by fused multiply-add, then the wave sum: every kernel that
+// produces router logits uses this routine, so logits are bit-identical between entry points.
+// xget(q, i) returns activation i of vector q.  The results are valid in every lane.
+template <int NT, class XF>
+__device__ __forceinline__ void router_row_dots(const float* __restrict__ wrow, int d, int lane, XF xget, float* p) {
+#pragma unroll
+  for (int q = 0; q < NT; q++) p[q] = 0.0f;
+  int i0 = 0;
+  for (; i0 + 512 <= d; i0 += 512) {          // eight loads in flight per lane
+    float w[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) w[u] = wrow[i0 + u * 64 + lane];
+#pragma unroll
+    for (int u = 0; u < 8; u++)
+#pragma unroll
+      for (int q = 0; q < NT; q++) p[q] = fmaf(w[u], xget(q, i0 + u * 64 + lane), p[q]);
+  }
+  for (int i = i0 + lane; i < d; i += 64) {
+    const float w = wrow[i];
+#pragma unroll
+    for (int q = 0; q < NT; q++) p[q] = fmaf(w, xget(q, i), p[q]);
+  }
+#pragma unroll
+  for (int q = 0; q < NT; q++) p[q] = wave_sum(p[q]);
+}
+
+// Routes NT tokens per work-group of RT_NW waves: every router row is read once per group, each wave
+// then selects for its share of the tokens; hist (may be null) counts selections by integer atomics.
+// Dynamic LDS: NT*E floats, RT_NW*E 64-bit keys, RT_NW*16 ints, RT_NW*16 floats, then (without given logits)
+// NT*d activations in their storage dtype.
+#define RT_NW 16
+#define RT_THREADS (RT_NW * 64)
+template <int ACT, int NT>
+__device__ __forceinline__ void route_tokens_block(const RouteArgs& a, int T, uint32_t* hist, uint8_t* dyn) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int E = a.E, d = a.d_model;
+  const int t0 = blockIdx.x * NT, nt = min(NT, T - t0);
+  float* zt = (float*)dyn;                                            // [NT][E]
+  unsigned long long* key = (unsigned long long*)(zt + NT * E);      // [RT_NW waves][E]
+  int* sel = (int*)(key + RT_NW * E);                                 // [RT_NW][16]
+  float* wsel = (float*)(sel + RT_NW * SMOE_MAX_TOPK);                // [RT_NW][16]
+  if (a.logits) {
+    for (int i = tid; i < nt * E; i += RT_THREADS) zt[i] = a.logits[(size_t)t0 * E + i];
+  } else {
+    if (ACT == SMOE_BF16) {
+      uint16_t* xs = (uint16_t*)(wsel + RT_NW * SMOE_MAX_TOPK);
+      for (int i = tid; i < NT * d; i += RT_THREADS) xs[i] = i < nt * d ? ((const uint16_t*)a.x)[(size_t)t0 * d + i] : (uint16_t)0;
+      __syncthreads();
+      for (int e = wave; e < E; e += RT_NW) {
+        float p[NT];
+        router_row_dots<NT>(a.w_router + (size_t)e * d, d, lane, [&](int q, int i) { return bf16_bits_to_f32(xs[q * d + i]); }, p);
+        if (lane == 0)
+#pragma unroll
+          for (int q = 0; q < NT; q++) zt[q * E + e] = p[q];
+      }
+    } else {
+      float* xs = wsel + RT_NW * SMOE_MAX_TOPK;
+      for (int i = tid; i < NT * d; i += RT_THREADS) xs[i] = i < nt * d ? ((const float*)a.x)[(size_t)t0 * d + i] : 0.0f;
+      __syncthreads();
+      for (int e = wave; e < E; e += RT_NW) {
+        float p[NT];
+        router_row_dots<NT>(a.w_router + (size_t)e * d, d, lane, [&](int q, int i) { return xs[q * d + i]; }, p);
+        if (lane == 0)
+#pragma unroll
+          for (int q = 0; q < NT; q++) zt[q * E + e] = p[q];
+      }
+    }
+  }
+  __syncthreads();
+  if (a.logits_out)
+    for (int i = tid; i < nt * E; i += RT_THREADS) a.logits_out[(size_t)t0 * E + i] = zt[i];
+  for (int q = wave; q < nt; q += RT_NW) {
+    select_topk_wave(a, t0 + q, zt + q * E, key + wave * E, sel + wave * SMOE_MAX_TOPK, wsel + wave * SMOE_MAX_TOPK, lane);
+    if (hist && lane < a.k) atomicAdd(&hist[sel[wave * SMOE_MAX_TOPK + lane]], 1u);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+template <int ACT, int NT> struct RouteLds {
+  static size_t bytes(int E, int d, bool given_logits) {
+    return (size_t)NT * E * 4 + (size_t)RT_NW * E * 8 + RT_NW * SMOE_MAX_TOPK * 8 +
+           (given_logits ? 0 : (size_t)NT * d * (ACT == SMOE_BF16 ? 2 : 4));
+  }
+};
