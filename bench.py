@@ -136,7 +136,7 @@ def main():
         "metric": "decode MoE-layer us/token (+ achieved HBM GB/s as a fraction of MI355X peak)",
         "value": ms_per_step * 1e3, "unit": "us/token", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u4+u4 bit-sliced weights, bf16 activations/scales rewritten as 14-bit integer digits, int32/fp32 accumulate",
+        "dtype": "u4+u4 bit-sliced weights, bf16 activations rewritten per 32-chunk as 3 balanced hex digits, signed 4-bit dot products, int32/fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": "DeepSeek-V2-Lite-shaped MoE layer decode, 1 token/step (BASELINE configs[1])",
                    "d_model": shp.d_model, "n_experts": shp.n_experts, "d_ff": shp.d_ff, "top_k": shp.top_k,

@@ -18,11 +18,9 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function"]
 
 def _compile(src: str, objdir: str) -> str:
     obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC, "-c", os.path.join(CSRC, src), "-o", obj] + COMMON
     if src.endswith(".hip"):
-        cmd += DEVICE_FLAGS
+        cmd = [HIPCC, "-c", os.path.join(CSRC, src), "-o", obj] + COMMON + DEVICE_FLAGS
     else:
-        cmd += ["-x", "c++"]
         cmd = [HIPCC, "-x", "c++", "-c", os.path.join(CSRC, src), "-o", obj] + COMMON
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

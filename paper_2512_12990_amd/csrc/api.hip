@@ -106,7 +106,7 @@ static size_t layout(const smoe_bank_desc* d, BankDev* b, MatOff* ogu, MatOff* o
     m[i]->zp_stride = up16((size_t)m[i]->N * m[i]->ng);
     m[i]->sc_stride = up16((size_t)m[i]->N * m[i]->ng * ssz);
     m[i]->ps32 = (unsigned)m[i]->plane_stride; m[i]->zs32 = (unsigned)m[i]->zp_stride; m[i]->ss32 = (unsigned)m[i]->sc_stride;
-    m[i]->fits32 = (E * m[i]->plane_stride < 0xFFFF0000ull) ? 1u : 0u;
+    m[i]->fits32 = (E * m[i]->plane_stride < 0x7FFF0000ull) ? 1u : 0u;
   }
   // MSB planes of both families first, then LSB planes, then metadata: a low-bit read never
   // touches the LSB region.
@@ -180,7 +180,7 @@ extern "C" int smoe_export_codes(smoe_ctx* ctx, const smoe_bank* bank, int exper
     // gate rows are the even rows of the interleaved family, up rows the odd ones
     const size_t sr = matrix == 2 ? (size_t)r : (size_t)2 * r + (matrix == 1);
     for (int kk = 0; kk < K; kk++) {
-      const uint8_t bm = pm[sr * row_b + kk / 2], bl = pl[sr * row_b + kk / 2];
+      const uint8_t bm = pm[sr * row_b + kk / 2] ^ 0x88, bl = pl[sr * row_b + kk / 2] ^ 0x88;   // stored as n ^ 8
       const uint8_t mv = (kk & 1) ? (bm >> 4) : (bm & 15), lv = (kk & 1) ? (bl >> 4) : (bl & 15);
       const size_t o = (size_t)r * K + kk;
       if (msb_host) msb_host[o] = mv;

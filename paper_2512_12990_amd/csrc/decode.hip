@@ -10,15 +10,17 @@
 //   down    y = sum_slots weight * Wd h (+ x): a work-group owns 8 output rows, its 16 waves split
 //           the (slot, k-slice, row) units evenly; partial sums meet in LDS in a fixed order.
 // A lane always handles one 32-column chunk = 16 bytes of a nibble plane (one 128-bit load) and
-// a wave issues all loads of a batch before it touches the first result; row addresses are
-// wave-uniform (scalar registers), the only per-lane part is the constant lane*16.
+// a wave issues all loads of a batch before it touches the first result.  Loads go through buffer
+// resources: wave-uniform row offsets in scalar registers, the per-lane part is lane*16, and a
+// lane or load with nothing to read is sent out of range (returns 0, moves no bytes), so the
+// issue code has no branches.
 // The kernels are VALU-issue bound before they are HBM bound, so the inner product is integer:
-// with bf16 activations each 32-value chunk of x (or h) is rewritten once, in LDS, as 14-bit
-// integers times a power-of-two chunk scale, split into two signed byte digits (x = 256 xh + xl);
-// a plane word is unpacked with 3 instructions into 8 byte-sized nibbles and consumed by 4
-// four-way int8 dot instructions.  All sums are exact int32:
-//   HIGH  (s sx)    * (16 A_m + A_l - zp X)       LOW  (16 s sx) * (A_m - (zp >> 4) X)
-// with A_p = sum nibble_p * xint over the lane's chunk, X = sum xint, sx the chunk scale.
+// with bf16 activations each 32-value chunk of x (or h) is rewritten once, in LDS, as integers
+// |q| <= 1911 times a power-of-two chunk scale, in three balanced hex digits (q = 256 d2 + 16 d1
+// + d0, d in [-8, 7]).  The planes store every nibble n as n - 8, so one signed 8 x 4-bit dot
+// instruction per plane word and digit does the work, with nothing to unpack.  All sums are exact
+// int32; with m' = m - 8, l' = l - 8, X = sum q, sx the chunk scale:
+//   HIGH  (s sx) * (16 m'.q + l'.q + (136 - zp) X)      LOW  (16 s sx) * (m'.q + (8 - (zp >> 4)) X)
 // fp32 activations take a plain fp32 path (byte -> float conversions and FMAs).
 #include "route_device.hpp"
 #include <hip/hip_ext.h>
@@ -89,38 +91,40 @@ template <int CTRL> __device__ __forceinline__ int quad_xchg(int v) {
 
 // ---------------------------------------------------------------------------------- lane operands
 // The lane's 32 activations.
-//   BF16: p[4j..4j+3] = digits of the values that meet plane word j: high digits of columns
-//         8j+{0,2,4,6}, their low digits, high digits of columns 8j+{1,3,5,7}, their low digits
-//         (one signed byte each); sx = chunk scale, xs = sum of the chunk's integers.
+//   BF16: the chunk as integers q = 256 d2 + 16 d1 + d0 with balanced digits d in [-8, 7] times a
+//         power-of-two chunk scale sx; p[4 d + j] = digit d of columns 8j .. 8j+7, one 4-bit two's
+//         complement value each, in the nibble order of a plane word; xs = sum of the chunk's q.
 //   F32 : plain values and their sum.
 template <int ACT> struct XR;
-template <> struct XR<SMOE_BF16> { uint32_t p[16]; float sx; int xs; };
+template <> struct XR<SMOE_BF16> { uint32_t p[12]; float sx; int xs; };
 template <> struct XR<SMOE_F32> { float v[32]; float xs; };
 
-__device__ __forceinline__ void dot_plane_i8(const uint4& m, const XR<SMOE_BF16>& x, int& ah, int& al) {
+// acc[t] += sum over the chunk of (plane nibble - 8) * digit t
+__device__ __forceinline__ void dot_plane_i4(const uint4& m, const XR<SMOE_BF16>& x, int& a0, int& a1, int& a2) {
   const uint32_t w[4] = {m.x, m.y, m.z, m.w};
 #pragma unroll
   for (int j = 0; j < 4; j++) {
-    const int e = (int)(w[j] & 0x0F0F0F0Fu), o = (int)((w[j] >> 4) & 0x0F0F0F0Fu);
-    ah = __builtin_amdgcn_sdot4(e, (int)x.p[4 * j + 0], ah, false);
-    al = __builtin_amdgcn_sdot4(e, (int)x.p[4 * j + 1], al, false);
-    ah = __builtin_amdgcn_sdot4(o, (int)x.p[4 * j + 2], ah, false);
-    al = __builtin_amdgcn_sdot4(o, (int)x.p[4 * j + 3], al, false);
+    a0 = __builtin_amdgcn_sdot8((int)w[j], (int)x.p[j], a0, false);
+    a1 = __builtin_amdgcn_sdot8((int)w[j], (int)x.p[4 + j], a1, false);
+    a2 = __builtin_amdgcn_sdot8((int)w[j], (int)x.p[8 + j], a2, false);
   }
 }
 
+// With m' = m - 8 and l' = l - 8 the stored nibbles:
+//   HIGH: s (16 m + l - zp) x = s sx (16 m'.q + l'.q + (136 - zp) sum q)
+//   LOW : 16 s (m - (zp >> 4)) x = 16 s sx (m'.q + (8 - (zp >> 4)) sum q)
 __device__ __forceinline__ float lane_value(const XR<SMOE_BF16>& x, const uint4& m, const uint4& l, int high, int zp,
                                             float s) {
-  int ah = 0, al = 0;
-  dot_plane_i8(m, x, ah, al);
-  int t = (ah << 8) + al;
+  int p0 = 0, p1 = 0, p2 = 0;
   if (high) {
-    int bh = 0, bl = 0;
-    dot_plane_i8(l, x, bh, bl);
-    t = (t << 4) + (bh << 8) + bl - zp * x.xs;
+    int p3 = 0;
+    dot_plane_i4(l, x, p0, p1, p2);      // powers 16^0..16^2
+    dot_plane_i4(m, x, p1, p2, p3);      // powers 16^1..16^3
+    const int t = p0 + (p1 << 4) + (p2 << 8) + (p3 << 12) + (136 - zp) * x.xs;
     return (s * x.sx) * (float)t;
   }
-  t -= (zp >> 4) * x.xs;
+  dot_plane_i4(m, x, p0, p1, p2);
+  const int t = p0 + (p1 << 4) + (p2 << 8) + (8 - (zp >> 4)) * x.xs;
   return (16.0f * s * x.sx) * (float)t;
 }
 
@@ -138,7 +142,8 @@ __device__ __forceinline__ float dot_bytes(uint32_t e, uint32_t o, const float* 
 
 __device__ __forceinline__ float lane_value(const XR<SMOE_F32>& x, const uint4& m, const uint4& l, int high, int zp,
                                             float s) {
-  const uint32_t wm[4] = {m.x, m.y, m.z, m.w}, wl[4] = {l.x, l.y, l.z, l.w};
+  const uint32_t f = 0x88888888u;      // the planes hold n ^ 8 per nibble
+  const uint32_t wm[4] = {m.x ^ f, m.y ^ f, m.z ^ f, m.w ^ f}, wl[4] = {l.x ^ f, l.y ^ f, l.z ^ f, l.w ^ f};
   float a0 = 0.0f, a1 = 0.0f;
   if (high) {
 #pragma unroll
@@ -156,8 +161,8 @@ __device__ __forceinline__ float lane_value(const XR<SMOE_F32>& x, const uint4& 
 
 // ---------------------------------------------------------------------------------- LDS staging
 // A vector of n = 32*C values is kept in LDS per 64-chunk k-slice as [piece][chunk][16 bytes] so
-// that the lanes of a wave read consecutive 16-byte pieces.  BF16: 4 pieces per chunk (64 B, the
-// digit words of XR), F32: 8 pieces of 4 floats (128 B).  cs[c] = (chunk scale, chunk sum).
+// that the lanes of a wave read consecutive 16-byte pieces.  BF16: 3 pieces per chunk (the digit
+// words of XR; 64 B per chunk are reserved), F32: 8 pieces of 4 floats (128 B).  cs[c] = (chunk scale, chunk sum).
 template <int ACT> struct StageTraits;
 template <> struct StageTraits<SMOE_BF16> { enum { BYTES_PER_VAL = 2 }; };
 template <> struct StageTraits<SMOE_F32> { enum { BYTES_PER_VAL = 4 }; };
@@ -183,10 +188,6 @@ template <int SRC> __device__ __forceinline__ void unpack8(const Raw8& r, float*
   }
 }
 
-__device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
-  return (uint32_t)(a & 255) | ((uint32_t)(b & 255) << 8) | ((uint32_t)(c & 255) << 16) | ((uint32_t)d << 24);
-}
-
 // Stages the 8 values v[0..8) = word j of chunk c of a vector with C chunks into dst (byte
 // address of that vector inside LDS) and its chunk figures into cs[c].  The four words of a chunk
 // must be handled by the four lanes of one quad in the same call.
@@ -199,24 +200,30 @@ __device__ __forceinline__ void stage_regs(float* v, int C, int c, int j, uint8_
     for (int i = 0; i < 8; i++) amax = fmaxf(amax, fabsf(v[i]));
     amax = fmaxf(amax, __int_as_float(quad_xchg<0xB1>(__float_as_int(amax))));
     amax = fmaxf(amax, __int_as_float(quad_xchg<0x4E>(__float_as_int(amax))));
-    // chunk scale 2^(e-13), e = exponent of the largest magnitude: integers stay below 2^14
-    const int be = (int)(__float_as_uint(amax) >> 23);
+    // chunk scale 2^(e-10), e = exponent of the largest magnitude, or 2^(e-9) when that would exceed
+    // 1911 = 7 * 273, the largest integer three balanced hex digits hold
+    int be = (int)(__float_as_uint(amax) >> 23);
     const bool live = be >= 20 && be < 255;
-    const float inv = live ? __uint_as_float((uint32_t)(267 - be) << 23) : 0.0f;
-    const float sx = live ? __uint_as_float((uint32_t)(be - 13) << 23) : 0.0f;
-    int xh[8], xl[8], part = 0;
+    if (amax * __uint_as_float((uint32_t)(264 - (live ? be : 127)) << 23) >= 1911.5f) be += 1;
+    const float inv = live ? __uint_as_float((uint32_t)(264 - be) << 23) : 0.0f;
+    const float sx = live ? __uint_as_float((uint32_t)(be - 10) << 23) : 0.0f;
+    uint32_t w0 = 0, w1 = 0, w2 = 0;
+    int part = 0;
 #pragma unroll
     for (int i = 0; i < 8; i++) {
       const int q = (int)rintf(v[i] * inv);
-      xl[i] = ((q + 128) & 255) - 128;          // balanced low digit in [-128, 127]
-      xh[i] = (q - xl[i]) >> 8;
       part += q;
+      const uint32_t t = (uint32_t)(q + 0x888) ^ 0x888u;      // nibble d = digit d in two's complement
+      w0 |= (t & 15u) << (4 * i);
+      w1 |= ((t >> 4) & 15u) << (4 * i);
+      w2 |= ((t >> 8) & 15u) << (4 * i);
     }
     part += quad_xchg<0xB1>(part);
     part += quad_xchg<0x4E>(part);
-    const uint4 o = make_uint4(pack4(xh[0], xh[2], xh[4], xh[6]), pack4(xl[0], xl[2], xl[4], xl[6]),
-                               pack4(xh[1], xh[3], xh[5], xh[7]), pack4(xl[1], xl[3], xl[5], xl[7]));
-    *(uint4*)(dst + (size_t)ks * 4096 + (size_t)(j * cw + cl) * 16) = o;
+    uint8_t* base = dst + (size_t)ks * 4096 + (size_t)j * 4;
+    *(uint32_t*)(base + (size_t)cl * 16) = w0;
+    *(uint32_t*)(base + (size_t)(cw + cl) * 16) = w1;
+    *(uint32_t*)(base + (size_t)(2 * cw + cl) * 16) = w2;
     if (j == 0) cs[c] = make_float2(sx, __int_as_float(part));
   } else {
     float part = 0.0f;
@@ -238,7 +245,7 @@ __device__ __forceinline__ void load_xr(XR<ACT>& x, const uint8_t* vec, const fl
     const uint4* b = (const uint4*)(vec + (size_t)ks * 4096);
     XR<SMOE_BF16>& xb = *(XR<SMOE_BF16>*)&x;
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
+    for (int j = 0; j < 3; j++) {
       const uint4 q = b[j * cw + lane];
       xb.p[4 * j] = q.x; xb.p[4 * j + 1] = q.y; xb.p[4 * j + 2] = q.z; xb.p[4 * j + 3] = q.w;
     }
@@ -255,19 +262,53 @@ __device__ __forceinline__ void load_xr(XR<ACT>& x, const uint8_t* vec, const fl
   }
 }
 
-// ---------------------------------------------------------------------------------- metadata addressing
-// Scale of element `elem + g` of an expert's scale block: a wave-uniform row pointer plus a small
-// per-lane offset.  16-bit scales are fetched as the aligned dword that contains them (a 16-bit
-// load would let the compiler pack two into one register, which forces it to wait for the load).
+// ---------------------------------------------------------------------------------- buffer addressing
+// Every bank section is read through a buffer resource: address = section base + a wave-uniform
+// byte offset (scalar register) + a small per-lane offset.  A lane (or a whole load) that has
+// nothing to read gets the per-lane offset DEC_OOB, which the hardware range check turns into
+// "return 0, touch no memory".  So every load below is unconditional, the issue code is straight
+// line, and the compiler can count outstanding loads exactly (partial s_waitcnt instead of
+// waiting for everything).  A zero scale makes a lane's contribution exactly 0.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+#define DEC_OOB 0x80000000u
+
+struct SecRsrc { __amdgpu_buffer_rsrc_t msb, lsb, zp, sc; };
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ SecRsrc make_sec(const MatDev& m, int n_experts) {
+  SecRsrc r;
+  r.msb = make_rsrc(m.msb, (unsigned)n_experts * m.ps32);
+  r.lsb = make_rsrc(m.lsb, (unsigned)n_experts * m.ps32);
+  r.zp = make_rsrc(m.zp, (unsigned)n_experts * m.zs32);
+  r.sc = make_rsrc(m.sc, (unsigned)n_experts * m.ss32);
+  return r;
+}
+__device__ __forceinline__ uint4 bload128(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint32_t bload32(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+  return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
+}
+__device__ __forceinline__ uint32_t bload8(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+  return __builtin_amdgcn_raw_buffer_load_b8(r, (int)voff, (int)soff, 0);
+}
+
+// Scale of element `elem + g` of an expert's scale block (block_off = its byte offset in the
+// section), fetched as the aligned dword that contains it; `odd` tells which half holds a 16-bit
+// scale.  live = false -> nothing is read and the scale is 0.
 template <int SCB>
-__device__ __forceinline__ uint32_t load_scale_raw(const uint8_t* sc, unsigned block_off, unsigned elem, int g, int& odd) {
+__device__ __forceinline__ uint32_t load_scale_raw(__amdgpu_buffer_rsrc_t sc, unsigned block_off, unsigned elem, int g,
+                                                   bool live, int& odd) {
   if (SCB) {
     const int t = (int)(elem & 1u) + g;
     odd = t & 1;
-    return *(const uint32_t*)(sc + (block_off + (elem >> 1) * 4u + (unsigned)((t >> 1) << 2)));
+    return bload32(sc, live ? (unsigned)((t >> 1) << 2) : DEC_OOB, block_off + (elem >> 1) * 4u);
   }
   odd = 0;
-  return *(const uint32_t*)(sc + (block_off + elem * 4u + (unsigned)(g << 2)));
+  return bload32(sc, live ? (unsigned)(g << 2) : DEC_OOB, block_off + elem * 4u);
 }
 template <int SCB> __device__ __forceinline__ float scale_val(uint32_t raw, int odd) {
   return SCB ? __uint_as_float(odd ? (raw & 0xFFFF0000u) : (raw << 16)) : __uint_as_float(raw);
@@ -392,6 +433,7 @@ __device__ __forceinline__ PairRef pair_ref(int e, int n_entries, int cap, int i
   bp = bp >= (int)gridDim.x ? bp - (int)gridDim.x : bp;
   p.r = bp + (int)gridDim.x * q;
   p.valid = e < n_entries && p.r < f;
+  p.r = p.valid ? p.r : 0;
   return p;
 }
 
@@ -404,49 +446,69 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
   const int d = a.d_model, C = d >> 5;
   const int k = a.has_routed ? a.k : 0;
   const unsigned rowb32 = (unsigned)d >> 1;
-  const unsigned voff = (unsigned)lane * 16u;
+  const bool live_lane = lane < C;
+  const unsigned voff = live_lane ? (unsigned)lane * 16u : DEC_OOB;
   const bool routed_wave = wave < a.gu_rw;
 
   uint4 gm[DEC_MAXP], um[DEC_MAXP], gl[DEC_MAXP], ul[DEC_MAXP];
   uint32_t zg[DEC_MAXP], zu[DEC_MAXP], sg[DEC_MAXP], su[DEC_MAXP];      // raw zero-points and scale bits
   int og[DEC_MAXP], ou[DEC_MAXP];                                        // position of a 16-bit scale in its dword
 
-  // every address is a section base (kernel argument, scalar) plus a 32-bit offset whose only
-  // per-lane part is lane*16 (planes) or the lane's group number (metadata)
-  auto issue = [&](int j, int r, const MatDev& md, int e, int prec, int sh) {
+  // eight unconditional loads per row pair (dead pairs / lanes / LSB planes read nothing); the small
+  // metadata loads of a batch go first, so that a pair's arithmetic waits for its own planes only
+  auto issue_meta = [&](int j, bool valid, int r, const SecRsrc& R, const MatDev& md, int e, int sh) {
     const unsigned ng = (unsigned)md.ng;
-    const unsigned po = (unsigned)e * md.ps32 + (unsigned)(2 * r) * rowb32;
-    gm[j] = *(const uint4*)(md.msb + (po + voff));
-    um[j] = *(const uint4*)(md.msb + (po + rowb32 + voff));
-    if (prec) {
-      gl[j] = *(const uint4*)(md.lsb + (po + voff));
-      ul[j] = *(const uint4*)(md.lsb + (po + rowb32 + voff));
-    }
     const int g = lane >> sh;
+    const bool live = valid && live_lane;
     const unsigned zo = (unsigned)e * md.zs32 + (unsigned)(2 * r) * ng;
-    zg[j] = md.zp[zo + (unsigned)g];
-    zu[j] = md.zp[zo + ng + (unsigned)g];
-    sg[j] = load_scale_raw<SCB>(md.sc, (unsigned)e * md.ss32, (unsigned)(2 * r) * ng, g, og[j]);
-    su[j] = load_scale_raw<SCB>(md.sc, (unsigned)e * md.ss32, (unsigned)(2 * r + 1) * ng, g, ou[j]);
+    const unsigned vg = live ? (unsigned)g : DEC_OOB;
+    zg[j] = bload8(R.zp, vg, zo);
+    zu[j] = bload8(R.zp, vg, zo + ng);
+    sg[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, (unsigned)(2 * r) * ng, g, live, og[j]);
+    su[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, (unsigned)(2 * r + 1) * ng, g, live, ou[j]);
+  };
+  auto issue_planes = [&](int j, bool valid, int r, const SecRsrc& R, const MatDev& md, int e, int prec) {
+    const unsigned po = (unsigned)e * md.ps32 + (unsigned)(2 * r) * rowb32;
+    const unsigned vo = valid ? voff : DEC_OOB, vl = (valid && prec) ? voff : DEC_OOB;
+    gm[j] = bload128(R.msb, vo, po);
+    gl[j] = bload128(R.lsb, vl, po);
+    um[j] = bload128(R.msb, vo, po + rowb32);
+    ul[j] = bload128(R.lsb, vl, po + rowb32);
   };
   auto finish = [&](int j, int prec, const XR<ACT>& x, int hidx) {
-    float av = 0.0f, uv = 0.0f;
-    if (lane < C) {
-      av = lane_value(x, gm[j], gl[j], prec, (int)zg[j], scale_val<SCB>(sg[j], og[j]));
-      uv = lane_value(x, um[j], ul[j], prec, (int)zu[j], scale_val<SCB>(su[j], ou[j]));
-    }
+    float av = lane_value(x, gm[j], gl[j], prec, (int)zg[j], scale_val<SCB>(sg[j], og[j]));
+    float uv = lane_value(x, um[j], ul[j], prec, (int)zu[j], scale_val<SCB>(su[j], ou[j]));
     av = wave_sum_to63(av);
     uv = wave_sum_to63(uv);
-    if (lane == 63) a.h[hidx] = av / (1.0f + __expf(-av)) * uv;
+    if (lane == 63 && hidx >= 0) a.h[hidx] = av / (1.0f + __expf(-av)) * uv;
   };
 
-  // ---- loads that depend on nothing: x (staged by the waves after wave 0, which has the routing to
-  // do), the routing inputs (wave 0) and, in the shared-expert waves, the first batch of rows
+  // ---- prologue: x into LDS (the four waves after wave 0), routing decision into LDS (wave 0), weight
+  // of the shared experts (a wave of block 0).  Each of these waits for its own loads right here: a
+  // load still pending where control flow merges would make all later code wait for every load.
   const int xt = tid - 64;
-  Raw8 xraw;
-  if (xt >= 0 && xt < 4 * C) load8_raw<ACT>(a.x, (size_t)xt * 8, xraw);
-  RouteRegs rr;
-  if (wave == 0 && k > 0) route_load(a, lane, rr);
+  if (xt >= 0 && xt < 4 * C) {
+    Raw8 xraw;
+    load8_raw<ACT>(a.x, (size_t)xt * 8, xraw);
+    float xv[8];
+    unpack8<ACT>(xraw, xv);
+    stage_regs<ACT>(xv, C, xt >> 2, xt & 3, xvec, xcs);
+  }
+  if (wave == 0 && k > 0) {
+    RouteRegs rr;
+    route_load(a, lane, rr);
+    if (a.E <= 64) route_compute<1>(a, lane, rr, rec);
+    else route_compute<4>(a, lane, rr, rec);
+  }
+  if (blockIdx.x == 0 && wave == 5) {
+    float g = 1.0f;
+    if (a.shared_gate_w) {
+      float p = 0.0f;
+      for (int i = lane; i < d; i += 64) p = fmaf(load_act<ACT>(a.shared_gate_w, i), load_act<ACT>(a.x, i), p);
+      g = 1.0f / (1.0f + expf(-wave_sum(p)));
+    }
+    if (lane == 0) rec.gamma = g;
+  }
 
   // entry t of this wave: index first + t * n, n = number of waves of its kind
   const int n_se = a.n_shared * a.cap_s, n_re = k * a.cap_r;
@@ -460,33 +522,22 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
     return routed_wave ? a.n_shared * a.f_s + p.slot * a.f_r + p.r : p.slot * a.f_s + p.r;
   };
 
+  // ---- shared-expert waves: rows in flight before the routing decision exists
   if (!routed_wave) {
+    const SecRsrc RS = make_sec(a.shared.gu, a.shared.n_experts);
 #pragma unroll
     for (int j = 0; j < DEC_MAXP; j++) {
       const PairRef p = entry(j);
-      if (p.valid && lane < C) issue(j, p.r, a.shared.gu, p.slot, 1, a.gu_sh_s);
+      issue_meta(j, p.valid, p.r, RS, a.shared.gu, p.slot, a.gu_sh_s);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < DEC_MAXP; j++) {
+      const PairRef p = entry(j);
+      issue_planes(j, p.valid, p.r, RS, a.shared.gu, p.slot, 1);
     }
   }
 
-  // ---- x into LDS, routing decision into LDS
-  if (xt >= 0 && xt < 4 * C) {
-    float xv[8];
-    unpack8<ACT>(xraw, xv);
-    stage_regs<ACT>(xv, C, xt >> 2, xt & 3, xvec, xcs);
-  }
-  if (wave == 0 && k > 0) {
-    if (a.E <= 64) route_compute<1>(a, lane, rr, rec);
-    else route_compute<4>(a, lane, rr, rec);
-  }
-  if (blockIdx.x == 0 && wave == DEC_NW - 1) {          // weight of the shared experts
-    float g = 1.0f;
-    if (a.shared_gate_w) {
-      float p = 0.0f;
-      for (int i = lane; i < d; i += 64) p = fmaf(load_act<ACT>(a.shared_gate_w, i), load_act<ACT>(a.x, i), p);
-      g = 1.0f / (1.0f + expf(-wave_sum(p)));
-    }
-    if (lane == 0) rec.gamma = g;
-  }
   lds_barrier();
   if (blockIdx.x == 0 && tid < 64) {                      // publish for the down kernel and the caller
     if (tid < k) {
@@ -504,36 +555,57 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
     const PairRef p = entry(j);
     hidx[j] = p.valid ? hidx_of(p) : -1;
     pr[j] = 1;
-    if (routed_wave && p.valid) {
-      pr[j] = uni(rec.prec[p.slot]);
-      if (lane < C) issue(j, p.r, a.routed.gu, uni(rec.sel[p.slot]), pr[j], a.gu_sh_r);
+  }
+  if (routed_wave) {
+    const SecRsrc RR = make_sec(a.routed.gu, a.routed.n_experts);
+    int ex[DEC_MAXP];
+#pragma unroll
+    for (int j = 0; j < DEC_MAXP; j++) {
+      const PairRef p = entry(j);
+      const int slot = p.valid ? p.slot : 0;
+      pr[j] = uni(rec.prec[slot]);
+      ex[j] = uni(rec.sel[slot]);
+      issue_meta(j, p.valid, p.r, RR, a.routed.gu, ex[j], a.gu_sh_r);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < DEC_MAXP; j++) {
+      const PairRef p = entry(j);
+      issue_planes(j, p.valid, p.r, RR, a.routed.gu, ex[j], pr[j]);
     }
   }
-  XR<ACT> x;
-  if (lane < C) load_xr<ACT>(x, xvec, xcs, 0, C, lane);
+  XR<ACT> x = {};
+  if (live_lane) load_xr<ACT>(x, xvec, xcs, 0, C, lane);
 #pragma unroll
-  for (int j = 0; j < DEC_MAXP; j++)
-    if (hidx[j] >= 0) finish(j, pr[j], x, hidx[j]);
+  for (int j = 0; j < DEC_MAXP; j++) finish(j, pr[j], x, hidx[j]);
 
   // layers with more than DEC_MAXP entries per wave: the rest one at a time
   for (int t = DEC_MAXP; my_first + t * my_n < my_cnt; t++) {
     const PairRef p = entry(t);
-    if (!p.valid) continue;
-    const int prec = routed_wave ? uni(rec.prec[p.slot]) : 1;
-    if (lane < C) {
-      if (routed_wave) issue(0, p.r, a.routed.gu, uni(rec.sel[p.slot]), prec, a.gu_sh_r);
-      else issue(0, p.r, a.shared.gu, p.slot, 1, a.gu_sh_s);
+    const int slot = p.valid ? p.slot : 0;
+    int prec = 1;
+    if (routed_wave) {
+      prec = uni(rec.prec[slot]);
+      const SecRsrc RR = make_sec(a.routed.gu, a.routed.n_experts);
+      issue_meta(0, p.valid, p.r, RR, a.routed.gu, uni(rec.sel[slot]), a.gu_sh_r);
+      issue_planes(0, p.valid, p.r, RR, a.routed.gu, uni(rec.sel[slot]), prec);
+    } else {
+      const SecRsrc RS = make_sec(a.shared.gu, a.shared.n_experts);
+      issue_meta(0, p.valid, p.r, RS, a.shared.gu, slot, a.gu_sh_s);
+      issue_planes(0, p.valid, p.r, RS, a.shared.gu, slot, 1);
     }
-    finish(0, prec, x, hidx_of(p));
+    finish(0, prec, x, p.valid ? hidx_of(p) : -1);
   }
 }
 
 // ---------------------------------------------------------------------------------- down kernel
 // A work-group owns DEC_RPW output rows.  Units = (slot, k-slice, row); unit u of a list: row =
 // u % 8, combo = u / 8 -> (slot, k-slice) = (combo / ks, combo % ks).  Waves [0, dn_rw) take the
-// routed list (and wait for the routing record), the other waves the shared-expert list, whose
-// loads are in flight from the first instruction.  A wave of a group of n takes a contiguous
-// share of its list, so that consecutive units mostly reuse the same h chunk.
+// routed list, the other waves the shared-expert list, whose loads are in flight from the first
+// instruction.  A wave of a group of n takes a contiguous share of its list, so that consecutive
+// units mostly reuse the same h chunk.  The routed waves also stage h (all waves do when there is
+// no routed bank); each routed wave reads the routing record itself, so nothing waits on LDS
+// before the plane loads are issued.
 struct UnitRef { int slot, ks, row; };
 
 __device__ __forceinline__ UnitRef unit_ref(int u, int ks_n, int inv_ks) {
@@ -545,10 +617,11 @@ __device__ __forceinline__ UnitRef unit_ref(int u, int ks_n, int inv_ks) {
   return r;
 }
 
+#define DEC_HQ 3      // h words of 8 values each stager thread loads up front
+
 template <int ACT, int SCB>
 __global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_bytes) {
   extern __shared__ __align__(16) uint8_t dyn[];     // [h vectors][chunk figures][unit partials]
-  __shared__ RouteRec rec;
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int k = a.has_routed ? a.k : 0;
   const int nsf = a.n_shared * a.f_s;
@@ -557,121 +630,170 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_
   float2* hcs = (float2*)(dyn + lds_vec_bytes);
   float* part = (float*)(hcs + (total_f >> 5));     // shared-expert units first, then routed units
   const int n0 = blockIdx.x * DEC_RPW;
-  const unsigned voff = (unsigned)lane * 16u;
   const bool routed_wave = wave < a.dn_rw;
-  const int n_su = a.n_shared * a.ks_s * DEC_RPW, n_ru = k * a.ks_r * DEC_RPW, n_sw = DEC_NW - a.dn_rw;
+  const int n_su = a.n_shared * a.ks_s * DEC_RPW, n_ru = k * a.ks_r * DEC_RPW;
 
   uint4 wm[DEC_MAXU], wl[DEC_MAXU];
   uint32_t zz[DEC_MAXU], ss[DEC_MAXU];      // raw zero-points and scale bits
   int so[DEC_MAXU];
 
-  auto issue = [&](int j, const UnitRef& u, int f, const MatDev& md, int e, int prec, int sh) {
+  // four unconditional loads per unit, the two small ones of a whole batch first
+  auto issue_meta = [&](int j, bool valid, const UnitRef& u, int f, const SecRsrc& R, const MatDev& md, int e, int sh) {
     const int cw = min(64, (f >> 5) - u.ks * 64);
-    if (lane < cw) {
-      const unsigned po = (unsigned)e * md.ps32 + (unsigned)(n0 + u.row) * ((unsigned)f >> 1) + (unsigned)u.ks * 1024u;
-      wm[j] = *(const uint4*)(md.msb + (po + voff));
-      if (prec) wl[j] = *(const uint4*)(md.lsb + (po + voff));
-      const int g = lane >> sh;
-      const unsigned elem = (unsigned)(n0 + u.row) * (unsigned)md.ng + (unsigned)((u.ks * 64) >> sh);
-      zz[j] = md.zp[(unsigned)e * md.zs32 + elem + (unsigned)g];
-      ss[j] = load_scale_raw<SCB>(md.sc, (unsigned)e * md.ss32, elem, g, so[j]);
-    }
+    const bool live = valid && lane < cw;
+    const int g = lane >> sh;
+    const unsigned elem = (unsigned)(n0 + u.row) * (unsigned)md.ng + (unsigned)((u.ks * 64) >> sh);
+    zz[j] = bload8(R.zp, live ? (unsigned)g : DEC_OOB, (unsigned)e * md.zs32 + elem);
+    ss[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, elem, g, live, so[j]);
   };
-  // consumes the units [b0, b0 + DEC_MAXU) of a list; h chunk registers are reloaded on a new combo
-  auto finish = [&](int j, const UnitRef& u, int f, int hoff, int prec, float wt, XR<ACT>& x, int& cur, int combo, int pidx) {
+  auto issue_planes = [&](int j, bool valid, const UnitRef& u, int f, const SecRsrc& R, const MatDev& md, int e, int prec) {
     const int cw = min(64, (f >> 5) - u.ks * 64);
-    if (combo != cur) {
+    const bool live = valid && lane < cw;
+    const unsigned po = (unsigned)e * md.ps32 + (unsigned)(n0 + u.row) * ((unsigned)f >> 1) + (unsigned)u.ks * 1024u;
+    const unsigned vo = live ? (unsigned)lane * 16u : DEC_OOB;
+    wm[j] = bload128(R.msb, vo, po);
+    wl[j] = bload128(R.lsb, prec ? vo : DEC_OOB, po);
+  };
+  // h chunk registers are reloaded when the (slot, k-slice) combo changes
+  auto finish = [&](int j, bool valid, const UnitRef& u, int f, int hoff, int prec, float wt, XR<ACT>& x, int& cur,
+                    int combo, int pidx) {
+    const int cw = min(64, (f >> 5) - u.ks * 64);
+    if (valid && combo != cur) {
       cur = combo;
       if (lane < cw) load_xr<ACT>(x, hvec + (size_t)hoff * StageTraits<ACT>::BYTES_PER_VAL, hcs + (hoff >> 5), u.ks, cw, lane);
     }
-    float v = 0.0f;
-    if (lane < cw) v = lane_value(x, wm[j], wl[j], prec, (int)zz[j], scale_val<SCB>(ss[j], so[j]));
+    float v = lane_value(x, wm[j], wl[j], prec, (int)zz[j], scale_val<SCB>(ss[j], so[j]));
     v = wave_sum_to63(v);
-    if (lane == 63) part[pidx] = wt * v;
+    if (lane == 63 && valid) part[pidx] = wt * v;
   };
 
-  // ---- loads that depend on nothing: the routing record, h, and (shared-expert waves) plane rows
-  int rec_word = 0;
-  if (tid < (int)(sizeof(RouteRec) / 4)) rec_word = ((const int*)a.rec)[tid];
-  Raw8 hraw[2];
-  int hitem[2];
-#pragma unroll
-  for (int q = 0; q < 2; q++) {
-    hitem[q] = tid + q * DEC_NT;
-    if (hitem[q] < (total_f >> 3)) load8_raw<SMOE_F32>(a.h, (size_t)hitem[q] * 8, hraw[q]);
-  }
-  // my units: a contiguous share [u_lo, u_hi) of my kind's list
-  const int my_w = routed_wave ? wave : wave - a.dn_rw, my_nw = routed_wave ? a.dn_rw : n_sw;
-  const int my_total = routed_wave ? n_ru : n_su;
-  const int u_lo = my_total * my_w / my_nw, u_hi = my_total * (my_w + 1) / my_nw;
-  const int my_ks = routed_wave ? a.ks_r : a.ks_s, my_inv = routed_wave ? a.inv_ks_r : a.inv_ks_s;
-  const int my_f = routed_wave ? a.f_r : a.f_s, my_hbase = routed_wave ? nsf : 0, my_pbase = routed_wave ? n_su : 0;
-  if (!routed_wave) {
-#pragma unroll
-    for (int j = 0; j < DEC_MAXU; j++)
-      if (u_lo + j < u_hi) {
-        const UnitRef u = unit_ref(u_lo + j, my_ks, my_inv);
-        issue(j, u, a.f_s, a.shared.dn, u.slot, 1, a.dn_sh_s);
-      }
-  }
-
-  // ---- routing record and h into LDS
-  if (tid < (int)(sizeof(RouteRec) / 4)) ((int*)&rec)[tid] = rec_word;
-  auto stage_h = [&](const Raw8& raw, int item) {
+  // h words -> LDS; `item` = index of a group of 8 consecutive h values
+  const __amdgpu_buffer_rsrc_t RH = make_rsrc(a.h, (unsigned)total_f * 4u);
+  auto stage_h = [&](const uint4& r0, const uint4& r1, int item) {
     const int i0 = item * 8;
     int voffs, f;                                      // which vector: shared experts first, then routed slots
     if (i0 < nsf) { const int s = i0 / a.f_s; voffs = s * a.f_s; f = a.f_s; }
     else { const int s = (i0 - nsf) / a.f_r; voffs = nsf + s * a.f_r; f = a.f_r; }
     const int local = i0 - voffs;
+    Raw8 raw; raw.a = r0; raw.b = r1;
     float hv[8];
     unpack8<SMOE_F32>(raw, hv);
     stage_regs<ACT>(hv, f >> 5, local >> 5, (local >> 3) & 3, hvec + (size_t)voffs * StageTraits<ACT>::BYTES_PER_VAL,
                     hcs + (voffs >> 5));
   };
+  uint4 hraw[DEC_HQ][2];
+  auto load_h = [&](int st_first, int st_n) {          // unconditional: items past the end read nothing
 #pragma unroll
-  for (int q = 0; q < 2; q++)
-    if (hitem[q] < (total_f >> 3)) stage_h(hraw[q], hitem[q]);
-  for (int item = tid + 2 * DEC_NT; item < (total_f >> 3); item += DEC_NT) {      // very wide layers only
-    Raw8 raw;
-    load8_raw<SMOE_F32>(a.h, (size_t)item * 8, raw);
-    stage_h(raw, item);
-  }
-  lds_barrier();
+    for (int q = 0; q < DEC_HQ; q++) {
+      const int item = st_first + q * st_n;
+      const unsigned vo = item < (total_f >> 3) ? (unsigned)item * 32u : DEC_OOB;
+      hraw[q][0] = bload128(RH, vo, 0);
+      hraw[q][1] = bload128(RH, vo, 16);
+    }
+  };
+  auto stage_all = [&](int st_first, int st_n) {
+#pragma unroll
+    for (int q = 0; q < DEC_HQ; q++) {
+      const int item = st_first + q * st_n;
+      if (item < (total_f >> 3)) stage_h(hraw[q][0], hraw[q][1], item);
+    }
+    for (int item = st_first + DEC_HQ * st_n; item < (total_f >> 3); item += st_n)        // very wide layers only
+      stage_h(bload128(RH, (unsigned)item * 32u, 0), bload128(RH, (unsigned)item * 32u, 16), item);
+  };
+  float* gamma_lds = part + n_su + n_ru;
 
-  int pr[DEC_MAXU];
-  float wt[DEC_MAXU];
-  const float gamma = __int_as_float(uni(__float_as_int(rec.gamma)));
+  // The two kinds of waves run separate straight-line code (no merge of control flow between the
+  // issue of a wave's loads and their use, so every wait is for exactly the load that is needed).
+  // Units of a kind are shared out in contiguous runs [u_lo, u_hi).
+  if (routed_wave) {
+    // routed waves: h words and the routing record first, rows as soon as the record is here, then h
+    // into LDS while the rows stream in.  sel / prec / w of slot s sit in words s, 16+s, 32+s of the
+    // record, gamma in word 48.
+    const int u_lo = n_ru * wave / a.dn_rw, u_hi = n_ru * (wave + 1) / a.dn_rw;
+    load_h(tid, a.dn_rw * 64);
+    const int rec_word = ((const int*)a.rec)[lane];                      // sizeof(RouteRec) == 64 words
+    const SecRsrc RR = make_sec(a.routed.dn, a.routed.n_experts);
+    int pr[DEC_MAXU], ex[DEC_MAXU];
+    float wt[DEC_MAXU];
 #pragma unroll
-  for (int j = 0; j < DEC_MAXU; j++) {
-    pr[j] = 1; wt[j] = gamma;
-    if (routed_wave && u_lo + j < u_hi) {
-      const UnitRef u = unit_ref(u_lo + j, my_ks, my_inv);
-      pr[j] = uni(rec.prec[u.slot]);
-      wt[j] = __int_as_float(uni(__float_as_int(rec.w[u.slot])));
-      issue(j, u, a.f_r, a.routed.dn, uni(rec.sel[u.slot]), pr[j], a.dn_sh_r);
+    for (int j = 0; j < DEC_MAXU; j++) {
+      const bool valid = u_lo + j < u_hi;
+      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_r, a.inv_ks_r);
+      ex[j] = __builtin_amdgcn_readlane(rec_word, u.slot);
+      pr[j] = __builtin_amdgcn_readlane(rec_word, SMOE_MAX_TOPK + u.slot);
+      wt[j] = __int_as_float(__builtin_amdgcn_readlane(rec_word, 2 * SMOE_MAX_TOPK + u.slot));
+      issue_meta(j, valid, u, a.f_r, RR, a.routed.dn, ex[j], a.dn_sh_r);
     }
-  }
-  XR<ACT> x;
-  int cur = -1;
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int j = 0; j < DEC_MAXU; j++)
-    if (u_lo + j < u_hi) {
-      const UnitRef u = unit_ref(u_lo + j, my_ks, my_inv);
-      finish(j, u, my_f, my_hbase + u.slot * my_f, pr[j], wt[j], x, cur, (u_lo + j) / DEC_RPW, my_pbase + u_lo + j);
+    for (int j = 0; j < DEC_MAXU; j++) {
+      const bool valid = u_lo + j < u_hi;
+      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_r, a.inv_ks_r);
+      issue_planes(j, valid, u, a.f_r, RR, a.routed.dn, ex[j], pr[j]);
     }
-  // layers with more than DEC_MAXU units per wave: the rest one at a time
-  for (int uu = u_lo + DEC_MAXU; uu < u_hi; uu++) {
-    const UnitRef u = unit_ref(uu, my_ks, my_inv);
-    int prec = 1;
-    float w1 = gamma;
-    if (routed_wave) {
-      prec = uni(rec.prec[u.slot]);
-      w1 = __int_as_float(uni(__float_as_int(rec.w[u.slot])));
-      issue(0, u, a.f_r, a.routed.dn, uni(rec.sel[u.slot]), prec, a.dn_sh_r);
-    } else {
-      issue(0, u, a.f_s, a.shared.dn, u.slot, 1, a.dn_sh_s);
+    __builtin_amdgcn_sched_barrier(0);
+    stage_all(tid, a.dn_rw * 64);
+    if (tid == 0) *gamma_lds = __int_as_float(__builtin_amdgcn_readlane(rec_word, 3 * SMOE_MAX_TOPK));
+    lds_barrier();
+    XR<ACT> x = {};
+    int cur = -1;
+#pragma unroll
+    for (int j = 0; j < DEC_MAXU; j++) {
+      const bool valid = u_lo + j < u_hi;
+      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_r, a.inv_ks_r);
+      finish(j, valid, u, a.f_r, nsf + u.slot * a.f_r, pr[j], wt[j], x, cur, (u_lo + j) / DEC_RPW, n_su + u_lo + j);
     }
-    finish(0, u, my_f, my_hbase + u.slot * my_f, prec, w1, x, cur, uu / DEC_RPW, my_pbase + uu);
+    for (int uu = u_lo + DEC_MAXU; uu < u_hi; uu++) {      // more than DEC_MAXU units per wave: one at a time
+      const UnitRef u = unit_ref(uu, a.ks_r, a.inv_ks_r);
+      const int e = __builtin_amdgcn_readlane(rec_word, u.slot);
+      const int prec = __builtin_amdgcn_readlane(rec_word, SMOE_MAX_TOPK + u.slot);
+      const float w1 = __int_as_float(__builtin_amdgcn_readlane(rec_word, 2 * SMOE_MAX_TOPK + u.slot));
+      issue_meta(0, true, u, a.f_r, RR, a.routed.dn, e, a.dn_sh_r);
+      issue_planes(0, true, u, a.f_r, RR, a.routed.dn, e, prec);
+      finish(0, true, u, a.f_r, nsf + u.slot * a.f_r, prec, w1, x, cur, uu / DEC_RPW, n_su + uu);
+    }
+  } else {
+    // shared-expert waves: rows in flight from the first instruction; without routed waves they also
+    // stage h
+    const int sw = wave - a.dn_rw, n_sw = DEC_NW - a.dn_rw;
+    const int u_lo = n_su * sw / n_sw, u_hi = n_su * (sw + 1) / n_sw;
+    const bool stage = a.dn_rw == 0;
+    if (stage) load_h(tid, DEC_NT);
+    const SecRsrc RS = make_sec(a.shared.dn, a.shared.n_experts);
+#pragma unroll
+    for (int j = 0; j < DEC_MAXU; j++) {
+      const bool valid = u_lo + j < u_hi;
+      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_s, a.inv_ks_s);
+      issue_meta(j, valid, u, a.f_s, RS, a.shared.dn, u.slot, a.dn_sh_s);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < DEC_MAXU; j++) {
+      const bool valid = u_lo + j < u_hi;
+      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_s, a.inv_ks_s);
+      issue_planes(j, valid, u, a.f_s, RS, a.shared.dn, u.slot, 1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (stage) {
+      stage_all(tid, DEC_NT);
+      if (tid == 0) *gamma_lds = a.rec->gamma;
+    }
+    lds_barrier();
+    const float gamma = *gamma_lds;
+    XR<ACT> x = {};
+    int cur = -1;
+#pragma unroll
+    for (int j = 0; j < DEC_MAXU; j++) {
+      const bool valid = u_lo + j < u_hi;
+      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_s, a.inv_ks_s);
+      finish(j, valid, u, a.f_s, u.slot * a.f_s, 1, gamma, x, cur, (u_lo + j) / DEC_RPW, u_lo + j);
+    }
+    for (int uu = u_lo + DEC_MAXU; uu < u_hi; uu++) {
+      const UnitRef u = unit_ref(uu, a.ks_s, a.inv_ks_s);
+      issue_meta(0, true, u, a.f_s, RS, a.shared.dn, u.slot, a.dn_sh_s);
+      issue_planes(0, true, u, a.f_s, RS, a.shared.dn, u.slot, 1);
+      finish(0, true, u, a.f_s, u.slot * a.f_s, 1, gamma, x, cur, uu / DEC_RPW, uu);
+    }
   }
   __syncthreads();
   if (tid < DEC_RPW) {
@@ -695,7 +817,7 @@ template <int ACT, int SCB>
 static int launch_decode_t(smoe_ctx* ctx, DecodeArgs& a, int total_f, int n_wg) {
   const size_t vec_bytes = (size_t)total_f * StageTraits<ACT>::BYTES_PER_VAL;
   const size_t n_units = (size_t)(a.n_shared * a.ks_s + a.k * a.ks_r) * DEC_RPW;
-  const size_t lds = vec_bytes + (size_t)(total_f / 32) * 8 + n_units * 4;
+  const size_t lds = vec_bytes + (size_t)(total_f / 32) * 8 + n_units * 4 + 16;      // + the shared experts' weight
   if (lds + sizeof(RouteRec) + 256 > 160u * 1024u) return SMOE_ESIZE;
   if (lds > 64u * 1024u) {       // beyond the default per-work-group limit: ask for the larger carve-out
     static size_t granted = 0;

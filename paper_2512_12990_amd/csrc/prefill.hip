@@ -149,8 +149,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
     uint32_t out[16];
 #pragma unroll
     for (int j = 0; j < 4; j++) {
-      const uint32_t qe = ((wm[j] & 0x0F0F0F0Fu) << 4) | (wl[j] & 0x0F0F0F0Fu);      // even columns
-      const uint32_t qo = (wm[j] & 0xF0F0F0F0u) | ((wl[j] >> 4) & 0x0F0F0F0Fu);     // odd columns
+      // the planes hold n ^ 8 per nibble
+      const uint32_t qe = (((wm[j] & 0x0F0F0F0Fu) << 4) | (wl[j] & 0x0F0F0F0Fu)) ^ 0x88888888u;      // even columns
+      const uint32_t qo = ((wm[j] & 0xF0F0F0F0u) | ((wl[j] >> 4) & 0x0F0F0F0Fu)) ^ 0x88888888u;     // odd columns
 #pragma unroll
       for (int b = 0; b < 4; b++) {
         const float we = fmaf((float)((qe >> (8 * b)) & 0xFF), rs, c0);

@@ -64,8 +64,10 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restri
       const float a = load_w<WDT>(src, sbase + k0 + 2 * p), b = load_w<WDT>(src, sbase + k0 + 2 * p + 1);
       const int qa = min(max((int)rintf(a / s) + zp, 0), 255);
       const int qb = min(max((int)rintf(b / s) + zp, 0), 255);
-      pm[(k0 >> 1) + p] = (uint8_t)((qa >> 4) | (qb & 0xF0));          // floor(q/16): the low-bit code
-      pl[(k0 >> 1) + p] = (uint8_t)((qa & 15) | ((qb & 15) << 4));     // the bits truncation drops
+      // planes keep every nibble n as n - 8 in 4-bit two's complement (n ^ 8): signed 4-bit dot products
+      // read them directly
+      pm[(k0 >> 1) + p] = (uint8_t)(((qa >> 4) | (qb & 0xF0)) ^ 0x88);          // floor(q/16): the low-bit code
+      pl[(k0 >> 1) + p] = (uint8_t)(((qa & 15) | ((qb & 15) << 4)) ^ 0x88);     // the bits truncation drops
     }
     if (lane == 0) {
       pz[g] = (uint8_t)zp;
