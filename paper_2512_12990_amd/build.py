@@ -13,13 +13,15 @@ SOURCES = ["api.hip", "quantize.hip", "route.hip", "decode.hip", "prefill.hip", 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 instructions are disabled on purpose: the compiler must not form them
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# decode kernels: the leading scalar kernel parameters arrive in registers at wave launch
+EXTRA_FLAGS = {"decode.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function"]
 
 
 def _compile(src: str, objdir: str) -> str:
     obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
     if src.endswith(".hip"):
-        cmd = [HIPCC, "-c", os.path.join(CSRC, src), "-o", obj] + COMMON + DEVICE_FLAGS
+        cmd = [HIPCC, "-c", os.path.join(CSRC, src), "-o", obj] + COMMON + DEVICE_FLAGS + EXTRA_FLAGS.get(src, [])
     else:
         cmd = [HIPCC, "-x", "c++", "-c", os.path.join(CSRC, src), "-o", obj] + COMMON
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -34,30 +34,66 @@
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
+// One expert matrix family as the kernels see it (48 bytes).
+struct MatK {
+  const uint8_t* msb; const uint8_t* lsb; const uint8_t* zp; const uint8_t* sc;
+  unsigned ps32, zs32, ss32;       // bytes per expert in the plane / zero-point / scale sections
+  int ng;                          // quantisation groups per row
+};
+
+// Kernel arguments, kept compact and ordered by use: a dispatch's arguments are cold in every
+// cache, each 64-byte line of them costs a memory round trip when first touched, and the kernels
+// therefore fetch all their lines at once in their first instructions (KARGS_TOUCH).
 struct DecodeArgs {
-  BankDev routed, shared;
-  int has_routed, n_shared, k, do_route;
-  int E, norm_topk;
-  float routed_scale, tau;
-  const float* logits; const float* bias;
+  MatK rgu, sgu;                   // gate/up families of the routed / shared bank        [gate/up kernel]
   const int32_t* idx_in; const float* w_in;
-  const uint8_t* mask;
-  const void* x; const void* shared_gate_w;
-  RouteRec* rec;        // routing record (gate/up block 0 writes, down reads)
-  float* h;             // SwiGLU vectors: shared experts first, then the routed slots, fp32
+  const void* shared_gate_w;
   int32_t* idx_out; float* w_out; uint8_t* prec_out;
-  void* y;
-  int add_residual, d_model;
-  // static work split, worked out on the host
-  int f_r, f_s;                    // d_ff of the routed / shared bank (0 if absent)
+  float routed_scale, tau;
+  int norm_topk;
   int cap_r, cap_s;                // gate/up: row pairs per work-group and slot = ceil(f / n_wg)
   int inv_cap_r, inv_cap_s;        // ceil(65536 / cap)
   int rot;                         // gate/up: per-slot rotation of the work-group index
   int gu_rw;                       // gate/up: waves [0, gu_rw) take routed slots, the rest shared experts
+  int gu_sh_r, gu_sh_s;            // log2(32-column chunks per quantisation group), gate/up families
+  int n_shared;                    // experts in the shared bank                          [both kernels]
+  const void* x;
+  RouteRec* rec;                   // routing record (gate/up block 0 writes, down reads)
+  float* h;                        // SwiGLU vectors: shared experts first, then the routed slots, fp32
+  int E, k;                        // experts in the routed bank, routed slots (0 without a routed bank)
+  int f_r, f_s;                    // d_ff of the routed / shared bank (0 if absent)
+  void* y;                         //                                                     [down kernel]
+  MatK rdn, sdn;                   // down families
   int ks_r, ks_s, inv_ks_r, inv_ks_s;   // down: 64-chunk k-slices per row, ceil(65536 / ks)
-  int dn_rw;                       // down: waves [0, dn_rw) take routed slots, the rest shared experts
-  int gu_sh_r, gu_sh_s, dn_sh_r, dn_sh_s;  // log2(32-column chunks per quantisation group)
+  int dn_sh_r, dn_sh_s;
+  int add_residual;
+  int dn_rw, d_model;              // host side only (the kernels get them as leading parameters)
 };
+
+// The routing inputs and the few numbers a wave needs for its first loads are not in this struct:
+// they are the kernels' leading scalar parameters (RouteIn; rec, h, unit shares), which the
+// hardware hands to a wave in registers at launch (kernel-argument preload), so those loads are
+// issued in the first instructions without waiting for a kernel-argument fetch.
+struct RouteIn {
+  const float* logits; const float* bias; const uint8_t* mask;   // [E] each; bias / mask may be null
+  int E, k, do_route;              // do_route 0: idx_in / w_in of DecodeArgs hold the decision
+};
+
+// Kernel-argument fetch: KARGS_TOUCH issues one scalar load per 64-byte line of the argument
+// segment (eight lines) into scratch registers, KARGS_WAIT waits for them; afterwards the
+// compiler's own argument loads hit the scalar cache.  The scratch registers stay reserved between
+// the two statements, so nothing can be overwritten by a load that is still in flight.
+struct KargTouch { unsigned t[7]; };
+#define KARGS_TOUCH(kt)                                                                                                   \
+  asm volatile("s_load_dword %0, %7, 0x40\n\ts_load_dword %1, %7, 0x80\n\ts_load_dword %2, %7, 0xc0\n\t"               \
+               "s_load_dword %3, %7, 0x100\n\ts_load_dword %4, %7, 0x140\n\ts_load_dword %5, %7, 0x180\n\t"            \
+               "s_load_dword %6, %7, 0x1c0"                                                                               \
+               : "=&s"(kt.t[0]), "=&s"(kt.t[1]), "=&s"(kt.t[2]), "=&s"(kt.t[3]), "=&s"(kt.t[4]), "=&s"(kt.t[5]), "=&s"(kt.t[6])  \
+               : "s"(__builtin_amdgcn_kernarg_segment_ptr()))
+#define KARGS_WAIT(kt)                                                                                                    \
+  asm volatile("s_waitcnt lgkmcnt(0)" ::"s"(kt.t[0]), "s"(kt.t[1]), "s"(kt.t[2]), "s"(kt.t[3]), "s"(kt.t[4]), "s"(kt.t[5]),   \
+               "s"(kt.t[6])                                                                                               \
+               : "memory")
 
 __device__ __forceinline__ void lds_barrier() {
   // orders LDS traffic only; outstanding global loads stay in flight across it
@@ -87,6 +123,58 @@ __device__ __forceinline__ float wave_sum_to63(float v) {
 }
 template <int CTRL> __device__ __forceinline__ int quad_xchg(int v) {
   return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+
+// ---------------------------------------------------------------------------------- buffer addressing
+// Every bank section is read through a buffer resource: address = section base + a wave-uniform
+// byte offset (scalar register) + a small per-lane offset.  A lane (or a whole load) that has
+// nothing to read gets the per-lane offset DEC_OOB, which the hardware range check turns into
+// "return 0, touch no memory".  So every load below is unconditional, the issue code is straight
+// line, and the compiler can count outstanding loads exactly (partial s_waitcnt instead of
+// waiting for everything).  A zero scale makes a lane's contribution exactly 0.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+#define DEC_OOB 0x80000000u
+
+struct SecRsrc { __amdgpu_buffer_rsrc_t msb, lsb, zp, sc; };
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ SecRsrc make_sec(const MatK& m, int n_experts) {
+  SecRsrc r;
+  r.msb = make_rsrc(m.msb, (unsigned)n_experts * m.ps32);
+  r.lsb = make_rsrc(m.lsb, (unsigned)n_experts * m.ps32);
+  r.zp = make_rsrc(m.zp, (unsigned)n_experts * m.zs32);
+  r.sc = make_rsrc(m.sc, (unsigned)n_experts * m.ss32);
+  return r;
+}
+__device__ __forceinline__ uint4 bload128(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint32_t bload32(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+  return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
+}
+__device__ __forceinline__ uint32_t bload8(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+  return __builtin_amdgcn_raw_buffer_load_b8(r, (int)voff, (int)soff, 0);
+}
+
+// Scale of element `elem + g` of an expert's scale block (block_off = its byte offset in the
+// section), fetched as the aligned dword that contains it; `odd` tells which half holds a 16-bit
+// scale.  live = false -> nothing is read and the scale is 0.
+template <int SCB>
+__device__ __forceinline__ uint32_t load_scale_raw(__amdgpu_buffer_rsrc_t sc, unsigned block_off, unsigned elem, int g,
+                                                   bool live, int& odd) {
+  if (SCB) {
+    const int t = (int)(elem & 1u) + g;
+    odd = t & 1;
+    return bload32(sc, live ? (unsigned)((t >> 1) << 2) : DEC_OOB, block_off + (elem >> 1) * 4u);
+  }
+  odd = 0;
+  return bload32(sc, live ? (unsigned)(g << 2) : DEC_OOB, block_off + elem * 4u);
+}
+template <int SCB> __device__ __forceinline__ float scale_val(uint32_t raw, int odd) {
+  return SCB ? __uint_as_float(odd ? (raw & 0xFFFF0000u) : (raw << 16)) : __uint_as_float(raw);
 }
 
 // ---------------------------------------------------------------------------------- lane operands
@@ -262,58 +350,6 @@ __device__ __forceinline__ void load_xr(XR<ACT>& x, const uint8_t* vec, const fl
   }
 }
 
-// ---------------------------------------------------------------------------------- buffer addressing
-// Every bank section is read through a buffer resource: address = section base + a wave-uniform
-// byte offset (scalar register) + a small per-lane offset.  A lane (or a whole load) that has
-// nothing to read gets the per-lane offset DEC_OOB, which the hardware range check turns into
-// "return 0, touch no memory".  So every load below is unconditional, the issue code is straight
-// line, and the compiler can count outstanding loads exactly (partial s_waitcnt instead of
-// waiting for everything).  A zero scale makes a lane's contribution exactly 0.
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-#define DEC_OOB 0x80000000u
-
-struct SecRsrc { __amdgpu_buffer_rsrc_t msb, lsb, zp, sc; };
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
-}
-__device__ __forceinline__ SecRsrc make_sec(const MatDev& m, int n_experts) {
-  SecRsrc r;
-  r.msb = make_rsrc(m.msb, (unsigned)n_experts * m.ps32);
-  r.lsb = make_rsrc(m.lsb, (unsigned)n_experts * m.ps32);
-  r.zp = make_rsrc(m.zp, (unsigned)n_experts * m.zs32);
-  r.sc = make_rsrc(m.sc, (unsigned)n_experts * m.ss32);
-  return r;
-}
-__device__ __forceinline__ uint4 bload128(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
-  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
-  return make_uint4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ uint32_t bload32(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
-  return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
-}
-__device__ __forceinline__ uint32_t bload8(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
-  return __builtin_amdgcn_raw_buffer_load_b8(r, (int)voff, (int)soff, 0);
-}
-
-// Scale of element `elem + g` of an expert's scale block (block_off = its byte offset in the
-// section), fetched as the aligned dword that contains it; `odd` tells which half holds a 16-bit
-// scale.  live = false -> nothing is read and the scale is 0.
-template <int SCB>
-__device__ __forceinline__ uint32_t load_scale_raw(__amdgpu_buffer_rsrc_t sc, unsigned block_off, unsigned elem, int g,
-                                                   bool live, int& odd) {
-  if (SCB) {
-    const int t = (int)(elem & 1u) + g;
-    odd = t & 1;
-    return bload32(sc, live ? (unsigned)((t >> 1) << 2) : DEC_OOB, block_off + (elem >> 1) * 4u);
-  }
-  odd = 0;
-  return bload32(sc, live ? (unsigned)(g << 2) : DEC_OOB, block_off + elem * 4u);
-}
-template <int SCB> __device__ __forceinline__ float scale_val(uint32_t raw, int odd) {
-  return SCB ? __uint_as_float(odd ? (raw & 0xFFFF0000u) : (raw << 16)) : __uint_as_float(raw);
-}
-
 // ---------------------------------------------------------------------------------- routing by one wave
 template <int CTRL, int ROWM, int BANKM> __device__ __forceinline__ uint32_t dpp_umax(uint32_t v) {
   const uint32_t t = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROWM, BANKM, true);
@@ -342,24 +378,28 @@ __device__ __forceinline__ float unorderable(uint32_t o) {
 // expert e; the loads are issued by route_load so that they overlap other work.
 struct RouteRegs { float z[4]; float b[4]; int mk[4]; };
 
-__device__ __forceinline__ void route_load(const DecodeArgs& a, int lane, RouteRegs& r) {
+// Unconditional loads: an absent input is a buffer of zero records, which reads as 0.
+__device__ __forceinline__ void route_load(const RouteIn& in, int lane, RouteRegs& r) {
+  const unsigned E = (unsigned)in.E;
+  const __amdgpu_buffer_rsrc_t rz = make_rsrc(in.logits, in.do_route ? E * 4u : 0u);
+  const __amdgpu_buffer_rsrc_t rb = make_rsrc(in.bias, (in.do_route && in.bias) ? E * 4u : 0u);
+  const __amdgpu_buffer_rsrc_t rm = make_rsrc(in.mask, (in.do_route && in.mask) ? E : 0u);
 #pragma unroll
   for (int j = 0; j < 4; j++) {
-    const int e = lane + 64 * j;
-    const bool ok = e < a.E;
-    r.z[j] = (ok && a.do_route) ? a.logits[e] : 0.0f;
-    r.b[j] = (ok && a.do_route && a.bias) ? a.bias[e] : 0.0f;
-    r.mk[j] = (ok && a.mask) ? a.mask[e] : 3;
+    const unsigned e = (unsigned)(lane + 64 * j);
+    r.z[j] = __uint_as_float(bload32(rz, e * 4u, 0));
+    r.b[j] = __uint_as_float(bload32(rb, e * 4u, 0));
+    r.mk[j] = (int)bload8(rm, e, 0);
   }
 }
 
 // Fills rec.sel / rec.prec / rec.w (LDS) for the k routed slots.  NJ = experts per lane.
 template <int NJ>
-__device__ void route_compute(const DecodeArgs& a, int lane, RouteRegs& rr, RouteRec& rec) {
-  const int E = a.E, k = a.k;
+__device__ void route_compute(const RouteIn& in, const DecodeArgs& a, int lane, RouteRegs& rr, RouteRec& rec) {
+  const int E = in.E, k = in.k;
   int mysel = 0, mymask = 3;
   float myw = 0.0f;
-  if (a.do_route) {
+  if (in.do_route) {
     uint32_t ord[NJ];              // orderable biased score; 0 = absent or already taken
     float p[NJ];
     uint32_t zmax_o = 0;
@@ -391,7 +431,7 @@ __device__ void route_compute(const DecodeArgs& a, int lane, RouteRegs& rr, Rout
         ls = e_star & 63; js = e_star >> 6;
       }
       float pw = 0.0f;
-      int mk = 3;
+      int mk = 0;
 #pragma unroll
       for (int j = 0; j < NJ; j++) {
         const float t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p[j]), ls));
@@ -400,15 +440,18 @@ __device__ void route_compute(const DecodeArgs& a, int lane, RouteRegs& rr, Rout
         if (js == j && lane == ls) ord[j] = 0u;
       }
       psum += pw;
-      if (lane == r) { myp = pw; mysel = ls + 64 * js; mymask = mk; }
+      if (lane == r) { myp = pw; mysel = ls + 64 * js; mymask = in.mask ? mk : 3; }
     }
     myw = myp / den;
     if (a.norm_topk) myw = myw / (psum / den);
     myw *= a.routed_scale;
-  } else if (lane < k) {
-    mysel = min(max(a.idx_in[lane], 0), E - 1);
-    myw = a.w_in[lane];
-    mymask = a.mask ? a.mask[mysel] : 3;
+  } else {
+    const unsigned vo = lane < k ? (unsigned)lane * 4u : DEC_OOB;
+    const int idx = (int)bload32(make_rsrc(a.idx_in, (unsigned)k * 4u), vo, 0);
+    myw = __uint_as_float(bload32(make_rsrc(a.w_in, (unsigned)k * 4u), vo, 0));
+    mysel = min(max(idx, 0), E - 1);
+    const int mk = (int)bload8(make_rsrc(in.mask, in.mask ? (unsigned)E : 0u), lane < k ? (unsigned)mysel : DEC_OOB, 0);
+    mymask = in.mask ? mk : 3;
   }
   if (lane < k) {
     rec.sel[lane] = mysel;
@@ -438,13 +481,28 @@ __device__ __forceinline__ PairRef pair_ref(int e, int n_entries, int cap, int i
 }
 
 template <int ACT, int SCB>
-__global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, const float* bias, const uint8_t* mask, const void* x_in,
+                                                        int E, int k, int do_route, int d_model, DecodeArgs a) {
   __shared__ RouteRec rec;
   __shared__ __align__(16) uint8_t xvec[2048 * StageTraits<ACT>::BYTES_PER_VAL];
   __shared__ float2 xcs[64];
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
-  const int d = a.d_model, C = d >> 5;
-  const int k = a.has_routed ? a.k : 0;
+  const RouteIn in{logits, bias, mask, E, k, do_route};
+  const int d = d_model, C = d >> 5;
+  // ---- first instructions: the loads that need only the leading parameters -- x (the four waves
+  // after wave 0 stage it) and the routing inputs (wave 0) -- then the fetch of all other
+  // arguments.  The explicit wait closes these loads for every wave: a load still pending where
+  // control flow merges would make all later code wait for every load.
+  const int xt = tid - 64;
+  const bool stager = xt >= 0 && xt < 4 * C, router = wave == 0 && k > 0;
+  KargTouch kt;
+  KARGS_TOUCH(kt);
+  Raw8 xraw = {};
+  RouteRegs rr = {};
+  if (stager) load8_raw<ACT>(x_in, (size_t)xt * 8, xraw);
+  if (router) route_load(in, lane, rr);
+  KARGS_WAIT(kt);
+  __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
   const unsigned rowb32 = (unsigned)d >> 1;
   const bool live_lane = lane < C;
   const unsigned voff = live_lane ? (unsigned)lane * 16u : DEC_OOB;
@@ -456,7 +514,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
 
   // eight unconditional loads per row pair (dead pairs / lanes / LSB planes read nothing); the small
   // metadata loads of a batch go first, so that a pair's arithmetic waits for its own planes only
-  auto issue_meta = [&](int j, bool valid, int r, const SecRsrc& R, const MatDev& md, int e, int sh) {
+  auto issue_meta = [&](int j, bool valid, int r, const SecRsrc& R, const MatK& md, int e, int sh) {
     const unsigned ng = (unsigned)md.ng;
     const int g = lane >> sh;
     const bool live = valid && live_lane;
@@ -467,7 +525,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
     sg[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, (unsigned)(2 * r) * ng, g, live, og[j]);
     su[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, (unsigned)(2 * r + 1) * ng, g, live, ou[j]);
   };
-  auto issue_planes = [&](int j, bool valid, int r, const SecRsrc& R, const MatDev& md, int e, int prec) {
+  auto issue_planes = [&](int j, bool valid, int r, const SecRsrc& R, const MatK& md, int e, int prec) {
     const unsigned po = (unsigned)e * md.ps32 + (unsigned)(2 * r) * rowb32;
     const unsigned vo = valid ? voff : DEC_OOB, vl = (valid && prec) ? voff : DEC_OOB;
     gm[j] = bload128(R.msb, vo, po);
@@ -483,22 +541,15 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
     if (lane == 63 && hidx >= 0) a.h[hidx] = av / (1.0f + __expf(-av)) * uv;
   };
 
-  // ---- prologue: x into LDS (the four waves after wave 0), routing decision into LDS (wave 0), weight
-  // of the shared experts (a wave of block 0).  Each of these waits for its own loads right here: a
-  // load still pending where control flow merges would make all later code wait for every load.
-  const int xt = tid - 64;
-  if (xt >= 0 && xt < 4 * C) {
-    Raw8 xraw;
-    load8_raw<ACT>(a.x, (size_t)xt * 8, xraw);
+  // ---- prologue: x into LDS, routing decision into LDS, weight of the shared experts (a wave of block 0)
+  if (stager) {
     float xv[8];
     unpack8<ACT>(xraw, xv);
     stage_regs<ACT>(xv, C, xt >> 2, xt & 3, xvec, xcs);
   }
-  if (wave == 0 && k > 0) {
-    RouteRegs rr;
-    route_load(a, lane, rr);
-    if (a.E <= 64) route_compute<1>(a, lane, rr, rec);
-    else route_compute<4>(a, lane, rr, rec);
+  if (router) {
+    if (E <= 64) route_compute<1>(in, a, lane, rr, rec);
+    else route_compute<4>(in, a, lane, rr, rec);
   }
   if (blockIdx.x == 0 && wave == 5) {
     float g = 1.0f;
@@ -524,17 +575,17 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
 
   // ---- shared-expert waves: rows in flight before the routing decision exists
   if (!routed_wave) {
-    const SecRsrc RS = make_sec(a.shared.gu, a.shared.n_experts);
+    const SecRsrc RS = make_sec(a.sgu, a.n_shared);
 #pragma unroll
     for (int j = 0; j < DEC_MAXP; j++) {
       const PairRef p = entry(j);
-      issue_meta(j, p.valid, p.r, RS, a.shared.gu, p.slot, a.gu_sh_s);
+      issue_meta(j, p.valid, p.r, RS, a.sgu, p.slot, a.gu_sh_s);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < DEC_MAXP; j++) {
       const PairRef p = entry(j);
-      issue_planes(j, p.valid, p.r, RS, a.shared.gu, p.slot, 1);
+      issue_planes(j, p.valid, p.r, RS, a.sgu, p.slot, 1);
     }
   }
 
@@ -557,7 +608,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
     pr[j] = 1;
   }
   if (routed_wave) {
-    const SecRsrc RR = make_sec(a.routed.gu, a.routed.n_experts);
+    const SecRsrc RR = make_sec(a.rgu, a.E);
     int ex[DEC_MAXP];
 #pragma unroll
     for (int j = 0; j < DEC_MAXP; j++) {
@@ -565,13 +616,13 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
       const int slot = p.valid ? p.slot : 0;
       pr[j] = uni(rec.prec[slot]);
       ex[j] = uni(rec.sel[slot]);
-      issue_meta(j, p.valid, p.r, RR, a.routed.gu, ex[j], a.gu_sh_r);
+      issue_meta(j, p.valid, p.r, RR, a.rgu, ex[j], a.gu_sh_r);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < DEC_MAXP; j++) {
       const PairRef p = entry(j);
-      issue_planes(j, p.valid, p.r, RR, a.routed.gu, ex[j], pr[j]);
+      issue_planes(j, p.valid, p.r, RR, a.rgu, ex[j], pr[j]);
     }
   }
   XR<ACT> x = {};
@@ -586,13 +637,13 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
     int prec = 1;
     if (routed_wave) {
       prec = uni(rec.prec[slot]);
-      const SecRsrc RR = make_sec(a.routed.gu, a.routed.n_experts);
-      issue_meta(0, p.valid, p.r, RR, a.routed.gu, uni(rec.sel[slot]), a.gu_sh_r);
-      issue_planes(0, p.valid, p.r, RR, a.routed.gu, uni(rec.sel[slot]), prec);
+      const SecRsrc RR = make_sec(a.rgu, a.E);
+      issue_meta(0, p.valid, p.r, RR, a.rgu, uni(rec.sel[slot]), a.gu_sh_r);
+      issue_planes(0, p.valid, p.r, RR, a.rgu, uni(rec.sel[slot]), prec);
     } else {
-      const SecRsrc RS = make_sec(a.shared.gu, a.shared.n_experts);
-      issue_meta(0, p.valid, p.r, RS, a.shared.gu, slot, a.gu_sh_s);
-      issue_planes(0, p.valid, p.r, RS, a.shared.gu, slot, 1);
+      const SecRsrc RS = make_sec(a.sgu, a.n_shared);
+      issue_meta(0, p.valid, p.r, RS, a.sgu, slot, a.gu_sh_s);
+      issue_planes(0, p.valid, p.r, RS, a.sgu, slot, 1);
     }
     finish(0, prec, x, p.valid ? hidx_of(p) : -1);
   }
@@ -602,8 +653,9 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(DecodeArgs a) {
 // A work-group owns DEC_RPW output rows.  Units = (slot, k-slice, row); unit u of a list: row =
 // u % 8, combo = u / 8 -> (slot, k-slice) = (combo / ks, combo % ks).  Waves [0, dn_rw) take the
 // routed list, the other waves the shared-expert list, whose loads are in flight from the first
-// instruction.  A wave of a group of n takes a contiguous share of its list, so that consecutive
-// units mostly reuse the same h chunk.  The routed waves also stage h (all waves do when there is
+// instruction.  A wave of a group of n takes a contiguous share of its list (q units, the first r
+// waves one more; q and r come from the host), so that consecutive units mostly reuse the same h
+// chunk.  The routed waves also stage h (all waves do when there is
 // no routed bank); each routed wave reads the routing record itself, so nothing waits on LDS
 // before the plane loads are issued.
 struct UnitRef { int slot, ks, row; };
@@ -620,17 +672,41 @@ __device__ __forceinline__ UnitRef unit_ref(int u, int ks_n, int inv_ks) {
 #define DEC_HQ 3      // h words of 8 values each stager thread loads up front
 
 template <int ACT, int SCB>
-__global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_bytes) {
+__global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const float* h, int total_f, int dn_rw, int ru_q, int ru_r,
+                                                      int su_q, int su_r, DecodeArgs a, int lds_vec_bytes) {
   extern __shared__ __align__(16) uint8_t dyn[];     // [h vectors][chunk figures][unit partials]
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
-  const int k = a.has_routed ? a.k : 0;
+  const bool routed_wave = wave < dn_rw;
+  KargTouch kt;
+  KARGS_TOUCH(kt);
+  // ---- first instructions: the loads that need only the leading parameters -- in the routed waves
+  // the h words they stage and the routing record (sizeof(RouteRec) == 64 words) -- then the fetch
+  // of all other arguments.  The explicit wait closes these loads for every wave (the routed waves
+  // need the record at once anyway).
+  const __amdgpu_buffer_rsrc_t RH = make_rsrc(h, (unsigned)total_f * 4u);
+  uint4 hraw[DEC_HQ][2] = {};
+  auto load_h = [&](int st_first, int st_n) {          // unconditional: items past the end read nothing
+#pragma unroll
+    for (int q = 0; q < DEC_HQ; q++) {
+      const int item = st_first + q * st_n;
+      const unsigned vo = item < (total_f >> 3) ? (unsigned)item * 32u : DEC_OOB;
+      hraw[q][0] = bload128(RH, vo, 0);
+      hraw[q][1] = bload128(RH, vo, 16);
+    }
+  };
+  int rec_word = 0;
+  if (routed_wave) {
+    load_h(tid, dn_rw * 64);
+    rec_word = rec[lane];
+  }
+  KARGS_WAIT(kt);
+  __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+  const int k = a.k;
   const int nsf = a.n_shared * a.f_s;
-  const int total_f = nsf + k * a.f_r;
   uint8_t* hvec = dyn;
   float2* hcs = (float2*)(dyn + lds_vec_bytes);
   float* part = (float*)(hcs + (total_f >> 5));     // shared-expert units first, then routed units
   const int n0 = blockIdx.x * DEC_RPW;
-  const bool routed_wave = wave < a.dn_rw;
   const int n_su = a.n_shared * a.ks_s * DEC_RPW, n_ru = k * a.ks_r * DEC_RPW;
 
   uint4 wm[DEC_MAXU], wl[DEC_MAXU];
@@ -638,7 +714,7 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_
   int so[DEC_MAXU];
 
   // four unconditional loads per unit, the two small ones of a whole batch first
-  auto issue_meta = [&](int j, bool valid, const UnitRef& u, int f, const SecRsrc& R, const MatDev& md, int e, int sh) {
+  auto issue_meta = [&](int j, bool valid, const UnitRef& u, int f, const SecRsrc& R, const MatK& md, int e, int sh) {
     const int cw = min(64, (f >> 5) - u.ks * 64);
     const bool live = valid && lane < cw;
     const int g = lane >> sh;
@@ -646,7 +722,7 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_
     zz[j] = bload8(R.zp, live ? (unsigned)g : DEC_OOB, (unsigned)e * md.zs32 + elem);
     ss[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, elem, g, live, so[j]);
   };
-  auto issue_planes = [&](int j, bool valid, const UnitRef& u, int f, const SecRsrc& R, const MatDev& md, int e, int prec) {
+  auto issue_planes = [&](int j, bool valid, const UnitRef& u, int f, const SecRsrc& R, const MatK& md, int e, int prec) {
     const int cw = min(64, (f >> 5) - u.ks * 64);
     const bool live = valid && lane < cw;
     const unsigned po = (unsigned)e * md.ps32 + (unsigned)(n0 + u.row) * ((unsigned)f >> 1) + (unsigned)u.ks * 1024u;
@@ -668,7 +744,6 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_
   };
 
   // h words -> LDS; `item` = index of a group of 8 consecutive h values
-  const __amdgpu_buffer_rsrc_t RH = make_rsrc(a.h, (unsigned)total_f * 4u);
   auto stage_h = [&](const uint4& r0, const uint4& r1, int item) {
     const int i0 = item * 8;
     int voffs, f;                                      // which vector: shared experts first, then routed slots
@@ -680,16 +755,6 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_
     unpack8<SMOE_F32>(raw, hv);
     stage_regs<ACT>(hv, f >> 5, local >> 5, (local >> 3) & 3, hvec + (size_t)voffs * StageTraits<ACT>::BYTES_PER_VAL,
                     hcs + (voffs >> 5));
-  };
-  uint4 hraw[DEC_HQ][2];
-  auto load_h = [&](int st_first, int st_n) {          // unconditional: items past the end read nothing
-#pragma unroll
-    for (int q = 0; q < DEC_HQ; q++) {
-      const int item = st_first + q * st_n;
-      const unsigned vo = item < (total_f >> 3) ? (unsigned)item * 32u : DEC_OOB;
-      hraw[q][0] = bload128(RH, vo, 0);
-      hraw[q][1] = bload128(RH, vo, 16);
-    }
   };
   auto stage_all = [&](int st_first, int st_n) {
 #pragma unroll
@@ -709,10 +774,8 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_
     // routed waves: h words and the routing record first, rows as soon as the record is here, then h
     // into LDS while the rows stream in.  sel / prec / w of slot s sit in words s, 16+s, 32+s of the
     // record, gamma in word 48.
-    const int u_lo = n_ru * wave / a.dn_rw, u_hi = n_ru * (wave + 1) / a.dn_rw;
-    load_h(tid, a.dn_rw * 64);
-    const int rec_word = ((const int*)a.rec)[lane];                      // sizeof(RouteRec) == 64 words
-    const SecRsrc RR = make_sec(a.routed.dn, a.routed.n_experts);
+    const int u_lo = wave * ru_q + min(wave, ru_r), u_hi = u_lo + ru_q + (wave < ru_r ? 1 : 0);
+    const SecRsrc RR = make_sec(a.rdn, a.E);
     int pr[DEC_MAXU], ex[DEC_MAXU];
     float wt[DEC_MAXU];
 #pragma unroll
@@ -722,17 +785,17 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_
       ex[j] = __builtin_amdgcn_readlane(rec_word, u.slot);
       pr[j] = __builtin_amdgcn_readlane(rec_word, SMOE_MAX_TOPK + u.slot);
       wt[j] = __int_as_float(__builtin_amdgcn_readlane(rec_word, 2 * SMOE_MAX_TOPK + u.slot));
-      issue_meta(j, valid, u, a.f_r, RR, a.routed.dn, ex[j], a.dn_sh_r);
+      issue_meta(j, valid, u, a.f_r, RR, a.rdn, ex[j], a.dn_sh_r);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < DEC_MAXU; j++) {
       const bool valid = u_lo + j < u_hi;
       const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_r, a.inv_ks_r);
-      issue_planes(j, valid, u, a.f_r, RR, a.routed.dn, ex[j], pr[j]);
+      issue_planes(j, valid, u, a.f_r, RR, a.rdn, ex[j], pr[j]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    stage_all(tid, a.dn_rw * 64);
+    stage_all(tid, dn_rw * 64);
     if (tid == 0) *gamma_lds = __int_as_float(__builtin_amdgcn_readlane(rec_word, 3 * SMOE_MAX_TOPK));
     lds_barrier();
     XR<ACT> x = {};
@@ -748,35 +811,35 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_
       const int e = __builtin_amdgcn_readlane(rec_word, u.slot);
       const int prec = __builtin_amdgcn_readlane(rec_word, SMOE_MAX_TOPK + u.slot);
       const float w1 = __int_as_float(__builtin_amdgcn_readlane(rec_word, 2 * SMOE_MAX_TOPK + u.slot));
-      issue_meta(0, true, u, a.f_r, RR, a.routed.dn, e, a.dn_sh_r);
-      issue_planes(0, true, u, a.f_r, RR, a.routed.dn, e, prec);
+      issue_meta(0, true, u, a.f_r, RR, a.rdn, e, a.dn_sh_r);
+      issue_planes(0, true, u, a.f_r, RR, a.rdn, e, prec);
       finish(0, true, u, a.f_r, nsf + u.slot * a.f_r, prec, w1, x, cur, uu / DEC_RPW, n_su + uu);
     }
   } else {
     // shared-expert waves: rows in flight from the first instruction; without routed waves they also
     // stage h
-    const int sw = wave - a.dn_rw, n_sw = DEC_NW - a.dn_rw;
-    const int u_lo = n_su * sw / n_sw, u_hi = n_su * (sw + 1) / n_sw;
-    const bool stage = a.dn_rw == 0;
+    const int sw = wave - dn_rw;
+    const int u_lo = sw * su_q + min(sw, su_r), u_hi = u_lo + su_q + (sw < su_r ? 1 : 0);
+    const bool stage = dn_rw == 0;
     if (stage) load_h(tid, DEC_NT);
-    const SecRsrc RS = make_sec(a.shared.dn, a.shared.n_experts);
+    const SecRsrc RS = make_sec(a.sdn, a.n_shared);
 #pragma unroll
     for (int j = 0; j < DEC_MAXU; j++) {
       const bool valid = u_lo + j < u_hi;
       const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_s, a.inv_ks_s);
-      issue_meta(j, valid, u, a.f_s, RS, a.shared.dn, u.slot, a.dn_sh_s);
+      issue_meta(j, valid, u, a.f_s, RS, a.sdn, u.slot, a.dn_sh_s);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < DEC_MAXU; j++) {
       const bool valid = u_lo + j < u_hi;
       const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_s, a.inv_ks_s);
-      issue_planes(j, valid, u, a.f_s, RS, a.shared.dn, u.slot, 1);
+      issue_planes(j, valid, u, a.f_s, RS, a.sdn, u.slot, 1);
     }
     __builtin_amdgcn_sched_barrier(0);
     if (stage) {
       stage_all(tid, DEC_NT);
-      if (tid == 0) *gamma_lds = a.rec->gamma;
+      if (tid == 0) *gamma_lds = __int_as_float(rec[3 * SMOE_MAX_TOPK]);
     }
     lds_barrier();
     const float gamma = *gamma_lds;
@@ -790,8 +853,8 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(DecodeArgs a, int lds_vec_
     }
     for (int uu = u_lo + DEC_MAXU; uu < u_hi; uu++) {
       const UnitRef u = unit_ref(uu, a.ks_s, a.inv_ks_s);
-      issue_meta(0, true, u, a.f_s, RS, a.shared.dn, u.slot, a.dn_sh_s);
-      issue_planes(0, true, u, a.f_s, RS, a.shared.dn, u.slot, 1);
+      issue_meta(0, true, u, a.f_s, RS, a.sdn, u.slot, a.dn_sh_s);
+      issue_planes(0, true, u, a.f_s, RS, a.sdn, u.slot, 1);
       finish(0, true, u, a.f_s, u.slot * a.f_s, 1, gamma, x, cur, uu / DEC_RPW, uu);
     }
   }
@@ -814,7 +877,7 @@ static int ilog2_exact(int v) {
 }
 
 template <int ACT, int SCB>
-static int launch_decode_t(smoe_ctx* ctx, DecodeArgs& a, int total_f, int n_wg) {
+static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int total_f, int n_wg) {
   const size_t vec_bytes = (size_t)total_f * StageTraits<ACT>::BYTES_PER_VAL;
   const size_t n_units = (size_t)(a.n_shared * a.ks_s + a.k * a.ks_r) * DEC_RPW;
   const size_t lds = vec_bytes + (size_t)(total_f / 32) * 8 + n_units * 4 + 16;      // + the shared experts' weight
@@ -831,22 +894,30 @@ static int launch_decode_t(smoe_ctx* ctx, DecodeArgs& a, int total_f, int n_wg) 
   }
   std::vector<hipEvent_t>* evs = (ctx->timing && ctx->timing_events) ? (std::vector<hipEvent_t>*)ctx->timing_events : nullptr;
   const dim3 g1(n_wg), g2(a.d_model / DEC_RPW), blk(DEC_NT);
+  // down kernel: contiguous unit shares of the routed / shared-expert waves
+  const int n_ru = a.k * a.ks_r * DEC_RPW, n_su = a.n_shared * a.ks_s * DEC_RPW, n_sw = DEC_NW - a.dn_rw;
+  const int ru_q = a.dn_rw ? n_ru / a.dn_rw : 0, ru_r = a.dn_rw ? n_ru % a.dn_rw : 0;
+  const int su_q = n_sw ? n_su / n_sw : 0, su_r = n_sw ? n_su % n_sw : 0;
+  const int* recw = (const int*)a.rec;
   if (evs) {
     // measurement aid: the dispatches themselves carry start/stop events (no extra marker packets)
     hipEvent_t ev[4];
     for (int i = 0; i < 4; i++) { HIPCHK(ctx, hipEventCreate(&ev[i])); evs->push_back(ev[i]); }
-    hipExtLaunchKernelGGL((gateup_kernel<ACT, SCB>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, a);
-    hipExtLaunchKernelGGL((down_kernel<ACT, SCB>), g2, blk, (unsigned)lds, ctx->stream, ev[2], ev[3], 0, a, (int)vec_bytes);
+    hipExtLaunchKernelGGL((gateup_kernel<ACT, SCB>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
+                          in.E, in.k, in.do_route, a.d_model, a);
+    hipExtLaunchKernelGGL((down_kernel<ACT, SCB>), g2, blk, (unsigned)lds, ctx->stream, ev[2], ev[3], 0, recw, (const float*)a.h,
+                          total_f, a.dn_rw, ru_q, ru_r, su_q, su_r, a, (int)vec_bytes);
   } else {
-    gateup_kernel<ACT, SCB><<<g1, blk, 0, ctx->stream>>>(a);
-    down_kernel<ACT, SCB><<<g2, blk, lds, ctx->stream>>>(a, (int)vec_bytes);
+    gateup_kernel<ACT, SCB><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, a);
+    down_kernel<ACT, SCB><<<g2, blk, lds, ctx->stream>>>(recw, (const float*)a.h, total_f, a.dn_rw, ru_q, ru_r, su_q, su_r, a,
+                                                         (int)vec_bytes);
   }
   HIPCHK(ctx, hipGetLastError());
   return SMOE_OK;
 }
 
 static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, int act_dtype, int k,
-                         DecodeArgs& a) {
+                         RouteIn in, DecodeArgs& a) {
   if (!routed && !shared) return SMOE_EINVAL;
   if (routed && routed->device != ctx->device) return SMOE_EINVAL;
   if (shared && shared->device != ctx->device) return SMOE_EINVAL;
@@ -869,10 +940,12 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   if ((routed && !(routed->dev.gu.fits32 && routed->dev.dn.fits32)) || (shared && !(shared->dev.gu.fits32 && shared->dev.dn.fits32)))
     return SMOE_ENOTIMPL;                                      // decode kernels address a bank section with 32-bit offsets
   HIPCHK(ctx, hipSetDevice(ctx->device));
-  if (routed) a.routed = routed->dev;
-  if (shared) a.shared = shared->dev;
-  a.has_routed = routed != nullptr; a.n_shared = ns; a.k = k;
+  auto matk = [](const MatDev& m) { return MatK{m.msb, m.lsb, m.zp, m.sc, m.ps32, m.zs32, m.ss32, m.ng}; };
+  if (routed) { a.rgu = matk(routed->dev.gu); a.rdn = matk(routed->dev.dn); }
+  if (shared) { a.sgu = matk(shared->dev.gu); a.sdn = matk(shared->dev.dn); }
+  a.n_shared = ns; a.k = k;
   a.E = routed ? routed->desc.n_experts : 0;
+  in.E = a.E; in.k = k;
   a.rec = (RouteRec*)(ctx->ws + WS_REC_OFF);
   a.h = (float*)(ctx->ws + WS_H_OFF);
   a.d_model = d_model;
@@ -910,8 +983,8 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   a.dn_rw = split(k * a.ks_r * DEC_RPW, ns * a.ks_s * DEC_RPW);
   const int scb = routed ? routed->dev.sc_bf16 : shared->dev.sc_bf16;
   if (routed && shared && routed->dev.sc_bf16 != shared->dev.sc_bf16) return SMOE_ENOTIMPL;   // one scale dtype per layer
-  if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1>(ctx, a, total_f, n_wg) : launch_decode_t<SMOE_F32, 0>(ctx, a, total_f, n_wg);
-  return scb ? launch_decode_t<SMOE_BF16, 1>(ctx, a, total_f, n_wg) : launch_decode_t<SMOE_BF16, 0>(ctx, a, total_f, n_wg);
+  if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1>(ctx, in, a, total_f, n_wg) : launch_decode_t<SMOE_F32, 0>(ctx, in, a, total_f, n_wg);
+  return scb ? launch_decode_t<SMOE_BF16, 1>(ctx, in, a, total_f, n_wg) : launch_decode_t<SMOE_BF16, 0>(ctx, in, a, total_f, n_wg);
 }
 
 extern "C" int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
@@ -924,9 +997,10 @@ extern "C" int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smo
   if (!aligned16(x_dev) || !aligned16(y_dev) || !aligned16(idx_dev) || !aligned16(w_dev) || !aligned16(shared_gate_w_dev))
     return SMOE_EALIGN;
   DecodeArgs a{};
-  a.do_route = 0; a.idx_in = idx_dev; a.w_in = w_dev; a.mask = slice_mask_dev; a.tau = tau_head;
+  a.idx_in = idx_dev; a.w_in = w_dev; a.tau = tau_head;
   a.x = x_dev; a.shared_gate_w = shared_gate_w_dev; a.prec_out = prec_out_dev; a.y = y_dev; a.add_residual = add_residual;
-  return launch_decode(ctx, routed, shared, act_dtype, k, a);
+  const RouteIn in{nullptr, nullptr, slice_mask_dev, 0, 0, 0};
+  return launch_decode(ctx, routed, shared, act_dtype, k, in, a);
 }
 
 extern "C" int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
@@ -951,8 +1025,9 @@ extern "C" int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const s
     logits = zws;
   }
   DecodeArgs a{};
-  a.do_route = 1; a.logits = logits; a.bias = bias_dev; a.norm_topk = norm_topk; a.routed_scale = routed_scale;
-  a.mask = slice_mask_dev; a.tau = tau_head; a.x = x_dev; a.shared_gate_w = shared_gate_w_dev;
+  a.norm_topk = norm_topk; a.routed_scale = routed_scale;
+  a.tau = tau_head; a.x = x_dev; a.shared_gate_w = shared_gate_w_dev;
+  const RouteIn in{logits, bias_dev, slice_mask_dev, 0, 0, 1};
   a.idx_out = idx_out_dev; a.w_out = w_out_dev; a.prec_out = prec_out_dev; a.y = y_dev; a.add_residual = add_residual;
-  return launch_decode(ctx, routed, shared, act_dtype, k, a);
+  return launch_decode(ctx, routed, shared, act_dtype, k, in, a);
 }
