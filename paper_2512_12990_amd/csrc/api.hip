@@ -104,7 +104,8 @@ static size_t layout(const smoe_bank_desc* d, BankDev* b, MatOff* ogu, MatOff* o
     m[i]->cpg = d->group / 32;
     m[i]->plane_stride = (size_t)m[i]->N * m[i]->K / 2;
     m[i]->zp_stride = up16((size_t)m[i]->N * m[i]->ng);
-    m[i]->sc_stride = up16((size_t)m[i]->N * m[i]->ng * ssz);
+    m[i]->sng = (m[i]->ng + 1) & ~1;
+    m[i]->sc_stride = up16((size_t)m[i]->N * m[i]->sng * ssz);
     m[i]->ps32 = (unsigned)m[i]->plane_stride; m[i]->zs32 = (unsigned)m[i]->zp_stride; m[i]->ss32 = (unsigned)m[i]->sc_stride;
     m[i]->fits32 = (E * m[i]->plane_stride < 0x7FFF0000ull) ? 1u : 0u;
   }
@@ -171,7 +172,7 @@ extern "C" int smoe_export_codes(smoe_ctx* ctx, const smoe_bank* bank, int exper
   const int N = matrix == 2 ? m.N : m.N / 2, K = m.K, ng = m.ng;
   const size_t row_b = (size_t)K / 2, ssz = bank->dev.sc_bf16 ? 2 : 4;
   HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
-  std::vector<uint8_t> pm(m.plane_stride), pl(m.plane_stride), zp((size_t)m.N * ng), sc((size_t)m.N * ng * ssz);
+  std::vector<uint8_t> pm(m.plane_stride), pl(m.plane_stride), zp((size_t)m.N * ng), sc((size_t)m.N * m.sng * ssz);
   HIPCHK(ctx, hipMemcpy(pm.data(), m.msb + (size_t)expert * m.plane_stride, pm.size(), hipMemcpyDeviceToHost));
   HIPCHK(ctx, hipMemcpy(pl.data(), m.lsb + (size_t)expert * m.plane_stride, pl.size(), hipMemcpyDeviceToHost));
   HIPCHK(ctx, hipMemcpy(zp.data(), m.zp + (size_t)expert * m.zp_stride, zp.size(), hipMemcpyDeviceToHost));
@@ -192,10 +193,10 @@ extern "C" int smoe_export_codes(smoe_ctx* ctx, const smoe_bank* bank, int exper
       if (scale_host) {
         float f;
         if (bank->dev.sc_bf16) {
-          uint32_t u = (uint32_t)((const uint16_t*)sc.data())[sr * ng + g] << 16;
+          uint32_t u = (uint32_t)((const uint16_t*)sc.data())[sr * m.sng + g] << 16;
           memcpy(&f, &u, 4);
         } else {
-          f = ((const float*)sc.data())[sr * ng + g];
+          f = ((const float*)sc.data())[sr * m.sng + g];
         }
         scale_host[(size_t)r * ng + g] = f;
       }

@@ -15,11 +15,13 @@
 // row 2r = gate r, row 2r+1 = up r, shape [2*d_ff, d_model]; "dn": down, [d_model, d_ff]).
 // Per expert e the data starts at base + e * stride.  Planes hold two 4-bit values per byte,
 // row-major, low nibble = even column, each value n stored as n ^ 8 (= n - 8 in 4-bit two's
-// complement).  Metadata: zp uint8 [N, ng], scale [N, ng].
+// complement).  Metadata: zp uint8 [N, ng], scale [N, sng] (the first ng of a row are used).
 struct MatDev {
   const uint8_t* msb; const uint8_t* lsb; const uint8_t* zp; const uint8_t* sc;
   unsigned long long plane_stride, zp_stride, sc_stride;   // bytes per expert
   int N, K, ng, cpg;                                       // cpg = 32-column chunks per group
+  int sng;                                                 // scales per row as stored: ng rounded up to even, so that
+                                                           // every row of scales starts on a 4-byte boundary
   unsigned ps32, zs32, ss32, fits32;                       // the strides as 32-bit numbers; fits32 = every
                                                            // byte offset inside a section is below 2^31
 };

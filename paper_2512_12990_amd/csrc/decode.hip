@@ -34,11 +34,12 @@
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
-// One expert matrix family as the kernels see it (48 bytes).
+// One expert matrix family as the kernels see it (56 bytes).
 struct MatK {
   const uint8_t* msb; const uint8_t* lsb; const uint8_t* zp; const uint8_t* sc;
   unsigned ps32, zs32, ss32;       // bytes per expert in the plane / zero-point / scale sections
-  int ng;                          // quantisation groups per row
+  int ng, sng;                     // quantisation groups per row; scales stored per row (ng rounded up to even)
+  int pad0;
 };
 
 // Kernel arguments, kept compact and ordered by use: a dispatch's arguments are cold in every
@@ -84,16 +85,20 @@ struct RouteIn {
 // compiler's own argument loads hit the scalar cache.  The scratch registers stay reserved between
 // the two statements, so nothing can be overwritten by a load that is still in flight.
 struct KargTouch { unsigned t[7]; };
-#define KARGS_TOUCH(kt)                                                                                                   \
-  asm volatile("s_load_dword %0, %7, 0x40\n\ts_load_dword %1, %7, 0x80\n\ts_load_dword %2, %7, 0xc0\n\t"               \
-               "s_load_dword %3, %7, 0x100\n\ts_load_dword %4, %7, 0x140\n\ts_load_dword %5, %7, 0x180\n\t"            \
-               "s_load_dword %6, %7, 0x1c0"                                                                               \
+#define KARG_OFF(i, size) ((i) * 64 < (size) ? (i) * 64 : (size) - 4)      /* never past the last argument */
+#define KARGS_TOUCH(kt, size)                                                                                             \
+  asm volatile("s_load_dword %0, %7, %8\n\ts_load_dword %1, %7, %9\n\ts_load_dword %2, %7, %10\n\t"                    \
+               "s_load_dword %3, %7, %11\n\ts_load_dword %4, %7, %12\n\ts_load_dword %5, %7, %13\n\t"                  \
+               "s_load_dword %6, %7, %14"                                                                                 \
                : "=&s"(kt.t[0]), "=&s"(kt.t[1]), "=&s"(kt.t[2]), "=&s"(kt.t[3]), "=&s"(kt.t[4]), "=&s"(kt.t[5]), "=&s"(kt.t[6])  \
-               : "s"(__builtin_amdgcn_kernarg_segment_ptr()))
+               : "s"(__builtin_amdgcn_kernarg_segment_ptr()), "n"(KARG_OFF(1, size)), "n"(KARG_OFF(2, size)),             \
+                 "n"(KARG_OFF(3, size)), "n"(KARG_OFF(4, size)), "n"(KARG_OFF(5, size)), "n"(KARG_OFF(6, size)),          \
+                 "n"(KARG_OFF(7, size)))
 #define KARGS_WAIT(kt)                                                                                                    \
   asm volatile("s_waitcnt lgkmcnt(0)" ::"s"(kt.t[0]), "s"(kt.t[1]), "s"(kt.t[2]), "s"(kt.t[3]), "s"(kt.t[4]), "s"(kt.t[5]),   \
                "s"(kt.t[6])                                                                                               \
                : "memory")
+static_assert(sizeof(DecodeArgs) + 56 <= 8 * 64, "KARGS_TOUCH covers eight lines");
 
 __device__ __forceinline__ void lds_barrier() {
   // orders LDS traffic only; outstanding global loads stay in flight across it
@@ -252,8 +257,8 @@ __device__ __forceinline__ float lane_value(const XR<SMOE_F32>& x, const uint4& 
 // that the lanes of a wave read consecutive 16-byte pieces.  BF16: 3 pieces per chunk (the digit
 // words of XR; 64 B per chunk are reserved), F32: 8 pieces of 4 floats (128 B).  cs[c] = (chunk scale, chunk sum).
 template <int ACT> struct StageTraits;
-template <> struct StageTraits<SMOE_BF16> { enum { BYTES_PER_VAL = 2 }; };
-template <> struct StageTraits<SMOE_F32> { enum { BYTES_PER_VAL = 4 }; };
+template <> struct StageTraits<SMOE_BF16> { enum { BYTES_PER_VAL = 2, COMBO_BYTES = 64 * 48 }; };     // one 64-chunk k-slice
+template <> struct StageTraits<SMOE_F32> { enum { BYTES_PER_VAL = 4, COMBO_BYTES = 64 * 128 }; };
 
 // Eight consecutive values as loaded (no arithmetic on them, so nothing waits for the load).
 struct Raw8 { uint4 a, b; };
@@ -295,17 +300,27 @@ __device__ __forceinline__ void stage_regs(float* v, int C, int c, int j, uint8_
     if (amax * __uint_as_float((uint32_t)(264 - (live ? be : 127)) << 23) >= 1911.5f) be += 1;
     const float inv = live ? __uint_as_float((uint32_t)(264 - be) << 23) : 0.0f;
     const float sx = live ? __uint_as_float((uint32_t)(be - 10) << 23) : 0.0f;
-    uint32_t w0 = 0, w1 = 0, w2 = 0;
-    int part = 0;
+    // u = q + 0x888 with q = rne(v * inv): one fused multiply-add onto 1.5 * 2^23 + 0x888 leaves u in
+    // the low 12 bits (and zeros in bits 12..21).  Nibble d of u ^ 0x888 is digit d in two's
+    // complement.  The 8 x 3 nibbles are regrouped by digit with byte permutes: two values per
+    // register, then the nibbles of neighbouring values merged into bytes.
+    uint32_t t[8];
 #pragma unroll
-    for (int i = 0; i < 8; i++) {
-      const int q = (int)rintf(v[i] * inv);
-      part += q;
-      const uint32_t t = (uint32_t)(q + 0x888) ^ 0x888u;      // nibble d = digit d in two's complement
-      w0 |= (t & 15u) << (4 * i);
-      w1 |= ((t >> 4) & 15u) << (4 * i);
-      w2 |= ((t >> 8) & 15u) << (4 * i);
+    for (int i = 0; i < 8; i++) t[i] = __float_as_uint(fmaf(v[i], inv, 12585096.0f));
+    uint32_t r[2], y[2];
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+      const uint32_t pa = __builtin_amdgcn_perm(t[4 * h + 2], t[4 * h], 0x05040100u);       // values 0 and 2 of this half
+      const uint32_t pb = __builtin_amdgcn_perm(t[4 * h + 3], t[4 * h + 1], 0x05040100u);   // values 1 and 3
+      r[h] = ((pb & 0x0F0F0F0Fu) << 4) | (pa & 0x0F0F0F0Fu);      // bytes: d0 of (0,1), d2 of (0,1), d0 of (2,3), d2 of (2,3)
+      y[h] = ((pa >> 4) & 0x000F000Fu) | (pb & 0x00F000F0u);      // bytes: d1 of (0,1), 0, d1 of (2,3), 0
     }
+    const uint32_t w0 = __builtin_amdgcn_perm(r[1], r[0], 0x06040200u) ^ 0x88888888u;
+    const uint32_t w2 = __builtin_amdgcn_perm(r[1], r[0], 0x07050301u) ^ 0x88888888u;
+    const uint32_t w1 = __builtin_amdgcn_perm(y[1], y[0], 0x06040200u) ^ 0x88888888u;
+    // sum of the eight q from the digit sums
+    int part = __builtin_amdgcn_sdot8((int)w0, 0x11111111, 0, false) + 16 * __builtin_amdgcn_sdot8((int)w1, 0x11111111, 0, false) +
+               256 * __builtin_amdgcn_sdot8((int)w2, 0x11111111, 0, false);
     part += quad_xchg<0xB1>(part);
     part += quad_xchg<0x4E>(part);
     uint8_t* base = dst + (size_t)ks * 4096 + (size_t)j * 4;
@@ -496,7 +511,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
   const int xt = tid - 64;
   const bool stager = xt >= 0 && xt < 4 * C, router = wave == 0 && k > 0;
   KargTouch kt;
-  KARGS_TOUCH(kt);
+  KARGS_TOUCH(kt, 48 + (int)sizeof(DecodeArgs));      // four pointers and four 4-byte leading parameters, then the struct
   Raw8 xraw = {};
   RouteRegs rr = {};
   if (stager) load8_raw<ACT>(x_in, (size_t)xt * 8, xraw);
@@ -522,8 +537,8 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
     const unsigned vg = live ? (unsigned)g : DEC_OOB;
     zg[j] = bload8(R.zp, vg, zo);
     zu[j] = bload8(R.zp, vg, zo + ng);
-    sg[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, (unsigned)(2 * r) * ng, g, live, og[j]);
-    su[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, (unsigned)(2 * r + 1) * ng, g, live, ou[j]);
+    sg[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, (unsigned)(2 * r) * (unsigned)md.sng, g, live, og[j]);
+    su[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, (unsigned)(2 * r + 1) * (unsigned)md.sng, g, live, ou[j]);
   };
   auto issue_planes = [&](int j, bool valid, int r, const SecRsrc& R, const MatK& md, int e, int prec) {
     const unsigned po = (unsigned)e * md.ps32 + (unsigned)(2 * r) * rowb32;
@@ -650,219 +665,138 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
 }
 
 // ---------------------------------------------------------------------------------- down kernel
-// A work-group owns DEC_RPW output rows.  Units = (slot, k-slice, row); unit u of a list: row =
-// u % 8, combo = u / 8 -> (slot, k-slice) = (combo / ks, combo % ks).  Waves [0, dn_rw) take the
-// routed list, the other waves the shared-expert list, whose loads are in flight from the first
-// instruction.  A wave of a group of n takes a contiguous share of its list (q units, the first r
-// waves one more; q and r come from the host), so that consecutive units mostly reuse the same h
-// chunk.  The routed waves also stage h (all waves do when there is
-// no routed bank); each routed wave reads the routing record itself, so nothing waits on LDS
-// before the plane loads are issued.
-struct UnitRef { int slot, ks, row; };
+// A work-group owns DEC_RPW = 8 output rows.  Its work is cut into pieces = (combo, part): a combo
+// is one (slot, 64-chunk k-slice) pair -- shared experts first, then the routed slots -- and a
+// combo's 8 rows are split into P parts of 8/P rows (P = the largest power of two that gives the 16
+// waves at most one piece each; the host picks it).  Wave w takes pieces w, w+16, ...  Everything a
+// piece needs beyond its rows -- expert, precision, weight, the h chunk in digit form -- belongs to
+// its combo, so a wave works it out once, and no wave depends on another before the final sum:
+// every wave puts the h chunks of its own combo into a private LDS area (the digit transposition
+// needs a trip through LDS, not a barrier).  The instruction count of the longest wave bounds the
+// kernel from below (a wave issues at most one instruction every four cycles), hence the flat
+// structure and the host-side arithmetic.
 
-__device__ __forceinline__ UnitRef unit_ref(int u, int ks_n, int inv_ks) {
-  UnitRef r;
-  r.row = u & (DEC_RPW - 1);
-  const int combo = u / DEC_RPW;
-  r.slot = (combo * inv_ks) >> 16;
-  r.ks = combo - r.slot * ks_n;
-  return r;
+// Totals of v0..v3 over the wave, left in lanes 60..63 (lane 60 + i holds the total of v_i).
+__device__ __forceinline__ float wave_sum4_to_last(float v0, float v1, float v2, float v3, int lane) {
+  const bool o1 = lane & 1, o2 = lane & 2;
+  const float t01 = (o1 ? v1 : v0) + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(o1 ? v0 : v1), 0xB1, 0xF, 0xF, true));
+  const float t23 = (o1 ? v3 : v2) + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(o1 ? v2 : v3), 0xB1, 0xF, 0xF, true));
+  float s = (o2 ? t23 : t01) + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(o2 ? t01 : t23), 0x4E, 0xF, 0xF, true));
+  s = dpp_add<0x114, 0xF, 0xE>(s);     // lane % 4 = i now holds the quad sum of v_i: fold the quads of a row
+  s = dpp_add<0x118, 0xF, 0xC>(s);     // lanes 12..15 of every row: the row's totals of v0..v3
+  s += __shfl_xor(s, 16);              // fold the four rows (the row broadcasts of the single-value
+  s += __shfl_xor(s, 32);              // reduction would mix the four interleaved sums)
+  return s;
 }
 
-#define DEC_HQ 3      // h words of 8 values each stager thread loads up front
+#define DEC_HQ 4      // h words of 8 values per lane that cover one combo (64 chunks)
 
 template <int ACT, int SCB>
-__global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const float* h, int total_f, int dn_rw, int ru_q, int ru_r,
-                                                      int su_q, int su_r, DecodeArgs a, int lds_vec_bytes) {
-  extern __shared__ __align__(16) uint8_t dyn[];     // [h vectors][chunk figures][unit partials]
+__global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const float* h, int n_combo_s, int n_pieces, int psh, int f_s,
+                                                      int f_r, int ks_s, int ks_r, int inv_ks_s, int inv_ks_r, int nsf,
+                                                      DecodeArgs a) {
+  extern __shared__ __align__(16) uint8_t dyn[];     // [16 waves: h digits of one combo, chunk figures][partials][gamma]
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
-  const bool routed_wave = wave < dn_rw;
-  KargTouch kt;
-  KARGS_TOUCH(kt);
-  // ---- first instructions: the loads that need only the leading parameters -- in the routed waves
-  // the h words they stage and the routing record (sizeof(RouteRec) == 64 words) -- then the fetch
-  // of all other arguments.  The explicit wait closes these loads for every wave (the routed waves
-  // need the record at once anyway).
-  const __amdgpu_buffer_rsrc_t RH = make_rsrc(h, (unsigned)total_f * 4u);
-  uint4 hraw[DEC_HQ][2] = {};
-  auto load_h = [&](int st_first, int st_n) {          // unconditional: items past the end read nothing
-#pragma unroll
-    for (int q = 0; q < DEC_HQ; q++) {
-      const int item = st_first + q * st_n;
-      const unsigned vo = item < (total_f >> 3) ? (unsigned)item * 32u : DEC_OOB;
-      hraw[q][0] = bload128(RH, vo, 0);
-      hraw[q][1] = bload128(RH, vo, 16);
-    }
-  };
-  int rec_word = 0;
-  if (routed_wave) {
-    load_h(tid, dn_rw * 64);
-    rec_word = rec[lane];
-  }
-  KARGS_WAIT(kt);
-  __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
-  const int k = a.k;
-  const int nsf = a.n_shared * a.f_s;
-  uint8_t* hvec = dyn;
-  float2* hcs = (float2*)(dyn + lds_vec_bytes);
-  float* part = (float*)(hcs + (total_f >> 5));     // shared-expert units first, then routed units
+  constexpr int XB = StageTraits<ACT>::COMBO_BYTES, WS = XB + 64 * 8;
+  constexpr int DEC_RB = ACT == SMOE_BF16 ? 4 : 2;      // rows per batch (the fp32 path keeps 32 activations per lane in registers)
+  uint8_t* xbuf = dyn + wave * WS;
+  float2* xcs = (float2*)(xbuf + XB);
+  float* part = (float*)(dyn + DEC_NW * WS);         // [combo][row]
   const int n0 = blockIdx.x * DEC_RPW;
-  const int n_su = a.n_shared * a.ks_s * DEC_RPW, n_ru = k * a.ks_r * DEC_RPW;
+  KargTouch kt;
+  KARGS_TOUCH(kt, 56 + (int)sizeof(DecodeArgs));      // two pointers and ten 4-byte leading parameters, then the struct
+  bool kargs_here = false;
 
-  uint4 wm[DEC_MAXU], wl[DEC_MAXU];
-  uint32_t zz[DEC_MAXU], ss[DEC_MAXU];      // raw zero-points and scale bits
-  int so[DEC_MAXU];
-
-  // four unconditional loads per unit, the two small ones of a whole batch first
-  auto issue_meta = [&](int j, bool valid, const UnitRef& u, int f, const SecRsrc& R, const MatK& md, int e, int sh) {
-    const int cw = min(64, (f >> 5) - u.ks * 64);
-    const bool live = valid && lane < cw;
-    const int g = lane >> sh;
-    const unsigned elem = (unsigned)(n0 + u.row) * (unsigned)md.ng + (unsigned)((u.ks * 64) >> sh);
-    zz[j] = bload8(R.zp, live ? (unsigned)g : DEC_OOB, (unsigned)e * md.zs32 + elem);
-    ss[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, elem, g, live, so[j]);
-  };
-  auto issue_planes = [&](int j, bool valid, const UnitRef& u, int f, const SecRsrc& R, const MatK& md, int e, int prec) {
-    const int cw = min(64, (f >> 5) - u.ks * 64);
-    const bool live = valid && lane < cw;
-    const unsigned po = (unsigned)e * md.ps32 + (unsigned)(n0 + u.row) * ((unsigned)f >> 1) + (unsigned)u.ks * 1024u;
-    const unsigned vo = live ? (unsigned)lane * 16u : DEC_OOB;
-    wm[j] = bload128(R.msb, vo, po);
-    wl[j] = bload128(R.lsb, prec ? vo : DEC_OOB, po);
-  };
-  // h chunk registers are reloaded when the (slot, k-slice) combo changes
-  auto finish = [&](int j, bool valid, const UnitRef& u, int f, int hoff, int prec, float wt, XR<ACT>& x, int& cur,
-                    int combo, int pidx) {
-    const int cw = min(64, (f >> 5) - u.ks * 64);
-    if (valid && combo != cur) {
-      cur = combo;
-      if (lane < cw) load_xr<ACT>(x, hvec + (size_t)hoff * StageTraits<ACT>::BYTES_PER_VAL, hcs + (hoff >> 5), u.ks, cw, lane);
-    }
-    float v = lane_value(x, wm[j], wl[j], prec, (int)zz[j], scale_val<SCB>(ss[j], so[j]));
-    v = wave_sum_to63(v);
-    if (lane == 63 && valid) part[pidx] = wt * v;
-  };
-
-  // h words -> LDS; `item` = index of a group of 8 consecutive h values
-  auto stage_h = [&](const uint4& r0, const uint4& r1, int item) {
-    const int i0 = item * 8;
-    int voffs, f;                                      // which vector: shared experts first, then routed slots
-    if (i0 < nsf) { const int s = i0 / a.f_s; voffs = s * a.f_s; f = a.f_s; }
-    else { const int s = (i0 - nsf) / a.f_r; voffs = nsf + s * a.f_r; f = a.f_r; }
-    const int local = i0 - voffs;
-    Raw8 raw; raw.a = r0; raw.b = r1;
-    float hv[8];
-    unpack8<SMOE_F32>(raw, hv);
-    stage_regs<ACT>(hv, f >> 5, local >> 5, (local >> 3) & 3, hvec + (size_t)voffs * StageTraits<ACT>::BYTES_PER_VAL,
-                    hcs + (voffs >> 5));
-  };
-  auto stage_all = [&](int st_first, int st_n) {
+  for (int p = wave; p < n_pieces; p += DEC_NW) {
+    // ---- which piece (leading parameters only)
+    const int combo = p >> psh, row0 = (p & ((1 << psh) - 1)) * (DEC_RPW >> psh), n_rows = DEC_RPW >> psh;
+    const bool is_sh = combo < n_combo_s;
+    const int c2 = is_sh ? combo : combo - n_combo_s;
+    const int ksn = is_sh ? ks_s : ks_r, inv_ks = is_sh ? inv_ks_s : inv_ks_r, f = is_sh ? f_s : f_r;
+    const int slot = (c2 * inv_ks) >> 16, ks = c2 - slot * ksn;
+    const int cw = min(64, (f >> 5) - ks * 64);
+    const int hoff = (is_sh ? 0 : nsf) + slot * f + ks * 2048;      // first h value of the combo
+    // ---- first loads: the combo's h values (8 per lane and word, words past the combo read nothing)
+    // and the routing record (sizeof(RouteRec) == 64 words: sel / prec / w of slot s in words s,
+    // 16+s, 32+s, gamma in word 48)
+    const __amdgpu_buffer_rsrc_t RH = make_rsrc(h + hoff, (unsigned)cw * 128u);
+    uint4 hraw[DEC_HQ][2];
 #pragma unroll
     for (int q = 0; q < DEC_HQ; q++) {
-      const int item = st_first + q * st_n;
-      if (item < (total_f >> 3)) stage_h(hraw[q][0], hraw[q][1], item);
+      hraw[q][0] = bload128(RH, (unsigned)(lane + 64 * q) * 32u, 0);
+      hraw[q][1] = bload128(RH, (unsigned)(lane + 64 * q) * 32u, 16);
     }
-    for (int item = st_first + DEC_HQ * st_n; item < (total_f >> 3); item += st_n)        // very wide layers only
-      stage_h(bload128(RH, (unsigned)item * 32u, 0), bload128(RH, (unsigned)item * 32u, 16), item);
-  };
-  float* gamma_lds = part + n_su + n_ru;
+    const int rec_word = rec[lane];
+    if (!kargs_here) { KARGS_WAIT(kt); kargs_here = true; }
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+    const int e = is_sh ? slot : __builtin_amdgcn_readlane(rec_word, slot);
+    const int prec = is_sh ? 1 : __builtin_amdgcn_readlane(rec_word, SMOE_MAX_TOPK + slot);
+    const float wt = __int_as_float(__builtin_amdgcn_readlane(rec_word, is_sh ? 3 * SMOE_MAX_TOPK : 2 * SMOE_MAX_TOPK + slot));
 
-  // The two kinds of waves run separate straight-line code (no merge of control flow between the
-  // issue of a wave's loads and their use, so every wait is for exactly the load that is needed).
-  // Units of a kind are shared out in contiguous runs [u_lo, u_hi).
-  if (routed_wave) {
-    // routed waves: h words and the routing record first, rows as soon as the record is here, then h
-    // into LDS while the rows stream in.  sel / prec / w of slot s sit in words s, 16+s, 32+s of the
-    // record, gamma in word 48.
-    const int u_lo = wave * ru_q + min(wave, ru_r), u_hi = u_lo + ru_q + (wave < ru_r ? 1 : 0);
-    const SecRsrc RR = make_sec(a.rdn, a.E);
-    int pr[DEC_MAXU], ex[DEC_MAXU];
-    float wt[DEC_MAXU];
-#pragma unroll
-    for (int j = 0; j < DEC_MAXU; j++) {
-      const bool valid = u_lo + j < u_hi;
-      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_r, a.inv_ks_r);
-      ex[j] = __builtin_amdgcn_readlane(rec_word, u.slot);
-      pr[j] = __builtin_amdgcn_readlane(rec_word, SMOE_MAX_TOPK + u.slot);
-      wt[j] = __int_as_float(__builtin_amdgcn_readlane(rec_word, 2 * SMOE_MAX_TOPK + u.slot));
-      issue_meta(j, valid, u, a.f_r, RR, a.rdn, ex[j], a.dn_sh_r);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < DEC_MAXU; j++) {
-      const bool valid = u_lo + j < u_hi;
-      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_r, a.inv_ks_r);
-      issue_planes(j, valid, u, a.f_r, RR, a.rdn, ex[j], pr[j]);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    stage_all(tid, dn_rw * 64);
-    if (tid == 0) *gamma_lds = __int_as_float(__builtin_amdgcn_readlane(rec_word, 3 * SMOE_MAX_TOPK));
-    lds_barrier();
+    // ---- the piece's rows: per batch of DEC_RB rows issue metadata, then planes; then h -> digits
+    // while they stream in; then the dot products
+    const MatK& md = is_sh ? a.sdn : a.rdn;
+    const SecRsrc R = make_sec(md, is_sh ? a.n_shared : a.E);
+    const int sh = is_sh ? a.dn_sh_s : a.dn_sh_r;
+    const bool live = lane < cw;
+    const unsigned vo = live ? (unsigned)lane * 16u : DEC_OOB, vl = (live && prec) ? vo : DEC_OOB;
+    const int g0 = (ks * 64) >> sh;                                  // first group of the k-slice
+    const int tg = (lane >> sh) + (g0 & 1);                          // scale position relative to an even element
+    const unsigned vz = live ? (unsigned)(lane >> sh) : DEC_OOB;
+    const unsigned vs = live ? (SCB ? (unsigned)(tg >> 1) << 2 : (unsigned)(lane >> sh) << 2) : DEC_OOB;
+    const int odd = SCB ? (tg & 1) : 0;
+    const unsigned rowb = (unsigned)f >> 1, ng = (unsigned)md.ng, srow = (unsigned)md.sng * (SCB ? 2u : 4u);
+    unsigned po = (unsigned)e * md.ps32 + (unsigned)(n0 + row0) * rowb + (unsigned)ks * 1024u;
+    unsigned zo = (unsigned)e * md.zs32 + (unsigned)(n0 + row0) * ng + (unsigned)g0;
+    unsigned so = (unsigned)e * md.ss32 + (unsigned)(n0 + row0) * srow + (SCB ? (unsigned)(g0 & ~1) * 2u : (unsigned)g0 * 4u);
     XR<ACT> x = {};
-    int cur = -1;
+    for (int b0 = 0; b0 < n_rows; b0 += DEC_RB) {
+      const int nr = min(DEC_RB, n_rows - b0);
+      uint4 wm[DEC_RB], wl[DEC_RB];
+      uint32_t zz[DEC_RB], ss[DEC_RB];
 #pragma unroll
-    for (int j = 0; j < DEC_MAXU; j++) {
-      const bool valid = u_lo + j < u_hi;
-      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_r, a.inv_ks_r);
-      finish(j, valid, u, a.f_r, nsf + u.slot * a.f_r, pr[j], wt[j], x, cur, (u_lo + j) / DEC_RPW, n_su + u_lo + j);
-    }
-    for (int uu = u_lo + DEC_MAXU; uu < u_hi; uu++) {      // more than DEC_MAXU units per wave: one at a time
-      const UnitRef u = unit_ref(uu, a.ks_r, a.inv_ks_r);
-      const int e = __builtin_amdgcn_readlane(rec_word, u.slot);
-      const int prec = __builtin_amdgcn_readlane(rec_word, SMOE_MAX_TOPK + u.slot);
-      const float w1 = __int_as_float(__builtin_amdgcn_readlane(rec_word, 2 * SMOE_MAX_TOPK + u.slot));
-      issue_meta(0, true, u, a.f_r, RR, a.rdn, e, a.dn_sh_r);
-      issue_planes(0, true, u, a.f_r, RR, a.rdn, e, prec);
-      finish(0, true, u, a.f_r, nsf + u.slot * a.f_r, prec, w1, x, cur, uu / DEC_RPW, n_su + uu);
-    }
-  } else {
-    // shared-expert waves: rows in flight from the first instruction; without routed waves they also
-    // stage h
-    const int sw = wave - dn_rw;
-    const int u_lo = sw * su_q + min(sw, su_r), u_hi = u_lo + su_q + (sw < su_r ? 1 : 0);
-    const bool stage = dn_rw == 0;
-    if (stage) load_h(tid, DEC_NT);
-    const SecRsrc RS = make_sec(a.sdn, a.n_shared);
+      for (int r = 0; r < DEC_RB; r++) {
+        zz[r] = bload8(R.zp, r < nr ? vz : DEC_OOB, zo + (unsigned)r * ng);
+        ss[r] = bload32(R.sc, r < nr ? vs : DEC_OOB, so + (unsigned)r * srow);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int j = 0; j < DEC_MAXU; j++) {
-      const bool valid = u_lo + j < u_hi;
-      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_s, a.inv_ks_s);
-      issue_meta(j, valid, u, a.f_s, RS, a.sdn, u.slot, a.dn_sh_s);
-    }
-    __builtin_amdgcn_sched_barrier(0);
+      for (int r = 0; r < DEC_RB; r++) {
+        wm[r] = bload128(R.msb, r < nr ? vo : DEC_OOB, po + (unsigned)r * rowb);
+        wl[r] = bload128(R.lsb, r < nr ? vl : DEC_OOB, po + (unsigned)r * rowb);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      po += DEC_RB * rowb; zo += DEC_RB * ng; so += DEC_RB * srow;
+      if (b0 == 0) {
+        // h -> LDS in digit form (the four lanes of a quad hold one chunk), back as one chunk per lane
 #pragma unroll
-    for (int j = 0; j < DEC_MAXU; j++) {
-      const bool valid = u_lo + j < u_hi;
-      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_s, a.inv_ks_s);
-      issue_planes(j, valid, u, a.f_s, RS, a.sdn, u.slot, 1);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if (stage) {
-      stage_all(tid, DEC_NT);
-      if (tid == 0) *gamma_lds = __int_as_float(rec[3 * SMOE_MAX_TOPK]);
-    }
-    lds_barrier();
-    const float gamma = *gamma_lds;
-    XR<ACT> x = {};
-    int cur = -1;
+        for (int q = 0; q < DEC_HQ; q++) {
+          if (64 * q < 4 * cw) {
+            const int item = lane + 64 * q;
+            if (item < 4 * cw) {
+              Raw8 raw; raw.a = hraw[q][0]; raw.b = hraw[q][1];
+              float hv[8];
+              unpack8<SMOE_F32>(raw, hv);
+              stage_regs<ACT>(hv, cw, item >> 2, item & 3, xbuf, xcs);
+            }
+          }
+        }
+        if (live) load_xr<ACT>(x, xbuf, xcs, 0, cw, lane);
+      }
+      float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-    for (int j = 0; j < DEC_MAXU; j++) {
-      const bool valid = u_lo + j < u_hi;
-      const UnitRef u = unit_ref(valid ? u_lo + j : u_lo, a.ks_s, a.inv_ks_s);
-      finish(j, valid, u, a.f_s, u.slot * a.f_s, 1, gamma, x, cur, (u_lo + j) / DEC_RPW, u_lo + j);
-    }
-    for (int uu = u_lo + DEC_MAXU; uu < u_hi; uu++) {
-      const UnitRef u = unit_ref(uu, a.ks_s, a.inv_ks_s);
-      issue_meta(0, true, u, a.f_s, RS, a.sdn, u.slot, a.dn_sh_s);
-      issue_planes(0, true, u, a.f_s, RS, a.sdn, u.slot, 1);
-      finish(0, true, u, a.f_s, u.slot * a.f_s, 1, gamma, x, cur, uu / DEC_RPW, uu);
+      for (int r = 0; r < DEC_RB; r++) v[r] = lane_value(x, wm[r], wl[r], prec, (int)zz[r], scale_val<SCB>(ss[r], odd));
+      const float tot = wave_sum4_to_last(v[0], v[1], v[2], v[3], lane);
+      if (lane >= 60 && lane - 60 < nr) part[combo * DEC_RPW + row0 + b0 + lane - 60] = wt * tot;
     }
   }
+  if (!kargs_here) KARGS_WAIT(kt);
   __syncthreads();
   if (tid < DEC_RPW) {
+    const int n_combo = n_pieces >> psh;
     float acc = 0.0f;
-    for (int c = 0; c < n_ru / DEC_RPW; c++) acc += part[n_su + c * DEC_RPW + tid];   // routed slots in slot order
-    for (int c = 0; c < n_su / DEC_RPW; c++) acc += part[c * DEC_RPW + tid];          // then the shared experts
+    for (int c = n_combo_s; c < n_combo; c++) acc += part[c * DEC_RPW + tid];      // routed slots in slot order
+    for (int c = 0; c < n_combo_s; c++) acc += part[c * DEC_RPW + tid];            // then the shared experts
     const int n = n0 + tid;
     if (a.add_residual) acc += load_act<ACT>(a.x, n);
     store_act<ACT>(a.y, n, acc);
@@ -877,11 +811,14 @@ static int ilog2_exact(int v) {
 }
 
 template <int ACT, int SCB>
-static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int total_f, int n_wg) {
-  const size_t vec_bytes = (size_t)total_f * StageTraits<ACT>::BYTES_PER_VAL;
-  const size_t n_units = (size_t)(a.n_shared * a.ks_s + a.k * a.ks_r) * DEC_RPW;
-  const size_t lds = vec_bytes + (size_t)(total_f / 32) * 8 + n_units * 4 + 16;      // + the shared experts' weight
-  if (lds + sizeof(RouteRec) + 256 > 160u * 1024u) return SMOE_ESIZE;
+static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int n_wg) {
+  // down kernel: pieces = combos x parts
+  const int n_combo_s = a.n_shared * a.ks_s, n_combo = n_combo_s + a.k * a.ks_r;
+  int psh = 3;
+  while (psh > 0 && (n_combo << psh) > DEC_NW) psh--;
+  const int n_pieces = n_combo << psh;
+  const size_t lds = (size_t)DEC_NW * (StageTraits<ACT>::COMBO_BYTES + 64 * 8) + (size_t)n_combo * DEC_RPW * 4;
+  if (lds > 160u * 1024u) return SMOE_ESIZE;
   if (lds > 64u * 1024u) {       // beyond the default per-work-group limit: ask for the larger carve-out
     static size_t granted = 0;
     if (lds > granted) {
@@ -894,11 +831,8 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
   }
   std::vector<hipEvent_t>* evs = (ctx->timing && ctx->timing_events) ? (std::vector<hipEvent_t>*)ctx->timing_events : nullptr;
   const dim3 g1(n_wg), g2(a.d_model / DEC_RPW), blk(DEC_NT);
-  // down kernel: contiguous unit shares of the routed / shared-expert waves
-  const int n_ru = a.k * a.ks_r * DEC_RPW, n_su = a.n_shared * a.ks_s * DEC_RPW, n_sw = DEC_NW - a.dn_rw;
-  const int ru_q = a.dn_rw ? n_ru / a.dn_rw : 0, ru_r = a.dn_rw ? n_ru % a.dn_rw : 0;
-  const int su_q = n_sw ? n_su / n_sw : 0, su_r = n_sw ? n_su % n_sw : 0;
   const int* recw = (const int*)a.rec;
+  const int nsf = a.n_shared * a.f_s;
   if (evs) {
     // measurement aid: the dispatches themselves carry start/stop events (no extra marker packets)
     hipEvent_t ev[4];
@@ -906,11 +840,11 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
     hipExtLaunchKernelGGL((gateup_kernel<ACT, SCB>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
                           in.E, in.k, in.do_route, a.d_model, a);
     hipExtLaunchKernelGGL((down_kernel<ACT, SCB>), g2, blk, (unsigned)lds, ctx->stream, ev[2], ev[3], 0, recw, (const float*)a.h,
-                          total_f, a.dn_rw, ru_q, ru_r, su_q, su_r, a, (int)vec_bytes);
+                          n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s, a.ks_r, a.inv_ks_s, a.inv_ks_r, nsf, a);
   } else {
     gateup_kernel<ACT, SCB><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, a);
-    down_kernel<ACT, SCB><<<g2, blk, lds, ctx->stream>>>(recw, (const float*)a.h, total_f, a.dn_rw, ru_q, ru_r, su_q, su_r, a,
-                                                         (int)vec_bytes);
+    down_kernel<ACT, SCB><<<g2, blk, lds, ctx->stream>>>(recw, (const float*)a.h, n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s,
+                                                         a.ks_r, a.inv_ks_s, a.inv_ks_r, nsf, a);
   }
   HIPCHK(ctx, hipGetLastError());
   return SMOE_OK;
@@ -940,7 +874,7 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   if ((routed && !(routed->dev.gu.fits32 && routed->dev.dn.fits32)) || (shared && !(shared->dev.gu.fits32 && shared->dev.dn.fits32)))
     return SMOE_ENOTIMPL;                                      // decode kernels address a bank section with 32-bit offsets
   HIPCHK(ctx, hipSetDevice(ctx->device));
-  auto matk = [](const MatDev& m) { return MatK{m.msb, m.lsb, m.zp, m.sc, m.ps32, m.zs32, m.ss32, m.ng}; };
+  auto matk = [](const MatDev& m) { return MatK{m.msb, m.lsb, m.zp, m.sc, m.ps32, m.zs32, m.ss32, m.ng, m.sng, 0}; };
   if (routed) { a.rgu = matk(routed->dev.gu); a.rdn = matk(routed->dev.dn); }
   if (shared) { a.sgu = matk(shared->dev.gu); a.sdn = matk(shared->dev.dn); }
   a.n_shared = ns; a.k = k;
@@ -983,8 +917,8 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   a.dn_rw = split(k * a.ks_r * DEC_RPW, ns * a.ks_s * DEC_RPW);
   const int scb = routed ? routed->dev.sc_bf16 : shared->dev.sc_bf16;
   if (routed && shared && routed->dev.sc_bf16 != shared->dev.sc_bf16) return SMOE_ENOTIMPL;   // one scale dtype per layer
-  if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1>(ctx, in, a, total_f, n_wg) : launch_decode_t<SMOE_F32, 0>(ctx, in, a, total_f, n_wg);
-  return scb ? launch_decode_t<SMOE_BF16, 1>(ctx, in, a, total_f, n_wg) : launch_decode_t<SMOE_BF16, 0>(ctx, in, a, total_f, n_wg);
+  if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1>(ctx, in, a, n_wg) : launch_decode_t<SMOE_F32, 0>(ctx, in, a, n_wg);
+  return scb ? launch_decode_t<SMOE_BF16, 1>(ctx, in, a, n_wg) : launch_decode_t<SMOE_BF16, 0>(ctx, in, a, n_wg);
 }
 
 extern "C" int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,

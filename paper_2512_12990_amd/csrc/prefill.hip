@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
   const uint8_t* pl = a.w.lsb + (size_t)e * a.w.plane_stride + (size_t)grow * (K >> 1) + wc * 16;
   const uint8_t* pz = a.w.zp + (size_t)e * a.w.zp_stride + (size_t)grow * a.w.ng;
   const uint8_t* ps = a.w.sc + (size_t)e * a.w.sc_stride;
-  const size_t srow = (size_t)grow * a.w.ng;
+  const size_t srow = (size_t)grow * a.w.sng;
   const int b_dst = wr * PF_LDK + wc * 32;
 
   f32x16 acc[3][2];

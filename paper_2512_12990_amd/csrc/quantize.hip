@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restri
     }
     if (lane == 0) {
       pz[g] = (uint8_t)zp;
-      const size_t si = (size_t)row * ng + g;
+      const size_t si = (size_t)row * m.sng + g;
       if (sc_bf16) ((uint16_t*)ps)[si] = (uint16_t)f32_to_bf16_bits(s);
       else ((float*)ps)[si] = s;
     }

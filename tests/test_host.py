@@ -30,10 +30,12 @@ def test_strerror_and_bank_bytes_validation():
     assert b"aligned" in lib.smoe_strerror(-3)
     d = B.BankDesc(64, 2048, 1408, 128, 8, 4, B.BF16, B.BF16)
     n = B.smoe_bank_bytes(d)
-    # two nibble planes (= one 8-bit copy, no duplication) + 3 bytes of metadata per group
+    # two nibble planes (= one 8-bit copy, no duplication) + 3 bytes of metadata per group; a row of
+    # scales is padded to an even count (the down rows have 11 groups -> 12 stored)
     weights = 64 * 3 * 2048 * 1408
     groups = 64 * (2 * 1408 * 16 + 2048 * 11)
-    assert weights + 3 * groups <= n <= weights + 3 * groups + 8 * 256 + 64 * 64
+    pad = 64 * 2048 * 2
+    assert weights + 3 * groups + pad <= n <= weights + 3 * groups + pad + 8 * 256 + 64 * 64
     nbytes = C.c_size_t()
     for bad, rc in [(B.BankDesc(0, 2048, 1408, 128, 8, 4, 0, 0), -2), (B.BankDesc(4, 2040, 1408, 128, 8, 4, 0, 0), -2),
                     (B.BankDesc(4, 2048, 1408, 100, 8, 4, 0, 0), -2), (B.BankDesc(4, 2048, 1408, 128, 6, 3, 0, 0), -6),
