@@ -55,7 +55,7 @@ struct DecodeArgs {
   int cap_r, cap_s;                // gate/up: row pairs per work-group and slot = ceil(f / n_wg)
   int inv_cap_r, inv_cap_s;        // ceil(65536 / cap)
   int rot;                         // gate/up: per-slot rotation of the work-group index
-  int gu_rw;                       // gate/up: waves [0, gu_rw) take routed slots, the rest shared experts
+  int gu_L;                        // gate/up: entries per wave
   int gu_sh_r, gu_sh_s;            // log2(32-column chunks per quantisation group), gate/up families
   int n_shared;                    // experts in the shared bank                          [both kernels]
   const void* x;
@@ -68,7 +68,7 @@ struct DecodeArgs {
   int ks_r, ks_s, inv_ks_r, inv_ks_s;   // down: 64-chunk k-slices per row, ceil(65536 / ks)
   int dn_sh_r, dn_sh_s;
   int add_residual;
-  int dn_rw, d_model;              // host side only (the kernels get them as leading parameters)
+  int d_model;                     // host side only (the kernels get it as a leading parameter)
 };
 
 // The routing inputs and the few numbers a wave needs for its first loads are not in this struct:
@@ -98,7 +98,8 @@ struct KargTouch { unsigned t[7]; };
   asm volatile("s_waitcnt lgkmcnt(0)" ::"s"(kt.t[0]), "s"(kt.t[1]), "s"(kt.t[2]), "s"(kt.t[3]), "s"(kt.t[4]), "s"(kt.t[5]),   \
                "s"(kt.t[6])                                                                                               \
                : "memory")
-static_assert(sizeof(DecodeArgs) + 56 <= 8 * 64, "KARGS_TOUCH covers eight lines");
+#define DEC_LEAD_BYTES 56      /* both kernels have 56 bytes of leading parameters before the struct */
+static_assert(sizeof(DecodeArgs) + DEC_LEAD_BYTES <= 8 * 64, "KARGS_TOUCH covers eight lines");
 
 __device__ __forceinline__ void lds_barrier() {
   // orders LDS traffic only; outstanding global loads stay in flight across it
@@ -408,259 +409,303 @@ __device__ __forceinline__ void route_load(const RouteIn& in, int lane, RouteReg
   }
 }
 
-// Fills rec.sel / rec.prec / rec.w (LDS) for the k routed slots.  NJ = experts per lane.
-template <int NJ>
-__device__ void route_compute(const RouteIn& in, const DecodeArgs& a, int lane, RouteRegs& rr, RouteRec& rec) {
+// Lane r < k gets slot r: expert (mysel), slice-mask bits of that expert (mymask) and, with WEIGHTS,
+// the gate weight (myw).  NJ = experts per lane.  The selection alone is what the row loads of the
+// gate/up kernel wait for; the softmax is left out where nothing needs the weights.
+template <int NJ, bool WEIGHTS>
+__device__ __forceinline__ void route_topk(const RouteIn& in, const DecodeArgs& a, int lane, const RouteRegs& rr, int& mysel,
+                                           int& mymask, float& myw) {
   const int E = in.E, k = in.k;
-  int mysel = 0, mymask = 3;
-  float myw = 0.0f;
-  if (in.do_route) {
-    uint32_t ord[NJ];              // orderable biased score; 0 = absent or already taken
-    float p[NJ];
-    uint32_t zmax_o = 0;
+  uint32_t ord[NJ];              // orderable biased score; 0 = absent or already taken
+  float p[NJ];
+  uint32_t zmax_o = 0;
 #pragma unroll
-    for (int j = 0; j < NJ; j++) {
-      const bool ok = lane + 64 * j < E;
-      ord[j] = ok ? orderable(rr.z[j] + rr.b[j]) : 0u;
-      const uint32_t zo = ok ? orderable(rr.z[j]) : 0u;
-      zmax_o = zo > zmax_o ? zo : zmax_o;
-    }
+  for (int j = 0; j < NJ; j++) {
+    const bool ok = lane + 64 * j < E;
+    ord[j] = ok ? orderable(rr.z[j] + rr.b[j]) : 0u;
+    const uint32_t zo = ok ? orderable(rr.z[j]) : 0u;
+    zmax_o = zo > zmax_o ? zo : zmax_o;
+  }
+  float den = 1.0f;
+  if (WEIGHTS) {
     const float m = unorderable(wave_umax(zmax_o));
-    float den = 0.0f;
+    den = 0.0f;
 #pragma unroll
     for (int j = 0; j < NJ; j++) { p[j] = (lane + 64 * j < E) ? __expf(rr.z[j] - m) : 0.0f; den += p[j]; }
     den = wave_sum_all(den);
-    float psum = 0.0f, myp = 0.0f;
-    for (int r = 0; r < k; r++) {
-      uint32_t best = ord[0];
-      int jb = 0;
+  }
+  float psum = 0.0f, myp = 0.0f;
+  mysel = 0; mymask = 3;
+  for (int r = 0; r < k; r++) {
+    uint32_t best = ord[0];
+    int jb = 0;
 #pragma unroll
-      for (int j = 1; j < NJ; j++) if (ord[j] > best) { best = ord[j]; jb = j; }
-      const uint32_t top = wave_umax(best);
-      int ls, js;
-      if (NJ == 1) {                                            // lowest lane among equal scores
-        ls = (int)__builtin_ctzll(__ballot(best == top)); js = 0;
-      } else {
-        const uint32_t cand = best == top ? (uint32_t)(lane + 64 * jb) : 0xFFFFFFFFu;
-        const int e_star = (int)~wave_umax(~cand);              // lowest index among equal scores
-        ls = e_star & 63; js = e_star >> 6;
-      }
-      float pw = 0.0f;
-      int mk = 0;
-#pragma unroll
-      for (int j = 0; j < NJ; j++) {
-        const float t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p[j]), ls));
-        const int u = __builtin_amdgcn_readlane(rr.mk[j], ls);
-        if (js == j) { pw = t; mk = u; }
-        if (js == j && lane == ls) ord[j] = 0u;
-      }
-      psum += pw;
-      if (lane == r) { myp = pw; mysel = ls + 64 * js; mymask = in.mask ? mk : 3; }
+    for (int j = 1; j < NJ; j++) if (ord[j] > best) { best = ord[j]; jb = j; }
+    const uint32_t top = wave_umax(best);
+    int ls, js;
+    if (NJ == 1) {                                            // lowest lane among equal scores
+      ls = (int)__builtin_ctzll(__ballot(best == top)); js = 0;
+    } else {
+      const uint32_t cand = best == top ? (uint32_t)(lane + 64 * jb) : 0xFFFFFFFFu;
+      const int e_star = (int)~wave_umax(~cand);              // lowest index among equal scores
+      ls = e_star & 63; js = e_star >> 6;
     }
+    float pw = 0.0f;
+    int mk = 0;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+      const int u = __builtin_amdgcn_readlane(rr.mk[j], ls);
+      if (js == j) mk = u;
+      if (WEIGHTS) {
+        const float t = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p[j]), ls));
+        if (js == j) pw = t;
+      }
+      if (js == j && lane == ls) ord[j] = 0u;      // taken
+    }
+    psum += pw;
+    // slot r belongs to lane r
+    if (lane == r) { mysel = ls + 64 * js; mymask = in.mask ? mk : 3; myp = pw; }
+  }
+  myw = 0.0f;
+  if (WEIGHTS) {
     myw = myp / den;
     if (a.norm_topk) myw = myw / (psum / den);
     myw *= a.routed_scale;
-  } else {
-    const unsigned vo = lane < k ? (unsigned)lane * 4u : DEC_OOB;
-    const int idx = (int)bload32(make_rsrc(a.idx_in, (unsigned)k * 4u), vo, 0);
-    myw = __uint_as_float(bload32(make_rsrc(a.w_in, (unsigned)k * 4u), vo, 0));
-    mysel = min(max(idx, 0), E - 1);
-    const int mk = (int)bload8(make_rsrc(in.mask, in.mask ? (unsigned)E : 0u), lane < k ? (unsigned)mysel : DEC_OOB, 0);
-    mymask = in.mask ? mk : 3;
   }
-  if (lane < k) {
-    rec.sel[lane] = mysel;
-    rec.w[lane] = myw;
-    rec.prec[lane] = ((mymask & 3) == 3) && (a.tau <= 0.0f || myw >= a.tau);
+}
+
+// The decision was made elsewhere: slot r's expert and weight are read from idx_in / w_in.
+__device__ __forceinline__ void route_given(const RouteIn& in, const DecodeArgs& a, int lane, int& mysel, int& mymask, float& myw) {
+  const int k = in.k;
+  const unsigned vo = lane < k ? (unsigned)lane * 4u : DEC_OOB;
+  const int idx = (int)bload32(make_rsrc(a.idx_in, (unsigned)k * 4u), vo, 0);
+  myw = __uint_as_float(bload32(make_rsrc(a.w_in, (unsigned)k * 4u), vo, 0));
+  mysel = min(max(idx, 0), in.E - 1);
+  const int mk = (int)bload8(make_rsrc(in.mask, in.mask ? (unsigned)in.E : 0u), lane < k ? (unsigned)mysel : DEC_OOB, 0);
+  mymask = in.mask ? mk : 3;
+}
+
+// Routing by one wave.  FULL: weights too (they are needed where the record is published, and
+// where tau > 0 lets the weight decide the precision).
+template <bool FULL>
+__device__ __forceinline__ void route_wave(const RouteIn& in, const DecodeArgs& a, int lane, const RouteRegs& rr, int& mysel,
+                                           int& myprec, float& myw) {
+  int mymask;
+  if (!in.do_route) route_given(in, a, lane, mysel, mymask, myw);
+  else if (in.E <= 64) route_topk<1, FULL>(in, a, lane, rr, mysel, mymask, myw);
+  else route_topk<4, FULL>(in, a, lane, rr, mysel, mymask, myw);
+  myprec = ((mymask & 3) == 3) && (a.tau <= 0.0f || myw >= a.tau);
+}
+
+// Gate weights for a selection made by route_topk<., false>: lane r < k holds slot r's expert in
+// mysel.  Same arithmetic, in the same order, as route_topk<., true>.
+template <int NJ>
+__device__ __forceinline__ float route_weights(const RouteIn& in, const DecodeArgs& a, int lane, const RouteRegs& rr, int mysel) {
+  const int E = in.E, k = in.k;
+  uint32_t zmax_o = 0;
+#pragma unroll
+  for (int j = 0; j < NJ; j++) {
+    const uint32_t zo = (lane + 64 * j < E) ? orderable(rr.z[j]) : 0u;
+    zmax_o = zo > zmax_o ? zo : zmax_o;
   }
+  const float m = unorderable(wave_umax(zmax_o));
+  float den = 0.0f;
+#pragma unroll
+  for (int j = 0; j < NJ; j++) den += (lane + 64 * j < E) ? __expf(rr.z[j] - m) : 0.0f;
+  den = wave_sum_all(den);
+  float zsel = 0.0f;
+#pragma unroll
+  for (int j = 0; j < NJ; j++) {
+    const float t = __shfl(rr.z[j], mysel & 63);
+    if ((mysel >> 6) == j) zsel = t;
+  }
+  const float myp = lane < k ? __expf(zsel - m) : 0.0f;
+  float psum = 0.0f;
+  for (int r = 0; r < k; r++) psum += __int_as_float(__builtin_amdgcn_readlane(__float_as_int(myp), r));
+  float myw = myp / den;
+  if (a.norm_topk) myw = myw / (psum / den);
+  return myw * a.routed_scale;
 }
 
 // ---------------------------------------------------------------------------------- gate/up kernel
-// A work-group takes the row pairs r = b' + n_wg*q (q < cap) of every slot, b' = (block + slot*rot)
-// mod n_wg.  Its waves are specialised: waves [0, gu_rw) work on the routed slots (entry e ->
-// slot e / cap_r, q = e % cap_r) and must wait for the routing decision; the other waves work on
-// the shared experts (entry e -> expert e / cap_s) and have their loads in flight from the first
-// instruction.  A wave of a group of n takes entries first, first + n, ...
-struct PairRef { int valid, slot, r; };
-
-__device__ __forceinline__ PairRef pair_ref(int e, int n_entries, int cap, int inv_cap, int slot_base, int rot, int f) {
-  PairRef p;
-  p.slot = (e * inv_cap) >> 16;
-  const int q = e - p.slot * cap;
-  int bp = (int)blockIdx.x + (slot_base + p.slot) * rot;
-  bp = bp >= (int)gridDim.x ? bp - (int)gridDim.x : bp;
-  p.r = bp + (int)gridDim.x * q;
-  p.valid = e < n_entries && p.r < f;
-  p.r = p.valid ? p.r : 0;
-  return p;
-}
+// Work-group b < n_wg takes the row pairs r = b' + n_wg*q (q < cap) of every slot, b' = (b +
+// slot*rot) mod n_wg, so all work-groups move the same bytes whatever the precision mix.  These
+// (slot, q) entries, shared experts first, are dealt to the 16 waves in runs of L; a run is worked
+// through as pieces = its entries of one slot, so expert, precision and base addresses are set up
+// once per piece and the rows of a piece differ by constant offsets.  Entries of shared experts
+// have their loads in flight before the routing decision exists; the last wave routes (selection
+// only), the four waves before it put x into LDS in digit form.
+// Work-group 0 also publishes the record for the down kernel and the caller (gate weights, weight of
+// the shared experts), after the barrier, so that nothing but the selection is on the path of the
+// row loads.
+struct GuPiece {
+  unsigned po, zo, so;      // byte offsets of the first row pair in the plane / zero-point / scale sections
+  int r0, hb;               // its row, its index in h
+  int prec;
+};
 
 template <int ACT, int SCB>
 __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, const float* bias, const uint8_t* mask, const void* x_in,
-                                                        int E, int k, int do_route, int d_model, DecodeArgs a) {
-  __shared__ RouteRec rec;
-  __shared__ __align__(16) uint8_t xvec[2048 * StageTraits<ACT>::BYTES_PER_VAL];
+                                                        int E, int k, int do_route, int d_model, int n_wg, int n_se,
+                                                        DecodeArgs a) {
+  __shared__ int sel_lds[SMOE_MAX_TOPK], prec_lds[SMOE_MAX_TOPK];
+  __shared__ __align__(16) uint8_t xvec[StageTraits<ACT>::COMBO_BYTES];
   __shared__ float2 xcs[64];
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const RouteIn in{logits, bias, mask, E, k, do_route};
   const int d = d_model, C = d >> 5;
-  // ---- first instructions: the loads that need only the leading parameters -- x (the four waves
-  // after wave 0 stage it) and the routing inputs (wave 0) -- then the fetch of all other
-  // arguments.  The explicit wait closes these loads for every wave: a load still pending where
-  // control flow merges would make all later code wait for every load.
-  const int xt = tid - 64;
-  const bool stager = xt >= 0 && xt < 4 * C, router = wave == 0 && k > 0;
+  // ---- first instructions: the loads that need only the leading parameters -- x (stager waves)
+  // and the routing inputs (router wave) -- then the fetch of all other arguments.  The explicit
+  // wait closes these loads for every wave: a load still pending where control flow merges would
+  // make all later code wait for every load.
+  const int xt = tid - (k > 0 ? (DEC_NW - 5) * 64 : 0);
+  const bool stager = xt >= 0 && xt < 4 * C;
+  const bool router = k > 0 && wave == DEC_NW - 1;
   KargTouch kt;
-  KARGS_TOUCH(kt, 48 + (int)sizeof(DecodeArgs));      // four pointers and four 4-byte leading parameters, then the struct
+  KARGS_TOUCH(kt, DEC_LEAD_BYTES + (int)sizeof(DecodeArgs));      // four pointers and six 4-byte leading parameters, then the struct
   Raw8 xraw = {};
   RouteRegs rr = {};
   if (stager) load8_raw<ACT>(x_in, (size_t)xt * 8, xraw);
   if (router) route_load(in, lane, rr);
   KARGS_WAIT(kt);
   __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+
   const unsigned rowb32 = (unsigned)d >> 1;
   const bool live_lane = lane < C;
   const unsigned voff = live_lane ? (unsigned)lane * 16u : DEC_OOB;
-  const bool routed_wave = wave < a.gu_rw;
+  const int nsf = a.n_shared * a.f_s;
+  const int N_e = n_se + k * a.cap_r;
+  const int e_lo = wave * a.gu_L, e_hi = uni(min(e_lo + a.gu_L, N_e));
 
   uint4 gm[DEC_MAXP], um[DEC_MAXP], gl[DEC_MAXP], ul[DEC_MAXP];
   uint32_t zg[DEC_MAXP], zu[DEC_MAXP], sg[DEC_MAXP], su[DEC_MAXP];      // raw zero-points and scale bits
-  int og[DEC_MAXP], ou[DEC_MAXP];                                        // position of a 16-bit scale in its dword
 
-  // eight unconditional loads per row pair (dead pairs / lanes / LSB planes read nothing); the small
-  // metadata loads of a batch go first, so that a pair's arithmetic waits for its own planes only
-  auto issue_meta = [&](int j, bool valid, int r, const SecRsrc& R, const MatK& md, int e, int sh) {
-    const unsigned ng = (unsigned)md.ng;
-    const int g = lane >> sh;
-    const bool live = valid && live_lane;
-    const unsigned zo = (unsigned)e * md.zs32 + (unsigned)(2 * r) * ng;
-    const unsigned vg = live ? (unsigned)g : DEC_OOB;
-    zg[j] = bload8(R.zp, vg, zo);
-    zu[j] = bload8(R.zp, vg, zo + ng);
-    sg[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, (unsigned)(2 * r) * (unsigned)md.sng, g, live, og[j]);
-    su[j] = load_scale_raw<SCB>(R.sc, (unsigned)e * md.ss32, (unsigned)(2 * r + 1) * (unsigned)md.sng, g, live, ou[j]);
+  // s = slot (shared experts first), q0 = first entry of the piece inside the slot
+  auto setup = [&](bool is_sh, int s, int q0, int e, int prec, const MatK& md) {
+    GuPiece pc;
+    int bp = (int)blockIdx.x + s * a.rot;
+    bp = bp >= n_wg ? bp - n_wg : bp;
+    pc.r0 = bp + n_wg * q0;
+    pc.po = (unsigned)e * md.ps32 + (unsigned)(2 * pc.r0) * rowb32;
+    pc.zo = (unsigned)e * md.zs32 + (unsigned)(2 * pc.r0) * (unsigned)md.ng;
+    pc.so = (unsigned)e * md.ss32 + (unsigned)(2 * pc.r0) * (unsigned)md.sng * (SCB ? 2u : 4u);
+    pc.hb = (is_sh ? s * a.f_s : nsf + (s - a.n_shared) * a.f_r) + pc.r0;
+    pc.prec = prec;
+    return pc;
   };
-  auto issue_planes = [&](int j, bool valid, int r, const SecRsrc& R, const MatK& md, int e, int prec) {
-    const unsigned po = (unsigned)e * md.ps32 + (unsigned)(2 * r) * rowb32;
-    const unsigned vo = valid ? voff : DEC_OOB, vl = (valid && prec) ? voff : DEC_OOB;
-    gm[j] = bload128(R.msb, vo, po);
-    gl[j] = bload128(R.lsb, vl, po);
-    um[j] = bload128(R.msb, vo, po + rowb32);
-    ul[j] = bload128(R.lsb, vl, po + rowb32);
+  // eight unconditional loads per row pair (dead pairs / lanes / LSB planes read nothing): the small
+  // metadata loads of a batch first, so that a pair's arithmetic waits for its own planes only.
+  // Entry t of the batch is row pair r0 + n_wg*t.
+  auto issue = [&](const GuPiece& pc, int nb, int f, const SecRsrc& R, const MatK& md, int sh) {
+    const unsigned gi = (unsigned)(lane >> sh);
+    const unsigned vz = live_lane ? gi : DEC_OOB;
+    const unsigned vs = live_lane ? (SCB ? (gi >> 1) << 2 : gi << 2) : DEC_OOB;
+    const unsigned ng = (unsigned)md.ng, sb = (unsigned)md.sng * (SCB ? 2u : 4u);
+    const unsigned dz = 2u * (unsigned)n_wg * ng, ds = 2u * (unsigned)n_wg * sb, dp = 2u * (unsigned)n_wg * rowb32;
+#pragma unroll
+    for (int t = 0; t < DEC_MAXP; t++) {
+      const bool valid = t < nb && pc.r0 + n_wg * t < f;
+      zg[t] = bload8(R.zp, valid ? vz : DEC_OOB, pc.zo + (unsigned)t * dz);
+      zu[t] = bload8(R.zp, valid ? vz : DEC_OOB, pc.zo + (unsigned)t * dz + ng);
+      sg[t] = bload32(R.sc, valid ? vs : DEC_OOB, pc.so + (unsigned)t * ds);
+      su[t] = bload32(R.sc, valid ? vs : DEC_OOB, pc.so + (unsigned)t * ds + sb);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < DEC_MAXP; t++) {
+      const bool valid = t < nb && pc.r0 + n_wg * t < f;
+      const unsigned vo = valid ? voff : DEC_OOB, vl = (valid && pc.prec) ? voff : DEC_OOB;
+      gm[t] = bload128(R.msb, vo, pc.po + (unsigned)t * dp);
+      gl[t] = bload128(R.lsb, vl, pc.po + (unsigned)t * dp);
+      um[t] = bload128(R.msb, vo, pc.po + (unsigned)t * dp + rowb32);
+      ul[t] = bload128(R.lsb, vl, pc.po + (unsigned)t * dp + rowb32);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   };
-  auto finish = [&](int j, int prec, const XR<ACT>& x, int hidx) {
-    float av = lane_value(x, gm[j], gl[j], prec, (int)zg[j], scale_val<SCB>(sg[j], og[j]));
-    float uv = lane_value(x, um[j], ul[j], prec, (int)zu[j], scale_val<SCB>(su[j], ou[j]));
-    av = wave_sum_to63(av);
-    uv = wave_sum_to63(uv);
-    if (lane == 63 && hidx >= 0) a.h[hidx] = av / (1.0f + __expf(-av)) * uv;
+  auto finish = [&](const GuPiece& pc, int nb, int f, int sh, const XR<ACT>& x) {
+    const int odd = SCB ? ((lane >> sh) & 1) : 0;
+#pragma unroll
+    for (int t = 0; t < DEC_MAXP; t++) {
+      if (t < nb && pc.r0 + n_wg * t < f) {                 // wave-uniform
+        float av = lane_value(x, gm[t], gl[t], pc.prec, (int)zg[t], scale_val<SCB>(sg[t], odd));
+        float uv = lane_value(x, um[t], ul[t], pc.prec, (int)zu[t], scale_val<SCB>(su[t], odd));
+        av = wave_sum_to63(av);
+        uv = wave_sum_to63(uv);
+        if (lane == 63) a.h[pc.hb + n_wg * t] = av / (1.0f + __expf(-av)) * uv;
+      }
+    }
   };
 
-  // ---- prologue: x into LDS, routing decision into LDS, weight of the shared experts (a wave of block 0)
+  // ---- prologue: x into LDS, routing decision into LDS
   if (stager) {
     float xv[8];
     unpack8<ACT>(xraw, xv);
     stage_regs<ACT>(xv, C, xt >> 2, xt & 3, xvec, xcs);
   }
+  int mysel = 0, myprec = 0;
+  float myw = 0.0f;
+  const bool have_w = a.tau > 0.0f || !do_route;      // the weight decides the precision, or was handed in
   if (router) {
-    if (E <= 64) route_compute<1>(in, a, lane, rr, rec);
-    else route_compute<4>(in, a, lane, rr, rec);
-  }
-  if (blockIdx.x == 0 && wave == 5) {
-    float g = 1.0f;
-    if (a.shared_gate_w) {
-      float p = 0.0f;
-      for (int i = lane; i < d; i += 64) p = fmaf(load_act<ACT>(a.shared_gate_w, i), load_act<ACT>(a.x, i), p);
-      g = 1.0f / (1.0f + expf(-wave_sum(p)));
-    }
-    if (lane == 0) rec.gamma = g;
+    if (have_w) route_wave<true>(in, a, lane, rr, mysel, myprec, myw);
+    else route_wave<false>(in, a, lane, rr, mysel, myprec, myw);
+    if (lane < k) { sel_lds[lane] = mysel; prec_lds[lane] = myprec; }
   }
 
-  // entry t of this wave: index first + t * n, n = number of waves of its kind
-  const int n_se = a.n_shared * a.cap_s, n_re = k * a.cap_r;
-  const int my_first = routed_wave ? wave : wave - a.gu_rw, my_n = routed_wave ? a.gu_rw : DEC_NW - a.gu_rw;
-  const int my_cnt = routed_wave ? n_re : n_se;
-  auto entry = [&](int t) {
-    return routed_wave ? pair_ref(my_first + t * my_n, n_re, a.cap_r, a.inv_cap_r, a.n_shared, a.rot, a.f_r)
-                       : pair_ref(my_first + t * my_n, n_se, a.cap_s, a.inv_cap_s, 0, a.rot, a.f_s);
-  };
-  auto hidx_of = [&](const PairRef& p) {
-    return routed_wave ? a.n_shared * a.f_s + p.slot * a.f_r + p.r : p.slot * a.f_s + p.r;
-  };
-
-  // ---- shared-expert waves: rows in flight before the routing decision exists
-  if (!routed_wave) {
-    const SecRsrc RS = make_sec(a.sgu, a.n_shared);
-#pragma unroll
-    for (int j = 0; j < DEC_MAXP; j++) {
-      const PairRef p = entry(j);
-      issue_meta(j, p.valid, p.r, RS, a.sgu, p.slot, a.gu_sh_s);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < DEC_MAXP; j++) {
-      const PairRef p = entry(j);
-      issue_planes(j, p.valid, p.r, RS, a.sgu, p.slot, 1);
-    }
+  // ---- a first batch of shared-expert entries: rows in flight before the routing decision exists
+  int e_cur = uni(e_lo), nb0 = 0;
+  GuPiece pc0 = {};
+  const bool pre = e_lo < min(e_hi, n_se);
+  if (pre) {
+    const int s = (e_cur * a.inv_cap_s) >> 16, q0 = e_cur - s * a.cap_s;
+    nb0 = uni(min(DEC_MAXP, min(min(e_hi, n_se) - e_cur, a.cap_s - q0)));
+    pc0 = setup(true, s, q0, s, 1, a.sgu);
+    issue(pc0, nb0, a.f_s, make_sec(a.sgu, a.n_shared), a.sgu, a.gu_sh_s);
   }
-
   lds_barrier();
-  if (blockIdx.x == 0 && tid < 64) {                      // publish for the down kernel and the caller
-    if (tid < k) {
-      a.rec->sel[tid] = rec.sel[tid]; a.rec->prec[tid] = rec.prec[tid]; a.rec->w[tid] = rec.w[tid];
-      if (a.prec_out) a.prec_out[tid] = (uint8_t)rec.prec[tid];
-      if (a.idx_out) a.idx_out[tid] = rec.sel[tid];
-      if (a.w_out) a.w_out[tid] = rec.w[tid];
+  if (blockIdx.x == 0) {
+    if (router) {                                        // publish for the down kernel and the caller
+      if (!have_w) myw = E <= 64 ? route_weights<1>(in, a, lane, rr, mysel) : route_weights<4>(in, a, lane, rr, mysel);
+      if (lane < k) {
+        a.rec->sel[lane] = mysel; a.rec->prec[lane] = myprec; a.rec->w[lane] = myw;
+        if (a.prec_out) a.prec_out[lane] = (uint8_t)myprec;
+        if (a.idx_out) a.idx_out[lane] = mysel;
+        if (a.w_out) a.w_out[lane] = myw;
+      }
     }
-    if (tid == 0) a.rec->gamma = rec.gamma;
-  }
-
-  int pr[DEC_MAXP], hidx[DEC_MAXP];
-#pragma unroll
-  for (int j = 0; j < DEC_MAXP; j++) {
-    const PairRef p = entry(j);
-    hidx[j] = p.valid ? hidx_of(p) : -1;
-    pr[j] = 1;
-  }
-  if (routed_wave) {
-    const SecRsrc RR = make_sec(a.rgu, a.E);
-    int ex[DEC_MAXP];
-#pragma unroll
-    for (int j = 0; j < DEC_MAXP; j++) {
-      const PairRef p = entry(j);
-      const int slot = p.valid ? p.slot : 0;
-      pr[j] = uni(rec.prec[slot]);
-      ex[j] = uni(rec.sel[slot]);
-      issue_meta(j, p.valid, p.r, RR, a.rgu, ex[j], a.gu_sh_r);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < DEC_MAXP; j++) {
-      const PairRef p = entry(j);
-      issue_planes(j, p.valid, p.r, RR, a.rgu, ex[j], pr[j]);
+    if (wave == DEC_NW - 3) {                            // weight of the shared experts
+      float g = 1.0f;
+      if (a.shared_gate_w) {
+        float p = 0.0f;
+        for (int i = lane; i < d; i += 64) p = fmaf(load_act<ACT>(a.shared_gate_w, i), load_act<ACT>(x_in, i), p);
+        g = 1.0f / (1.0f + expf(-wave_sum(p)));
+      }
+      if (lane == 0) a.rec->gamma = g;
     }
   }
   XR<ACT> x = {};
   if (live_lane) load_xr<ACT>(x, xvec, xcs, 0, C, lane);
-#pragma unroll
-  for (int j = 0; j < DEC_MAXP; j++) finish(j, pr[j], x, hidx[j]);
-
-  // layers with more than DEC_MAXP entries per wave: the rest one at a time
-  for (int t = DEC_MAXP; my_first + t * my_n < my_cnt; t++) {
-    const PairRef p = entry(t);
-    const int slot = p.valid ? p.slot : 0;
-    int prec = 1;
-    if (routed_wave) {
-      prec = uni(rec.prec[slot]);
-      const SecRsrc RR = make_sec(a.rgu, a.E);
-      issue_meta(0, p.valid, p.r, RR, a.rgu, uni(rec.sel[slot]), a.gu_sh_r);
-      issue_planes(0, p.valid, p.r, RR, a.rgu, uni(rec.sel[slot]), prec);
+  if (pre) {
+    finish(pc0, nb0, a.f_s, a.gu_sh_s, x);
+    e_cur = uni(e_cur + nb0);
+  }
+  // ---- everything else, batch by batch
+  while (e_cur < e_hi) {
+    if (e_cur < n_se) {
+      const int s = (e_cur * a.inv_cap_s) >> 16, q0 = e_cur - s * a.cap_s;
+      const int nb = uni(min(DEC_MAXP, min(min(e_hi, n_se) - e_cur, a.cap_s - q0)));
+      const GuPiece pc = setup(true, s, q0, s, 1, a.sgu);
+      issue(pc, nb, a.f_s, make_sec(a.sgu, a.n_shared), a.sgu, a.gu_sh_s);
+      finish(pc, nb, a.f_s, a.gu_sh_s, x);
+      e_cur = uni(e_cur + nb);
     } else {
-      const SecRsrc RS = make_sec(a.sgu, a.n_shared);
-      issue_meta(0, p.valid, p.r, RS, a.sgu, slot, a.gu_sh_s);
-      issue_planes(0, p.valid, p.r, RS, a.sgu, slot, 1);
+      const int er = e_cur - n_se;
+      const int sr = (er * a.inv_cap_r) >> 16, q0 = er - sr * a.cap_r;
+      const int nb = uni(min(DEC_MAXP, min(e_hi - e_cur, a.cap_r - q0)));
+      const GuPiece pc = setup(false, a.n_shared + sr, q0, uni(sel_lds[sr]), uni(prec_lds[sr]), a.rgu);
+      issue(pc, nb, a.f_r, make_sec(a.rgu, E), a.rgu, a.gu_sh_r);
+      finish(pc, nb, a.f_r, a.gu_sh_r, x);
+      e_cur = uni(e_cur + nb);
     }
-    finish(0, prec, x, p.valid ? hidx_of(p) : -1);
   }
 }
 
@@ -704,7 +749,7 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
   float* part = (float*)(dyn + DEC_NW * WS);         // [combo][row]
   const int n0 = blockIdx.x * DEC_RPW;
   KargTouch kt;
-  KARGS_TOUCH(kt, 56 + (int)sizeof(DecodeArgs));      // two pointers and ten 4-byte leading parameters, then the struct
+  KARGS_TOUCH(kt, DEC_LEAD_BYTES + (int)sizeof(DecodeArgs));      // two pointers and ten 4-byte leading parameters, then the struct
   bool kargs_here = false;
 
   for (int p = wave; p < n_pieces; p += DEC_NW) {
@@ -831,6 +876,7 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
   }
   std::vector<hipEvent_t>* evs = (ctx->timing && ctx->timing_events) ? (std::vector<hipEvent_t>*)ctx->timing_events : nullptr;
   const dim3 g1(n_wg), g2(a.d_model / DEC_RPW), blk(DEC_NT);
+  const int n_se = a.n_shared * a.cap_s;
   const int* recw = (const int*)a.rec;
   const int nsf = a.n_shared * a.f_s;
   if (evs) {
@@ -838,11 +884,12 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
     hipEvent_t ev[4];
     for (int i = 0; i < 4; i++) { HIPCHK(ctx, hipEventCreate(&ev[i])); evs->push_back(ev[i]); }
     hipExtLaunchKernelGGL((gateup_kernel<ACT, SCB>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
-                          in.E, in.k, in.do_route, a.d_model, a);
+                          in.E, in.k, in.do_route, a.d_model, n_wg, n_se, a);
     hipExtLaunchKernelGGL((down_kernel<ACT, SCB>), g2, blk, (unsigned)lds, ctx->stream, ev[2], ev[3], 0, recw, (const float*)a.h,
                           n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s, a.ks_r, a.inv_ks_s, a.inv_ks_r, nsf, a);
   } else {
-    gateup_kernel<ACT, SCB><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, a);
+    gateup_kernel<ACT, SCB><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, n_wg, n_se,
+                                                         a);
     down_kernel<ACT, SCB><<<g2, blk, lds, ctx->stream>>>(recw, (const float*)a.h, n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s,
                                                          a.ks_r, a.inv_ks_s, a.inv_ks_r, nsf, a);
   }
@@ -892,29 +939,12 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   a.inv_cap_s = (65536 + a.cap_s - 1) / a.cap_s;
   a.rot = n_wg / (k + ns);
   if (ns * a.cap_s >= 8192 || k * a.cap_r >= 8192) return SMOE_ESIZE;
-  // split of the 16 waves between routed work items and shared-expert work items: the split with
-  // the smallest worst per-wave cost (a routed item is HIGH or LOW, 1.5 planes on average; shared
-  // experts are always HIGH, 2 planes); among equals the one that is lightest on the routed waves,
-  // which start later because they wait for the routing decision
-  auto split = [&](int n_routed, int n_shared_items) {
-    if (ns == 0 || n_shared_items == 0) return DEC_NW;
-    if (k == 0 || n_routed == 0) return 0;
-    int best = 1;
-    double best_max = 1e30, best_r = 1e30;
-    for (int rw = 1; rw < DEC_NW; rw++) {
-      const double cr = 1.5 * ((n_routed + rw - 1) / rw), cs = 2.0 * ((n_shared_items + (DEC_NW - rw) - 1) / (DEC_NW - rw));
-      const double mx = cr > cs ? cr : cs;
-      if (mx < best_max - 1e-9 || (mx < best_max + 1e-9 && cr < best_r - 1e-9)) { best = rw; best_max = mx; best_r = cr; }
-    }
-    return best;
-  };
-  a.gu_rw = split(k * a.cap_r, ns * a.cap_s);
+  a.gu_L = (ns * a.cap_s + k * a.cap_r + DEC_NW - 1) / DEC_NW;
   // down split
   a.ks_r = a.f_r ? (a.f_r / 32 + 63) / 64 : 1;
   a.ks_s = a.f_s ? (a.f_s / 32 + 63) / 64 : 1;
   a.inv_ks_r = (65536 + a.ks_r - 1) / a.ks_r;
   a.inv_ks_s = (65536 + a.ks_s - 1) / a.ks_s;
-  a.dn_rw = split(k * a.ks_r * DEC_RPW, ns * a.ks_s * DEC_RPW);
   const int scb = routed ? routed->dev.sc_bf16 : shared->dev.sc_bf16;
   if (routed && shared && routed->dev.sc_bf16 != shared->dev.sc_bf16) return SMOE_ENOTIMPL;   // one scale dtype per layer
   if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1>(ctx, in, a, n_wg) : launch_decode_t<SMOE_F32, 0>(ctx, in, a, n_wg);
