@@ -121,10 +121,12 @@ template <int CTRL, int ROWM, int BANKM> __device__ __forceinline__ float dpp_ad
 __device__ __forceinline__ float wave_sum_to63(float v) {
   v = dpp_add<0xB1, 0xF, 0xF>(v);      // quad_perm [1,0,3,2]
   v = dpp_add<0x4E, 0xF, 0xF>(v);      // quad_perm [2,3,0,1]: every lane holds its quad's sum
-  v = dpp_add<0x114, 0xF, 0xE>(v);     // row_shr 4, banks 1..3
-  v = dpp_add<0x118, 0xF, 0xC>(v);     // row_shr 8, banks 2..3: lanes 12..15 hold the row sum
-  v = dpp_add<0x142, 0xA, 0xF>(v);     // row_bcast 15 into rows 1 and 3
-  v = dpp_add<0x143, 0xC, 0xF>(v);     // row_bcast 31 into rows 2 and 3
+  // all lanes enabled from here on (the result is only read from the lanes named; with no lane
+  // masked each step is a single add with a lane-shifted operand)
+  v = dpp_add<0x114, 0xF, 0xF>(v);     // row_shr 4
+  v = dpp_add<0x118, 0xF, 0xF>(v);     // row_shr 8: lanes 12..15 hold the row sum
+  v = dpp_add<0x142, 0xF, 0xF>(v);     // row_bcast 15: lane 15 of a row into the next row; lanes 31 / 63: rows 0+1 / 2+3
+  v = dpp_add<0x143, 0xF, 0xF>(v);     // row_bcast 31: lane 31 into rows 2 and 3
   return v;
 }
 template <int CTRL> __device__ __forceinline__ int quad_xchg(int v) {
@@ -214,11 +216,11 @@ __device__ __forceinline__ float lane_value(const XR<SMOE_BF16>& x, const uint4&
     int p3 = 0;
     dot_plane_i4(l, x, p0, p1, p2);      // powers 16^0..16^2
     dot_plane_i4(m, x, p1, p2, p3);      // powers 16^1..16^3
-    const int t = p0 + (p1 << 4) + (p2 << 8) + (p3 << 12) + (136 - zp) * x.xs;
+    const int t = ((((((p3 << 4) + p2) << 4) + p1) << 4) + p0) + __mul24(136 - zp, x.xs);      // |xs| < 2^17
     return (s * x.sx) * (float)t;
   }
   dot_plane_i4(m, x, p0, p1, p2);
-  const int t = p0 + (p1 << 4) + (p2 << 8) + (8 - (zp >> 4)) * x.xs;
+  const int t = ((((p2 << 4) + p1) << 4) + p0) + __mul24(8 - (zp >> 4), x.xs);
   return (16.0f * s * x.sx) * (float)t;
 }
 
@@ -631,7 +633,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
         float uv = lane_value(x, um[t], ul[t], pc.prec, (int)zu[t], scale_val<SCB>(su[t], odd));
         av = wave_sum_to63(av);
         uv = wave_sum_to63(uv);
-        if (lane == 63) a.h[pc.hb + n_wg * t] = av / (1.0f + __expf(-av)) * uv;
+        if (lane == 63) a.h[pc.hb + n_wg * t] = av * __builtin_amdgcn_rcpf(1.0f + __expf(-av)) * uv;
       }
     }
   };
@@ -727,8 +729,8 @@ __device__ __forceinline__ float wave_sum4_to_last(float v0, float v1, float v2,
   const float t01 = (o1 ? v1 : v0) + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(o1 ? v0 : v1), 0xB1, 0xF, 0xF, true));
   const float t23 = (o1 ? v3 : v2) + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(o1 ? v2 : v3), 0xB1, 0xF, 0xF, true));
   float s = (o2 ? t23 : t01) + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(o2 ? t01 : t23), 0x4E, 0xF, 0xF, true));
-  s = dpp_add<0x114, 0xF, 0xE>(s);     // lane % 4 = i now holds the quad sum of v_i: fold the quads of a row
-  s = dpp_add<0x118, 0xF, 0xC>(s);     // lanes 12..15 of every row: the row's totals of v0..v3
+  s = dpp_add<0x114, 0xF, 0xF>(s);     // lane % 4 = i now holds the quad sum of v_i: fold the quads of a row
+  s = dpp_add<0x118, 0xF, 0xF>(s);     // lanes 12..15 of every row: the row's totals of v0..v3
   s += __shfl_xor(s, 16);              // fold the four rows (the row broadcasts of the single-value
   s += __shfl_xor(s, 32);              // reduction would mix the four interleaved sums)
   return s;
