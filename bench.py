@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=4)
     ap.add_argument("--workload", choices=["decode", "prefill"], default="decode",
                     help="decode (default, the headline metric) or the prefill grouped GEMM of one Qwen-shaped layer")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="after the timed passes, copy this many MiB device-to-device four times (a kernel of known "
+                         "traffic, used to scale the HBM byte counters of a profiler run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (the decode layer of one token has no second-GPU path); "
@@ -151,9 +154,17 @@ def main():
                                       "bytes_per_launch": bytes_per_step - gu_bytes_per_launch,
                                       "achieved": (bytes_per_step - gu_bytes_per_launch) / (dn_us * 1e-6) / 1e9},
                      "timing": "start/stop HIP events attached to every dispatch on the launch stream, second pass over the same steps",
-                     "traffic": None},
+                     # HBM bytes per gate/up launch from the FETCH_SIZE / WRITE_SIZE counter runs recorded in
+                     # profiles/decode_dsv2lite_gateup_down_hbm_traffic.txt (scaled by a 256 MiB copy)
+                     "traffic": 39.50e6 + 0.36e6, "traffic_over_algorithmic": (39.50e6 + 0.36e6) / 37.4e6},
     }
 
+    if args.calib_copy_mib:
+        src = torch.full((args.calib_copy_mib << 20,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_steps, idx.cpu().numpy(), prec_np)
     print(json.dumps(out))
