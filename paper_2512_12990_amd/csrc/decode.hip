@@ -6,15 +6,18 @@
 //   gateup  h = silu(Wg x) * (Wu x) for every slot.  Work-group b takes the row pairs
 //           r = b' + n_wg*q of EVERY slot (b' rotated per slot), so all work-groups move the same
 //           bytes whatever the precision mix, and nothing about the split depends on routing:
-//           loads of the shared experts are in flight while wave 0 routes the token.
-//   down    y = sum_slots weight * Wd h (+ x): a work-group owns 8 output rows, its 16 waves split
-//           the (slot, k-slice, row) units evenly; partial sums meet in LDS in a fixed order.
+//           loads of the shared experts are in flight while the last wave routes the token.
+//   down    y = sum_slots weight * Wd h (+ x): a work-group owns 8 output rows, each wave takes the
+//           rows of one (slot, k-slice) piece; partial sums meet in LDS in a fixed order.
+// A wave issues at most one instruction every four cycles, so the instruction count of the
+// longest wave bounds a kernel from below as surely as the bytes do: the code is flat, and what
+// can be worked out once per piece or on the host is.
 // A lane always handles one 32-column chunk = 16 bytes of a nibble plane (one 128-bit load) and
 // a wave issues all loads of a batch before it touches the first result.  Loads go through buffer
 // resources: wave-uniform row offsets in scalar registers, the per-lane part is lane*16, and a
 // lane or load with nothing to read is sent out of range (returns 0, moves no bytes), so the
 // issue code has no branches.
-// The kernels are VALU-issue bound before they are HBM bound, so the inner product is integer:
+// The inner product is integer:
 // with bf16 activations each 32-value chunk of x (or h) is rewritten once, in LDS, as integers
 // |q| <= 1911 times a power-of-two chunk scale, in three balanced hex digits (q = 256 d2 + 16 d1
 // + d0, d in [-8, 7]).  The planes store every nibble n as n - 8, so one signed 8 x 4-bit dot
