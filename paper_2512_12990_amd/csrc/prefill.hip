@@ -1,6 +1,6 @@
 // Prefill (paper Section 4.3: token-parallel, every expert high-bit, per-expert access counts):
 //   route        eight tokens per work-group: router mat-vec, top-k, integer-atomic histogram (route.hip)
-//   scan         exclusive scan of the histogram -> row offset of every expert
+//   scan         exclusive scan of the histogram -> row offset of every expert, list of (expert, row) tiles
 //   permute      one work-group per expert: stable list of its (token, slot) pairs
 //   gemm<0>      grouped GEMM  H = silu(X Wg^T) * (X Wu^T)     (bf16 MFMA, fp32 accumulate)
 //   gemm<1>      grouped GEMM  O = w * (H Wd^T)
@@ -25,11 +25,19 @@ __global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
   if (i < n) p[i] = v;
 }
 
-__global__ void scan_kernel(const uint32_t* hist, int E, int32_t* offsets) {
+// offsets[e] = first row of expert e in the grouped layout; tiles[0] = number of row tiles,
+// tiles[1 + 2i], tiles[2 + 2i] = expert and first row (inside the expert) of tile i.
+__global__ void scan_kernel(const uint32_t* hist, int E, int32_t* offsets, int32_t* tiles) {
   if (threadIdx.x == 0) {
-    int acc = 0;
-    for (int e = 0; e < E; e++) { offsets[e] = acc; acc += (int)hist[e]; }
+    int acc = 0, nt = 0;
+    for (int e = 0; e < E; e++) {
+      offsets[e] = acc;
+      const int n = (int)hist[e];
+      for (int m0 = 0; m0 < n; m0 += PF_BM) { tiles[1 + 2 * nt] = e; tiles[2 + 2 * nt] = m0; nt++; }
+      acc += n;
+    }
     offsets[E] = acc;
+    tiles[0] = nt;
   }
 }
 
@@ -59,6 +67,7 @@ struct GemmArgs {
   MatDev w;                 // gu (MODE 0) or dn (MODE 1) family of the bank
   int sc_bf16, group;
   const int32_t* offsets;   // [E+1]
+  const int32_t* tiles;     // tile list written by scan_kernel
   const int32_t* rows;      // [T*k]
   const uint16_t* x;        // MODE 0: X [T, d_model] bf16
   uint16_t* h;              // H [T*k, d_ff] bf16 (MODE 0 output, MODE 1 input)
@@ -78,12 +87,11 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
   __shared__ __align__(16) uint16_t As[PF_BM * PF_LDK];
   __shared__ __align__(16) uint16_t Bs[PF_BN * PF_LDK];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int e = blockIdx.y, nt = blockIdx.x;
+  const int nt = blockIdx.x, ti = blockIdx.y;
+  if (ti >= a.tiles[0]) return;
+  const int e = a.tiles[1 + 2 * ti], m0 = a.tiles[2 + 2 * ti];
   const int row0 = a.offsets[e];
-  const int n_e = a.offsets[e + 1] - row0;
-  const int m0 = blockIdx.z * PF_BM;
-  if (m0 >= n_e) return;
-  const int m_cnt = min(PF_BM, n_e - m0);
+  const int m_cnt = min(PF_BM, a.offsets[e + 1] - row0 - m0);
   const int K = MODE == 0 ? a.d_model : a.d_ff;
   const int mh = wave >> 1, nh = wave & 1;
 
@@ -130,22 +138,23 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
   // number of 32-row fragments this wave really has (fragments are mh, mh+2, mh+4)
   const int n_frag_total = (m_cnt + 31) >> 5;
 
-  uint4 ra[6], rm, rl;
-  float rs, rz;
-  auto gload = [&](int k0) {
+  // two register sets of prefetched inputs: the loads of K step t+2 are issued while step t is
+  // computed, which is what it takes to cover the memory latency of a loaded machine
+  struct Pre { uint4 ra[6], rm, rl; float rs, rz; };
+  auto gload = [&](int k0, Pre& p) {
 #pragma unroll
-    for (int q = 0; q < 6; q++) ra[q] = a_src[q] ? *(const uint4*)(a_src[q] + k0) : make_uint4(0, 0, 0, 0);
-    rm = *(const uint4*)(pm + (k0 >> 1));
-    rl = *(const uint4*)(pl + (k0 >> 1));
+    for (int q = 0; q < 6; q++) p.ra[q] = a_src[q] ? *(const uint4*)(a_src[q] + k0) : make_uint4(0, 0, 0, 0);
+    p.rm = *(const uint4*)(pm + (k0 >> 1));
+    p.rl = *(const uint4*)(pl + (k0 >> 1));
     const int g = (k0 + wc * 32) / a.group;
-    rz = (float)pz[g];
-    rs = load_scale(ps, a.sc_bf16, srow + g);
+    p.rz = (float)pz[g];
+    p.rs = load_scale(ps, a.sc_bf16, srow + g);
   };
-  auto lstore = [&]() {
+  auto lstore = [&](const Pre& p) {
 #pragma unroll
-    for (int q = 0; q < 6; q++) *(uint4*)(As + a_dst[q]) = ra[q];
-    const uint32_t wm[4] = {rm.x, rm.y, rm.z, rm.w}, wl[4] = {rl.x, rl.y, rl.z, rl.w};
-    const float c0 = -rz * rs;
+    for (int q = 0; q < 6; q++) *(uint4*)(As + a_dst[q]) = p.ra[q];
+    const uint32_t wm[4] = {p.rm.x, p.rm.y, p.rm.z, p.rm.w}, wl[4] = {p.rl.x, p.rl.y, p.rl.z, p.rl.w};
+    const float c0 = -p.rz * p.rs;
     uint32_t out[16];
 #pragma unroll
     for (int j = 0; j < 4; j++) {
@@ -154,8 +163,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
       const uint32_t qo = ((wm[j] & 0xF0F0F0F0u) | ((wl[j] >> 4) & 0x0F0F0F0Fu)) ^ 0x88888888u;     // odd columns
 #pragma unroll
       for (int b = 0; b < 4; b++) {
-        const float we = fmaf((float)((qe >> (8 * b)) & 0xFF), rs, c0);
-        const float wo = fmaf((float)((qo >> (8 * b)) & 0xFF), rs, c0);
+        const float we = fmaf((float)((qe >> (8 * b)) & 0xFF), p.rs, c0);
+        const float wo = fmaf((float)((qo >> (8 * b)) & 0xFF), p.rs, c0);
         out[4 * j + b] = pack_bf16(we, wo);
       }
     }
@@ -163,13 +172,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
     for (int v = 0; v < 4; v++)
       *(uint4*)(Bs + b_dst + 8 * v) = make_uint4(out[4 * v], out[4 * v + 1], out[4 * v + 2], out[4 * v + 3]);
   };
-
-  gload(0);
-  for (int k0 = 0; k0 < K; k0 += PF_BK) {
-    __syncthreads();              // previous tile fully consumed
-    lstore();
-    __syncthreads();
-    if (k0 + PF_BK < K) gload(k0 + PF_BK);
+  auto compute = [&]() {
 #pragma unroll
     for (int s = 0; s < PF_BK / 16; s++) {
       const int ko = s * 16 + (lane >> 5) * 8;
@@ -185,6 +188,25 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
           for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf[j], acc[i][j], 0, 0, 0);
         }
       }
+    }
+  };
+
+  const int nk = K / PF_BK;
+  Pre p0, p1;
+  gload(0, p0);
+  if (nk > 1) gload(PF_BK, p1);
+  for (int t = 0; t < nk; t += 2) {
+    __syncthreads();              // previous tile fully consumed
+    lstore(p0);
+    __syncthreads();
+    if (t + 2 < nk) gload((t + 2) * PF_BK, p0);
+    compute();
+    if (t + 1 < nk) {
+      __syncthreads();
+      lstore(p1);
+      __syncthreads();
+      if (t + 3 < nk) gload((t + 3) * PF_BK, p1);
+      compute();
     }
   }
 
@@ -240,7 +262,9 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* o, const int3
 // ------------------------------------------------------------------------------- host entry
 static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-struct PrefillLayout { size_t rows, pos, offsets, h, o, total; };
+struct PrefillLayout { size_t rows, pos, offsets, tiles, h, o, total; };
+
+static inline int max_tiles(int T, int E, int k) { return E + (T * k) / PF_BM; }
 
 static PrefillLayout prefill_layout(int T, int E, int k, int d_model, int d_ff) {
   PrefillLayout L;
@@ -248,6 +272,7 @@ static PrefillLayout prefill_layout(int T, int E, int k, int d_model, int d_ff) 
   L.rows = off;    off = up256(off + (size_t)T * k * 4);
   L.pos = off;     off = up256(off + (size_t)T * k * 4);
   L.offsets = off; off = up256(off + (size_t)(E + 1) * 4);
+  L.tiles = off;   off = up256(off + (size_t)(1 + 2 * max_tiles(T, E, k)) * 4);
   L.h = off;       off = up256(off + (size_t)T * k * d_ff * 2);
   L.o = off;       off = up256(off + (size_t)T * k * d_model * 4);
   L.total = off;
@@ -285,6 +310,7 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
   int32_t* rows = (int32_t*)(s + L.rows);
   int32_t* pos = (int32_t*)(s + L.pos);
   int32_t* offsets = (int32_t*)(s + L.offsets);
+  int32_t* tiles = (int32_t*)(s + L.tiles);
   uint16_t* h = (uint16_t*)(s + L.h);
   float* o = (float*)(s + L.o);
   hipStream_t st = ctx->stream;
@@ -292,17 +318,17 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
   fill_u32_kernel<<<(E + 255) / 256, 256, 0, st>>>(hist_dev, E, 0u);
   RouteArgs ra{E, k, d, logits_dev, x_dev, w_router_dev, nullptr, norm_topk, routed_scale, nullptr, idx_dev, w_dev};
   { const int rc = smoe_launch_route(ctx, ra, T, SMOE_BF16, hist_dev); if (rc) return rc; }
-  scan_kernel<<<1, 64, 0, st>>>(hist_dev, E, offsets);
+  scan_kernel<<<1, 64, 0, st>>>(hist_dev, E, offsets, tiles);
   permute_kernel<<<E, 256, 0, st>>>(idx_dev, T * k, offsets, rows, pos);
 
   GemmArgs g{};
-  g.sc_bf16 = routed->dev.sc_bf16; g.group = routed->dev.group; g.offsets = offsets; g.rows = rows;
+  g.sc_bf16 = routed->dev.sc_bf16; g.group = routed->dev.group; g.offsets = offsets; g.tiles = tiles; g.rows = rows;
   g.x = (const uint16_t*)x_dev; g.h = h; g.o = o; g.wgt = w_dev; g.k = k; g.d_model = d; g.d_ff = f;
-  const int mz = (T + PF_BM - 1) / PF_BM;        // an expert appears at most once per token
+  const int mt = max_tiles(T, E, k);             // upper bound of the tile count; surplus work-groups return at once
   g.w = routed->dev.gu;
-  grouped_gemm_kernel<0><<<dim3(f / 64, E, mz), 256, 0, st>>>(g);
+  grouped_gemm_kernel<0><<<dim3(f / 64, mt), 256, 0, st>>>(g);
   g.w = routed->dev.dn;
-  grouped_gemm_kernel<1><<<dim3(d / PF_BN, E, mz), 256, 0, st>>>(g);
+  grouped_gemm_kernel<1><<<dim3(d / PF_BN, mt), 256, 0, st>>>(g);
   combine_kernel<<<T, 256, 0, st>>>(o, pos, (const uint16_t*)x_dev, (uint16_t*)y_dev, k, d, add_residual);
   HIPCHK(ctx, hipGetLastError());
   return SMOE_OK;
