@@ -82,6 +82,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return *(uint32_t*)&r;
 }
 
+// Work-group barrier that orders LDS traffic only: the global loads of the prefetch stay in flight
+// across it (__syncthreads would wait for them and undo the prefetch).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <int MODE>
 __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
   __shared__ __align__(16) uint16_t As[PF_BM * PF_LDK];
@@ -97,17 +101,18 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
 
   // ---- loader roles
   // A: 192 rows x 8 sixteen-byte columns = 1536 vectors, 6 per thread
-  const uint16_t* a_src[6];
+  const uint16_t* a_src[6];                 // an absent row reads the start of the matrix and is stored as zeros
   int a_dst[6];
+  unsigned a_live = 0;
 #pragma unroll
   for (int q = 0; q < 6; q++) {
     const int i = tid + 256 * q, r = i >> 3, c = i & 7;
     a_dst[q] = r * PF_LDK + c * 8;
+    a_src[q] = MODE == 0 ? a.x : (const uint16_t*)a.h;
     if (r < m_cnt) {
+      a_live |= 1u << q;
       if (MODE == 0) a_src[q] = a.x + (size_t)(a.rows[row0 + m0 + r] / a.k) * a.d_model + c * 8;
       else a_src[q] = a.h + (size_t)(row0 + m0 + r) * a.d_ff + c * 8;
-    } else {
-      a_src[q] = nullptr;
     }
   }
   // B: 128 weight rows x 2 chunks of 32 columns; thread -> (row, chunk)
@@ -140,21 +145,27 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
 
   // two register sets of prefetched inputs: the loads of K step t+2 are issued while step t is
   // computed, which is what it takes to cover the memory latency of a loaded machine
-  struct Pre { uint4 ra[6], rm, rl; float rs, rz; };
+  // (the registers hold what the loads return, untouched: any arithmetic on them at this point
+  // would make it wait for the loads)
+  struct Pre { uint4 ra[6], rm, rl; uint32_t rs, rz, rzs; };
   auto gload = [&](int k0, Pre& p) {
 #pragma unroll
-    for (int q = 0; q < 6; q++) p.ra[q] = a_src[q] ? *(const uint4*)(a_src[q] + k0) : make_uint4(0, 0, 0, 0);
+    for (int q = 0; q < 6; q++) p.ra[q] = *(const uint4*)(a_src[q] + k0);
     p.rm = *(const uint4*)(pm + (k0 >> 1));
     p.rl = *(const uint4*)(pl + (k0 >> 1));
-    const int g = (k0 + wc * 32) / a.group;
-    p.rz = (float)pz[g];
-    p.rs = load_scale(ps, a.sc_bf16, srow + g);
+    const unsigned g = (unsigned)(k0 + wc * 32) / (unsigned)a.group;
+    if (a.sc_bf16) p.rs = ((const uint16_t*)ps)[srow + g];
+    else p.rs = ((const uint32_t*)ps)[srow + g];
+    const size_t zi = (size_t)(pz - a.w.zp) + g;                  // byte index inside the zero-point section
+    p.rz = ((const uint32_t*)a.w.zp)[zi >> 2];                    // the aligned word that holds it
+    p.rzs = (unsigned)(zi & 3) * 8u;
   };
   auto lstore = [&](const Pre& p) {
 #pragma unroll
-    for (int q = 0; q < 6; q++) *(uint4*)(As + a_dst[q]) = p.ra[q];
+    for (int q = 0; q < 6; q++) *(uint4*)(As + a_dst[q]) = (a_live >> q) & 1 ? p.ra[q] : make_uint4(0, 0, 0, 0);
     const uint32_t wm[4] = {p.rm.x, p.rm.y, p.rm.z, p.rm.w}, wl[4] = {p.rl.x, p.rl.y, p.rl.z, p.rl.w};
-    const float c0 = -p.rz * p.rs;
+    const float rs = __uint_as_float(a.sc_bf16 ? p.rs << 16 : p.rs);
+    const float c0 = -(float)((p.rz >> p.rzs) & 0xFFu) * rs;
     uint32_t out[16];
 #pragma unroll
     for (int j = 0; j < 4; j++) {
@@ -163,8 +174,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
       const uint32_t qo = ((wm[j] & 0xF0F0F0F0u) | ((wl[j] >> 4) & 0x0F0F0F0Fu)) ^ 0x88888888u;     // odd columns
 #pragma unroll
       for (int b = 0; b < 4; b++) {
-        const float we = fmaf((float)((qe >> (8 * b)) & 0xFF), p.rs, c0);
-        const float wo = fmaf((float)((qo >> (8 * b)) & 0xFF), p.rs, c0);
+        const float we = fmaf((float)((qe >> (8 * b)) & 0xFF), rs, c0);
+        const float wo = fmaf((float)((qo >> (8 * b)) & 0xFF), rs, c0);
         out[4 * j + b] = pack_bf16(we, wo);
       }
     }
@@ -196,15 +207,15 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
   gload(0, p0);
   if (nk > 1) gload(PF_BK, p1);
   for (int t = 0; t < nk; t += 2) {
-    __syncthreads();              // previous tile fully consumed
+    lds_barrier();                // previous tile fully consumed
     lstore(p0);
-    __syncthreads();
+    lds_barrier();
     if (t + 2 < nk) gload((t + 2) * PF_BK, p0);
     compute();
     if (t + 1 < nk) {
-      __syncthreads();
+      lds_barrier();
       lstore(p1);
-      __syncthreads();
+      lds_barrier();
       if (t + 3 < nk) gload((t + 3) * PF_BK, p1);
       compute();
     }
