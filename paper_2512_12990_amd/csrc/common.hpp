@@ -118,4 +118,4 @@ __device__ __forceinline__ float wave_sum(float v) {
 int smoe_launch_quantize(smoe_ctx* ctx, smoe_bank* bank, int e0, int n, const void* wg, const void* wu, const void* wd);
 int smoe_launch_router_logits(smoe_ctx* ctx, int E, int d, const void* x, int act_dtype, const float* w_router, float* z);
 struct RouteArgs;
-int smoe_launch_route(smoe_ctx* ctx, const RouteArgs& a, int T, int act_dtype, uint32_t* hist);
+int smoe_launch_route(smoe_ctx* ctx, const RouteArgs& a, int T, int act_dtype);

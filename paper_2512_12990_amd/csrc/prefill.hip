@@ -1,7 +1,7 @@
 // Prefill (paper Section 4.3: token-parallel, every expert high-bit, per-expert access counts):
-//   route        eight tokens per work-group: router mat-vec, top-k, integer-atomic histogram (route.hip)
-//   scan         exclusive scan of the histogram -> row offset of every expert, list of (expert, row) tiles
-//   permute      one work-group per expert: stable list of its (token, slot) pairs
+//   route        eight tokens per work-group: router mat-vec, top-k (route.hip)
+//   group        one work-group per expert: histogram, row offsets, list of (expert, row) tiles, stable
+//                list of the expert's (token, slot) pairs
 //   gemm<0>      grouped GEMM  H = silu(X Wg^T) * (X Wu^T)     (bf16 MFMA, fp32 accumulate)
 //   gemm<1>      grouped GEMM  O = w * (H Wd^T)
 //   combine      Y[t] = sum over slots (slot order) O[(t, slot)]  (+ x)
@@ -20,45 +20,47 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 #define PF_LDK 72          // padded LDS row length in bf16 (144 bytes)
 
 // ------------------------------------------------------------------------------- small kernels
-__global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = v;
-}
-
-// offsets[e] = first row of expert e in the grouped layout; tiles[0] = number of row tiles,
-// tiles[1 + 2i], tiles[2 + 2i] = expert and first row (inside the expert) of tile i.
-__global__ void scan_kernel(const uint32_t* hist, int E, int32_t* offsets, int32_t* tiles) {
-  if (threadIdx.x == 0) {
-    int acc = 0, nt = 0;
-    for (int e = 0; e < E; e++) {
-      offsets[e] = acc;
-      const int n = (int)hist[e];
-      for (int m0 = 0; m0 < n; m0 += PF_BM) { tiles[1 + 2 * nt] = e; tiles[2 + 2 * nt] = m0; nt++; }
-      acc += n;
-    }
-    offsets[E] = acc;
-    tiles[0] = nt;
-  }
-}
-
-// rows[p] = flat (token*k + slot) index of the p-th row of the grouped layout; pos = inverse.
-__global__ __launch_bounds__(256) void permute_kernel(const int32_t* idx, int n, const int32_t* offsets, int32_t* rows,
-                                                      int32_t* pos) {
-  __shared__ int wcount[4];
+#define GR_THREADS 1024
+// One work-group per expert e, no global atomics and no ordering between work-groups: each counts
+// every expert's selections in LDS, so it knows its own row offset and tile offset.  Writes
+//   hist[e]    number of (token, slot) pairs routed to e (the per-expert access count of the layer)
+//   offsets[e] first row of expert e in the grouped layout (offsets[E] = total)
+//   tiles[0]   number of row tiles; tiles[1 + 2i], tiles[2 + 2i] = expert and first row (inside the
+//              expert) of tile i, experts ascending
+//   rows[p]    flat (token*k + slot) index of the p-th row of the grouped layout, ascending inside an
+//              expert; pos = inverse of rows.
+__global__ __launch_bounds__(GR_THREADS) void group_kernel(const int32_t* idx, int n, int E, uint32_t* hist,
+                                                           int32_t* offsets, int32_t* tiles, int32_t* rows, int32_t* pos) {
+  __shared__ int cnt[SMOE_MAX_EXPERTS];
+  __shared__ int wtot[GR_THREADS / 64];
   const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int base = offsets[e];
-  for (int i0 = 0; i0 < n; i0 += 256) {
-    const int i = i0 + tid;
-    const bool hit = i < n && idx[i] == e;
-    const unsigned long long b = __ballot(hit);
-    const int before = __popcll(b & ((1ull << lane) - 1ull));
-    if (lane == 0) wcount[wave] = __popcll(b);
-    __syncthreads();
-    int woff = 0, tot = 0;
-    for (int w = 0; w < 4; w++) { if (w < wave) woff += wcount[w]; tot += wcount[w]; }
-    if (hit) { rows[base + woff + before] = i; pos[i] = base + woff + before; }
-    base += tot;
-    __syncthreads();
+  if (tid < SMOE_MAX_EXPERTS) cnt[tid] = 0;
+  __syncthreads();
+  const int c = (n + GR_THREADS - 1) / GR_THREADS;          // every thread owns a contiguous run of c pairs
+  const int i0 = min(n, tid * c), i1 = min(n, i0 + c);
+  int mine = 0;
+  for (int i = i0; i < i1; i++) {
+    const int v = idx[i];
+    if ((unsigned)v < (unsigned)E) atomicAdd(&cnt[v], 1);
+    mine += v == e;
+  }
+  int incl = mine;
+  for (int s = 1; s < 64; s <<= 1) { const int o = __shfl_up(incl, s); if (lane >= s) incl += o; }
+  if (lane == 63) wtot[wave] = incl;
+  __syncthreads();
+  int p = incl - mine;
+  for (int w = 0; w < wave; w++) p += wtot[w];
+  int off = 0, nt = 0;
+  for (int j = 0; j < e; j++) { off += cnt[j]; nt += (cnt[j] + PF_BM - 1) / PF_BM; }
+  p += off;
+  for (int i = i0; i < i1; i++)
+    if (idx[i] == e) { rows[p] = i; pos[i] = p; p++; }
+  if (tid == 0) {
+    const int ne = cnt[e];
+    hist[e] = (uint32_t)ne;
+    offsets[e] = off;
+    for (int m0 = 0; m0 < ne; m0 += PF_BM) { tiles[1 + 2 * nt] = e; tiles[2 + 2 * nt] = m0; nt++; }
+    if (e == E - 1) { offsets[E] = off + ne; tiles[0] = nt; }
   }
 }
 
@@ -67,7 +69,7 @@ struct GemmArgs {
   MatDev w;                 // gu (MODE 0) or dn (MODE 1) family of the bank
   int sc_bf16, group;
   const int32_t* offsets;   // [E+1]
-  const int32_t* tiles;     // tile list written by scan_kernel
+  const int32_t* tiles;     // tile list written by group_kernel
   const int32_t* rows;      // [T*k]
   const uint16_t* x;        // MODE 0: X [T, d_model] bf16
   uint16_t* h;              // H [T*k, d_ff] bf16 (MODE 0 output, MODE 1 input)
@@ -326,11 +328,9 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
   float* o = (float*)(s + L.o);
   hipStream_t st = ctx->stream;
 
-  fill_u32_kernel<<<(E + 255) / 256, 256, 0, st>>>(hist_dev, E, 0u);
   RouteArgs ra{E, k, d, logits_dev, x_dev, w_router_dev, nullptr, norm_topk, routed_scale, nullptr, idx_dev, w_dev};
-  { const int rc = smoe_launch_route(ctx, ra, T, SMOE_BF16, hist_dev); if (rc) return rc; }
-  scan_kernel<<<1, 64, 0, st>>>(hist_dev, E, offsets, tiles);
-  permute_kernel<<<E, 256, 0, st>>>(idx_dev, T * k, offsets, rows, pos);
+  { const int rc = smoe_launch_route(ctx, ra, T, SMOE_BF16); if (rc) return rc; }
+  group_kernel<<<E, GR_THREADS, 0, st>>>(idx_dev, T * k, E, hist_dev, offsets, tiles, rows, pos);
 
   GemmArgs g{};
   g.sc_bf16 = routed->dev.sc_bf16; g.group = routed->dev.group; g.offsets = offsets; g.tiles = tiles; g.rows = rows;

@@ -3,9 +3,9 @@
 #include "route_device.hpp"
 
 template <int ACT, int NT>
-__global__ __launch_bounds__(RT_THREADS) void route_batch_kernel(RouteArgs a, int T, uint32_t* hist) {
+__global__ __launch_bounds__(RT_THREADS) void route_batch_kernel(RouteArgs a, int T) {
   extern __shared__ __align__(16) uint8_t rdyn[];
-  route_tokens_block<ACT, NT>(a, T, hist, rdyn);
+  route_tokens_block<ACT, NT>(a, T, rdyn);
 }
 
 // z[e] = w_router[e, :] . x for one token: one wave per expert, so the mat-vec of a single token is
@@ -28,16 +28,16 @@ int smoe_launch_router_logits(smoe_ctx* ctx, int E, int d, const void* x, int ac
   return SMOE_OK;
 }
 
-int smoe_launch_route(smoe_ctx* ctx, const RouteArgs& a, int T, int act_dtype, uint32_t* hist) {
+int smoe_launch_route(smoe_ctx* ctx, const RouteArgs& a, int T, int act_dtype) {
   const bool given = a.logits != nullptr;
   if (act_dtype == SMOE_BF16) {
     const size_t lds = RouteLds<SMOE_BF16, 8>::bytes(a.E, a.d_model, given);
     if (lds > 64u * 1024u) return SMOE_ESIZE;
-    route_batch_kernel<SMOE_BF16, 8><<<(T + 7) / 8, RT_THREADS, lds, ctx->stream>>>(a, T, hist);
+    route_batch_kernel<SMOE_BF16, 8><<<(T + 7) / 8, RT_THREADS, lds, ctx->stream>>>(a, T);
   } else {
     const size_t lds = RouteLds<SMOE_F32, 4>::bytes(a.E, a.d_model, given);
     if (lds > 64u * 1024u) return SMOE_ESIZE;
-    route_batch_kernel<SMOE_F32, 4><<<(T + 3) / 4, RT_THREADS, lds, ctx->stream>>>(a, T, hist);
+    route_batch_kernel<SMOE_F32, 4><<<(T + 3) / 4, RT_THREADS, lds, ctx->stream>>>(a, T);
   }
   HIPCHK(ctx, hipGetLastError());
   return SMOE_OK;
@@ -58,5 +58,5 @@ extern "C" int smoe_route(smoe_ctx* ctx, int T, int E, int k, int d_model, const
   HIPCHK(ctx, hipSetDevice(ctx->device));
   RouteArgs a{E, k, d_model, logits_dev, x_dev, w_router_dev, bias_dev, norm_topk, routed_scale,
               logits_out_dev, idx_dev, w_dev};
-  return smoe_launch_route(ctx, a, T, act_dtype, nullptr);
+  return smoe_launch_route(ctx, a, T, act_dtype);
 }

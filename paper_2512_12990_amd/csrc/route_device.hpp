@@ -101,14 +101,77 @@ __device__ __forceinline__ void router_row_dots(const float* __restrict__ wrow, 
   for (int q = 0; q < NT; q++) p[q] = wave_sum(p[q]);
 }
 
+// Dot products of RT_R consecutive router rows (first row e0; rows past E repeat row E-1 and are
+// discarded by the caller) with the NT activation vectors of the work-group.  xs holds the vectors
+// column by column ([d][NT] in storage dtype, 16 bytes per column), so one LDS read feeds NT*RT_R
+// multiply-adds.  Every (row, vector) sum takes the columns in the order router_row_dots does.
+#define RT_R 4
+template <int ACT, int NT>
+__device__ __forceinline__ void router_rows_dots_lds(const float* __restrict__ w_router, int e0, int E, int d, int lane,
+                                                     const uint4* xs, float (&p)[RT_R][NT]) {
+  static_assert((ACT == SMOE_BF16 && NT == 8) || (ACT == SMOE_F32 && NT == 4), "one column of xs is 16 bytes");
+  const float* wrow[RT_R];
+#pragma unroll
+  for (int r = 0; r < RT_R; r++) {
+    wrow[r] = w_router + (size_t)min(e0 + r, E - 1) * d;
+#pragma unroll
+    for (int q = 0; q < NT; q++) p[r][q] = 0.0f;
+  }
+  auto column = [&](int i, float (&xf)[NT]) {
+    const uint4 v = xs[i];
+    if (ACT == SMOE_BF16) {
+      const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        xf[(2 * j) % NT] = __uint_as_float(u[j] << 16);
+        xf[(2 * j + 1) % NT] = __uint_as_float(u[j] & 0xFFFF0000u);
+      }
+    } else {
+      xf[0] = __uint_as_float(v.x); xf[1] = __uint_as_float(v.y);
+      xf[2 % NT] = __uint_as_float(v.z); xf[3 % NT] = __uint_as_float(v.w);
+    }
+  };
+  int i0 = 0;
+  for (; i0 + 512 <= d; i0 += 512) {
+    float w[RT_R][8];
+#pragma unroll
+    for (int r = 0; r < RT_R; r++)
+#pragma unroll
+      for (int u = 0; u < 8; u++) w[r][u] = wrow[r][i0 + u * 64 + lane];
+#pragma unroll
+    for (int u = 0; u < 8; u++) {
+      float xf[NT];
+      column(i0 + u * 64 + lane, xf);
+#pragma unroll
+      for (int r = 0; r < RT_R; r++)
+#pragma unroll
+        for (int q = 0; q < NT; q++) p[r][q] = fmaf(w[r][u], xf[q], p[r][q]);
+    }
+  }
+  for (int i = i0 + lane; i < d; i += 64) {
+    float xf[NT];
+    column(i, xf);
+#pragma unroll
+    for (int r = 0; r < RT_R; r++) {
+      const float w = wrow[r][i];
+#pragma unroll
+      for (int q = 0; q < NT; q++) p[r][q] = fmaf(w, xf[q], p[r][q]);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < RT_R; r++)
+#pragma unroll
+    for (int q = 0; q < NT; q++) p[r][q] = wave_sum(p[r][q]);
+}
+
 // Routes NT tokens per work-group of RT_NW waves: every router row is read once per group, each wave
-// then selects for its share of the tokens; hist (may be null) counts selections by integer atomics.
+// then selects for its share of the tokens.
 // Dynamic LDS: NT*E floats, RT_NW*E 64-bit keys, RT_NW*16 ints, RT_NW*16 floats, then (without given logits)
 // NT*d activations in their storage dtype.
 #define RT_NW 16
 #define RT_THREADS (RT_NW * 64)
 template <int ACT, int NT>
-__device__ __forceinline__ void route_tokens_block(const RouteArgs& a, int T, uint32_t* hist, uint8_t* dyn) {
+__device__ __forceinline__ void route_tokens_block(const RouteArgs& a, int T, uint8_t* dyn) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int E = a.E, d = a.d_model;
   const int t0 = blockIdx.x * NT, nt = min(NT, T - t0);
@@ -119,28 +182,22 @@ __device__ __forceinline__ void route_tokens_block(const RouteArgs& a, int T, ui
   if (a.logits) {
     for (int i = tid; i < nt * E; i += RT_THREADS) zt[i] = a.logits[(size_t)t0 * E + i];
   } else {
-    if (ACT == SMOE_BF16) {
-      uint16_t* xs = (uint16_t*)(wsel + RT_NW * SMOE_MAX_TOPK);
-      for (int i = tid; i < NT * d; i += RT_THREADS) xs[i] = i < nt * d ? ((const uint16_t*)a.x)[(size_t)t0 * d + i] : (uint16_t)0;
-      __syncthreads();
-      for (int e = wave; e < E; e += RT_NW) {
-        float p[NT];
-        router_row_dots<NT>(a.w_router + (size_t)e * d, d, lane, [&](int q, int i) { return bf16_bits_to_f32(xs[q * d + i]); }, p);
-        if (lane == 0)
+    uint8_t* xs = (uint8_t*)(wsel + RT_NW * SMOE_MAX_TOPK);           // [d][NT], 16 bytes per column
+    for (int i = tid; i < NT * d; i += RT_THREADS) {
+      const int q = i / d, c = i - q * d;
+      if (ACT == SMOE_BF16) ((uint16_t*)xs)[c * NT + q] = q < nt ? ((const uint16_t*)a.x)[(size_t)t0 * d + i] : (uint16_t)0;
+      else ((float*)xs)[c * NT + q] = q < nt ? ((const float*)a.x)[(size_t)t0 * d + i] : 0.0f;
+    }
+    __syncthreads();
+    for (int e0 = wave * RT_R; e0 < E; e0 += RT_NW * RT_R) {
+      float p[RT_R][NT];
+      router_rows_dots_lds<ACT, NT>(a.w_router, e0, E, d, lane, (const uint4*)xs, p);
+      if (lane == 0)
 #pragma unroll
-          for (int q = 0; q < NT; q++) zt[q * E + e] = p[q];
-      }
-    } else {
-      float* xs = wsel + RT_NW * SMOE_MAX_TOPK;
-      for (int i = tid; i < NT * d; i += RT_THREADS) xs[i] = i < nt * d ? ((const float*)a.x)[(size_t)t0 * d + i] : 0.0f;
-      __syncthreads();
-      for (int e = wave; e < E; e += RT_NW) {
-        float p[NT];
-        router_row_dots<NT>(a.w_router + (size_t)e * d, d, lane, [&](int q, int i) { return xs[q * d + i]; }, p);
-        if (lane == 0)
+        for (int r = 0; r < RT_R; r++)
+          if (e0 + r < E)
 #pragma unroll
-          for (int q = 0; q < NT; q++) zt[q * E + e] = p[q];
-      }
+            for (int q = 0; q < NT; q++) zt[q * E + e0 + r] = p[r][q];
     }
   }
   __syncthreads();
@@ -148,7 +205,6 @@ __device__ __forceinline__ void route_tokens_block(const RouteArgs& a, int T, ui
     for (int i = tid; i < nt * E; i += RT_THREADS) a.logits_out[(size_t)t0 * E + i] = zt[i];
   for (int q = wave; q < nt; q += RT_NW) {
     select_topk_wave(a, t0 + q, zt + q * E, key + wave * E, sel + wave * SMOE_MAX_TOPK, wsel + wave * SMOE_MAX_TOPK, lane);
-    if (hist && lane < a.k) atomicAdd(&hist[sel[wave * SMOE_MAX_TOPK + lane]], 1u);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
   }
