@@ -106,6 +106,9 @@ __device__ __forceinline__ void router_row_dots(const float* __restrict__ wrow, 
 // column by column ([d][NT] in storage dtype, 16 bytes per column), so one LDS read feeds NT*RT_R
 // multiply-adds.  Every (row, vector) sum takes the columns in the order router_row_dots does.
 #define RT_R 4
+// Position (in 16-byte units) of column i of the staged activations: one unit of padding after every
+// nt columns, so the nt-column blocks that the staging threads of a wave write start in different banks.
+__device__ __forceinline__ int rt_col(int i, int nt) { return i + i / nt; }
 template <int ACT, int NT>
 __device__ __forceinline__ void router_rows_dots_lds(const float* __restrict__ w_router, int e0, int E, int d, int lane,
                                                      const uint4* xs, float (&p)[RT_R][NT]) {
@@ -118,7 +121,7 @@ __device__ __forceinline__ void router_rows_dots_lds(const float* __restrict__ w
     for (int q = 0; q < NT; q++) p[r][q] = 0.0f;
   }
   auto column = [&](int i, float (&xf)[NT]) {
-    const uint4 v = xs[i];
+    const uint4 v = xs[rt_col(i, NT)];
     if (ACT == SMOE_BF16) {
       const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -167,7 +170,7 @@ __device__ __forceinline__ void router_rows_dots_lds(const float* __restrict__ w
 // Routes NT tokens per work-group of RT_NW waves: every router row is read once per group, each wave
 // then selects for its share of the tokens.
 // Dynamic LDS: NT*E floats, RT_NW*E 64-bit keys, RT_NW*16 ints, RT_NW*16 floats, then (without given logits)
-// NT*d activations in their storage dtype.
+// the activations, 16 bytes per column plus padding.
 #define RT_NW 16
 #define RT_THREADS (RT_NW * 64)
 template <int ACT, int NT>
@@ -182,11 +185,29 @@ __device__ __forceinline__ void route_tokens_block(const RouteArgs& a, int T, ui
   if (a.logits) {
     for (int i = tid; i < nt * E; i += RT_THREADS) zt[i] = a.logits[(size_t)t0 * E + i];
   } else {
-    uint8_t* xs = (uint8_t*)(wsel + RT_NW * SMOE_MAX_TOPK);           // [d][NT], 16 bytes per column
-    for (int i = tid; i < NT * d; i += RT_THREADS) {
-      const int q = i / d, c = i - q * d;
-      if (ACT == SMOE_BF16) ((uint16_t*)xs)[c * NT + q] = q < nt ? ((const uint16_t*)a.x)[(size_t)t0 * d + i] : (uint16_t)0;
-      else ((float*)xs)[c * NT + q] = q < nt ? ((const float*)a.x)[(size_t)t0 * d + i] : 0.0f;
+    uint8_t* xs = (uint8_t*)(wsel + RT_NW * SMOE_MAX_TOPK);           // 16 bytes per column, see rt_col()
+    constexpr int ESZ = ACT == SMOE_BF16 ? 2 : 4;
+    if (d % NT == 0) {
+      // a thread moves NT consecutive columns of one vector: one 16-byte load, NT LDS stores
+      const int q = tid % NT;
+      for (int cb = tid / NT; cb * NT < d; cb += RT_THREADS / NT) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (q < nt) v = *(const uint4*)((const uint8_t*)a.x + ((size_t)(t0 + q) * d + (size_t)cb * NT) * ESZ);
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < NT; j++) {
+          uint8_t* dst = xs + (size_t)rt_col(cb * NT + j, NT) * 16 + q * ESZ;
+          if (ACT == SMOE_BF16) *(uint16_t*)dst = (uint16_t)(u[j / 2] >> ((j & 1) * 16));
+          else *(uint32_t*)dst = u[j % 4];
+        }
+      }
+    } else {
+      for (int i = tid; i < NT * d; i += RT_THREADS) {
+        const int q = i / d, c = i - q * d;
+        uint8_t* dst = xs + (size_t)rt_col(c, NT) * 16 + q * ESZ;
+        if (ACT == SMOE_BF16) *(uint16_t*)dst = q < nt ? ((const uint16_t*)a.x)[(size_t)t0 * d + i] : (uint16_t)0;
+        else *(float*)dst = q < nt ? ((const float*)a.x)[(size_t)t0 * d + i] : 0.0f;
+      }
     }
     __syncthreads();
     for (int e0 = wave * RT_R; e0 < E; e0 += RT_NW * RT_R) {
@@ -213,6 +234,6 @@ __device__ __forceinline__ void route_tokens_block(const RouteArgs& a, int T, ui
 template <int ACT, int NT> struct RouteLds {
   static size_t bytes(int E, int d, bool given_logits) {
     return (size_t)NT * E * 4 + (size_t)RT_NW * E * 8 + RT_NW * SMOE_MAX_TOPK * 8 +
-           (given_logits ? 0 : (size_t)NT * d * (ACT == SMOE_BF16 ? 2 : 4));
+           (given_logits ? 0 : (size_t)(d + d / NT + 1) * 16);
   }
 };
