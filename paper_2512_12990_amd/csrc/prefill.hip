@@ -8,15 +8,20 @@
 // Weights are read from the same nibble planes the decode path uses and expanded to
 // bf16 s*(16 msb + lsb - zp) on the way into LDS.
 #include "route_device.hpp"
+#include <type_traits>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+struct __attribute__((packed)) U32x2Unaligned { uint32_t x, y; };
 
 #define PF_BM 192          // token rows per work-group tile
-#define PF_BN 128          // weight rows per work-group tile
+#define PF_BN 256          // weight rows per work-group tile
 #define PF_BK 64
+#define PF_NT 512          // threads per work-group
 #define PF_LDK 72          // padded LDS row length in bf16 (144 bytes)
 
 // ------------------------------------------------------------------------------- small kernels
@@ -67,7 +72,7 @@ __global__ __launch_bounds__(GR_THREADS) void group_kernel(const int32_t* idx, i
 // ------------------------------------------------------------------------------- grouped GEMM
 struct GemmArgs {
   MatDev w;                 // gu (MODE 0) or dn (MODE 1) family of the bank
-  int sc_bf16, group;
+  int sc_bf16, group_shift; // quantisation group = 1 << group_shift columns
   const int32_t* offsets;   // [E+1]
   const int32_t* tiles;     // tile list written by group_kernel
   const int32_t* rows;      // [T*k]
@@ -76,6 +81,7 @@ struct GemmArgs {
   float* o;                 // MODE 1 output [T*k, d_model] fp32
   const float* wgt;         // [T*k] gate weights (flat token*k + slot)
   int k, d_model, d_ff;
+  int n_col_tiles;          // column tiles of this GEMM (grid = 8 * ceil(max row tiles / 8) * n_col_tiles)
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -88,51 +94,127 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // across it (__syncthreads would wait for them and undo the prefetch).
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int MODE>
-__global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
-  __shared__ __align__(16) uint16_t As[PF_BM * PF_LDK];
-  __shared__ __align__(16) uint16_t Bs[PF_BN * PF_LDK];
+// One work-group of eight waves (two per SIMD) per CU: the tile is 192 token rows x 256 weight rows,
+// a wave owns 96 x 64 of it (3 x 2 MFMA fragments), and LDS holds two copies of the K slice so that
+// one barrier per K step is enough.
+template <int MODE, int SCB>
+__global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
+  // (separate arrays, so that the compiler knows a write into one buffer cannot alias a read of the other)
+  __shared__ __align__(16) uint16_t As0[PF_BM * PF_LDK], As1[PF_BM * PF_LDK];
+  __shared__ __align__(16) uint16_t Bs0[PF_BN * PF_LDK], Bs1[PF_BN * PF_LDK];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int nt = blockIdx.x, ti = blockIdx.y;
+  // Work-groups go to the eight XCDs round-robin by their linear index.  All column tiles of one row
+  // tile are given to the same XCD, consecutively, so its rows of A are fetched into one L2 only and
+  // stay there while they are re-read.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int ti = (slot / a.n_col_tiles) * 8 + xcd, nt = slot % a.n_col_tiles;
   if (ti >= a.tiles[0]) return;
   const int e = a.tiles[1 + 2 * ti], m0 = a.tiles[2 + 2 * ti];
   const int row0 = a.offsets[e];
   const int m_cnt = min(PF_BM, a.offsets[e + 1] - row0 - m0);
   const int K = MODE == 0 ? a.d_model : a.d_ff;
-  const int mh = wave >> 1, nh = wave & 1;
+  const int N = MODE == 0 ? a.d_ff : a.d_model;         // output columns of this GEMM
+  const int mh = wave >> 2, nq = wave & 3;
 
   // ---- loader roles
-  // A: 192 rows x 8 sixteen-byte columns = 1536 vectors, 6 per thread
-  const uint16_t* a_src[6];                 // an absent row reads the start of the matrix and is stored as zeros
-  int a_dst[6];
-  unsigned a_live = 0;
+  // A: 192 rows x 8 sixteen-byte columns = 1536 vectors, 3 per thread
+  // (a row past the tile's last one repeats that row: rows of the product are independent and the
+  // epilogue stores none of the surplus ones)
+  const uint16_t* a_base = MODE == 0 ? a.x : (const uint16_t*)a.h;
+  uint32_t a_src[3];                        // element offsets into a_base (the host checks they fit 32 bits)
+  const int a_dst0 = (tid >> 3) * PF_LDK + (tid & 7) * 8;       // vector q goes 64 rows further down
 #pragma unroll
-  for (int q = 0; q < 6; q++) {
-    const int i = tid + 256 * q, r = i >> 3, c = i & 7;
-    a_dst[q] = r * PF_LDK + c * 8;
-    a_src[q] = MODE == 0 ? a.x : (const uint16_t*)a.h;
-    if (r < m_cnt) {
-      a_live |= 1u << q;
-      if (MODE == 0) a_src[q] = a.x + (size_t)(a.rows[row0 + m0 + r] / a.k) * a.d_model + c * 8;
-      else a_src[q] = a.h + (size_t)(row0 + m0 + r) * a.d_ff + c * 8;
-    }
+  for (int q = 0; q < 3; q++) {
+    const int i = tid + PF_NT * q, r = min(i >> 3, m_cnt - 1), c = i & 7;
+    if (MODE == 0) a_src[q] = (uint32_t)(a.rows[row0 + m0 + r] / a.k) * (uint32_t)a.d_model + c * 8;
+    else a_src[q] = (uint32_t)(row0 + m0 + r) * (uint32_t)a.d_ff + c * 8;
   }
-  // B: 128 weight rows x 2 chunks of 32 columns; thread -> (row, chunk)
-  const int wr = tid >> 1, wc = tid & 1;
-  int grow;                                   // row inside the bank's matrix family
+  // B: thread -> (weight row b of the tile, half hb of the 64 columns of the K slice).  MODE 0: the 64
+  // rows of a wave's column block are [gate 32 | up 32] of 32 output columns, so that gate and up
+  // of one output element land in the same lane of two accumulators.
+  const int b = tid >> 1, hb = tid & 1;
+  int grow;                                   // row inside the bank's matrix family (clamped)
   if (MODE == 0) {
-    const int half = wr >> 6, t = wr & 63;    // wave column block, then 32 gate rows + 32 up rows
-    const int col = nt * 64 + half * 32 + (t & 31);
-    grow = 2 * col + (t >> 5);
+    const int col = nt * (PF_BN / 2) + (b >> 6) * 32 + (b & 31);
+    grow = 2 * min(col, N - 1) + ((b >> 5) & 1);
   } else {
-    grow = nt * PF_BN + wr;
+    grow = min(nt * PF_BN + b, N - 1);
   }
-  const uint8_t* pm = a.w.msb + (size_t)e * a.w.plane_stride + (size_t)grow * (K >> 1) + wc * 16;
-  const uint8_t* pl = a.w.lsb + (size_t)e * a.w.plane_stride + (size_t)grow * (K >> 1) + wc * 16;
-  const uint8_t* pz = a.w.zp + (size_t)e * a.w.zp_stride + (size_t)grow * a.w.ng;
+  // uniform 64-bit section bases + 32-bit per-thread offsets (every section of a bank is below 2 GiB)
+  const uint8_t* pm = a.w.msb + (size_t)e * a.w.plane_stride;
+  const uint8_t* pl = a.w.lsb + (size_t)e * a.w.plane_stride;
   const uint8_t* ps = a.w.sc + (size_t)e * a.w.sc_stride;
-  const size_t srow = (size_t)grow * a.w.sng;
-  const int b_dst = wr * PF_LDK + wc * 32;
+  const uint8_t* pz = a.w.zp + (size_t)e * a.w.zp_stride;       // 4-byte aligned: zp_stride is a multiple of 4
+  const uint32_t poff = (uint32_t)grow * (uint32_t)(K >> 1) + hb * 16;
+  const uint32_t srow = (uint32_t)grow * (uint32_t)a.w.sng;
+  const uint32_t zrow = (uint32_t)grow * (uint32_t)a.w.ng;
+  const int b_dst = b * PF_LDK + hb * 32;
+
+  // Two register sets of prefetched inputs: the loads of K step t+2 are issued while step t is
+  // computed.  The registers hold what the loads return, untouched: arithmetic on them at this
+  // point would make the wave wait for the loads.
+  struct PreA { u32x4 ra[3]; };
+  struct Pre { u32x4 rm, rl; };
+  // Scales and zero-points of eight consecutive groups of the thread's row (the chunk that holds the
+  // groups of a K step), kept in registers and reloaded only when a step enters a new chunk: loading
+  // them step by step costs a cache line per thread and step.  Reads are clamped to the expert's
+  // section (what is read past the row's end belongs to groups the row does not have).
+  constexpr int NSD = SCB ? 4 : 8;
+  struct Meta { u32x4 s[NSD / 4]; u32x2 z; };     // (vector registers: picking one element by a run-time index stays in registers)
+  const uint32_t last_s = (uint32_t)(a.w.sc_stride >> 2) - 1u, last_z = (uint32_t)a.w.zp_stride - 8u;
+  auto chunk_of = [&](int k0) __attribute__((always_inline)) { return ((uint32_t)k0 >> a.group_shift) >> 3; };
+  auto mload = [&](int k0, Meta& m) __attribute__((always_inline)) {
+    const uint32_t c0 = chunk_of(k0) << 3;
+    const uint32_t sd = SCB ? (srow + c0) >> 1 : srow + c0;         // srow is even
+    const U32x2Unaligned zz = *(const U32x2Unaligned*)(pz + min(zrow + c0, last_z));    // eight bytes at any alignment
+    m.z = u32x2{zz.x, zz.y};
+#pragma unroll
+    for (int j = 0; j < NSD; j++) m.s[j / 4][j % 4] = ((const uint32_t*)ps)[min(sd + j, last_s)];
+  };
+  auto gload_a = [&](int k0, PreA& p) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < 3; q++) p.ra[q] = *(const u32x4*)(a_base + (a_src[q] + (uint32_t)k0));
+  };
+  auto lstore_a = [&](const PreA& p, uint16_t* As) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < 3; q++) *(u32x4*)(As + a_dst0 + q * 64 * PF_LDK) = p.ra[q];
+  };
+  auto gload = [&](int k0, Pre& p) __attribute__((always_inline)) {
+    p.rm = *(const u32x4*)(pm + (poff + (uint32_t)(k0 >> 1)));
+    p.rl = *(const u32x4*)(pl + (poff + (uint32_t)(k0 >> 1)));
+  };
+  auto lstore = [&](int k0, const Pre& p, const Meta& m, uint16_t* Bs) __attribute__((always_inline)) {
+    const uint32_t wm[4] = {p.rm.x, p.rm.y, p.rm.z, p.rm.w}, wl[4] = {p.rl.x, p.rl.y, p.rl.z, p.rl.w};
+    const uint32_t g = (uint32_t)(k0 + 32 * hb) >> a.group_shift, gi = g & 7u;
+    float rs;
+    if (SCB) {
+      const uint32_t d = m.s[0][gi >> 1];
+      rs = __uint_as_float((gi & 1u) ? d & 0xFFFF0000u : d << 16);
+    } else {
+      const uint32_t lo = m.s[0][gi & 3u], hi = m.s[NSD / 4 - 1][gi & 3u];
+      rs = __uint_as_float(gi < 4 ? lo : hi);
+    }
+    const uint32_t zb = zrow + (g & ~7u);
+    const uint32_t zo = zb - min(zb, last_z) + gi;                 // byte of the zero-point inside m.z
+    const uint32_t zw = m.z[(zo >> 2) & 1u];
+    const float c0 = -(float)((zw >> ((zo & 3u) * 8u)) & 0xFFu) * rs;
+    uint32_t out[16];
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      // the planes hold n ^ 8 per nibble
+      const uint32_t qe = (((wm[j] & 0x0F0F0F0Fu) << 4) | (wl[j] & 0x0F0F0F0Fu)) ^ 0x88888888u;      // even columns
+      const uint32_t qo = ((wm[j] & 0xF0F0F0F0u) | ((wl[j] >> 4) & 0x0F0F0F0Fu)) ^ 0x88888888u;     // odd columns
+#pragma unroll
+      for (int bb = 0; bb < 4; bb++) {
+        const float we = fmaf((float)((qe >> (8 * bb)) & 0xFF), rs, c0);
+        const float wo = fmaf((float)((qo >> (8 * bb)) & 0xFF), rs, c0);
+        out[4 * j + bb] = pack_bf16(we, wo);
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < 4; v++)
+      *(u32x4*)(Bs + b_dst + 8 * v) = u32x4{out[4 * v], out[4 * v + 1], out[4 * v + 2], out[4 * v + 3]};
+  };
 
   f32x16 acc[3][2];
 #pragma unroll
@@ -142,108 +224,110 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.0f;
 
-  // number of 32-row fragments this wave really has (fragments are mh, mh+2, mh+4)
+  // 32-row fragments of this wave are mh, mh+2, mh+4; the first nf of them hold rows of the tile
   const int n_frag_total = (m_cnt + 31) >> 5;
+  const int nf = n_frag_total > mh ? (n_frag_total - mh + 1) >> 1 : 0;
+  const int nk = K / PF_BK;
 
-  // two register sets of prefetched inputs: the loads of K step t+2 are issued while step t is
-  // computed, which is what it takes to cover the memory latency of a loaded machine
-  // (the registers hold what the loads return, untouched: any arithmetic on them at this point
-  // would make it wait for the loads)
-  struct Pre { uint4 ra[6], rm, rl; uint32_t rs, rz, rzs; };
-  auto gload = [&](int k0, Pre& p) {
+  // K loop for a wave with NF live fragments: step t multiplies out of LDS buffer t&1 while the
+  // inputs of step t+1 are expanded into the other buffer; the expansion (VALU) and the products
+  // (MFMA) are independent instruction streams of one basic block.  Loads run two steps ahead;
+  // past the end they repeat the last step (their results are not used).
+  auto kloop = [&](auto nf_c) __attribute__((always_inline)) {
+    constexpr int NF = decltype(nf_c)::value;
+    auto compute = [&](const uint16_t* As, const uint16_t* Bs) __attribute__((always_inline)) {
 #pragma unroll
-    for (int q = 0; q < 6; q++) p.ra[q] = *(const uint4*)(a_src[q] + k0);
-    p.rm = *(const uint4*)(pm + (k0 >> 1));
-    p.rl = *(const uint4*)(pl + (k0 >> 1));
-    const unsigned g = (unsigned)(k0 + wc * 32) / (unsigned)a.group;
-    if (a.sc_bf16) p.rs = ((const uint16_t*)ps)[srow + g];
-    else p.rs = ((const uint32_t*)ps)[srow + g];
-    const size_t zi = (size_t)(pz - a.w.zp) + g;                  // byte index inside the zero-point section
-    p.rz = ((const uint32_t*)a.w.zp)[zi >> 2];                    // the aligned word that holds it
-    p.rzs = (unsigned)(zi & 3) * 8u;
-  };
-  auto lstore = [&](const Pre& p) {
+      for (int s = 0; s < PF_BK / 16; s++) {
+        const int ko = s * 16 + (lane >> 5) * 8;
+        bf16x8 bf[2];
 #pragma unroll
-    for (int q = 0; q < 6; q++) *(uint4*)(As + a_dst[q]) = (a_live >> q) & 1 ? p.ra[q] : make_uint4(0, 0, 0, 0);
-    const uint32_t wm[4] = {p.rm.x, p.rm.y, p.rm.z, p.rm.w}, wl[4] = {p.rl.x, p.rl.y, p.rl.z, p.rl.w};
-    const float rs = __uint_as_float(a.sc_bf16 ? p.rs << 16 : p.rs);
-    const float c0 = -(float)((p.rz >> p.rzs) & 0xFFu) * rs;
-    uint32_t out[16];
+        for (int j = 0; j < 2; j++) bf[j] = *(const bf16x8*)(Bs + (nq * 64 + j * 32 + (lane & 31)) * PF_LDK + ko);
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
-      // the planes hold n ^ 8 per nibble
-      const uint32_t qe = (((wm[j] & 0x0F0F0F0Fu) << 4) | (wl[j] & 0x0F0F0F0Fu)) ^ 0x88888888u;      // even columns
-      const uint32_t qo = ((wm[j] & 0xF0F0F0F0u) | ((wl[j] >> 4) & 0x0F0F0F0Fu)) ^ 0x88888888u;     // odd columns
-#pragma unroll
-      for (int b = 0; b < 4; b++) {
-        const float we = fmaf((float)((qe >> (8 * b)) & 0xFF), rs, c0);
-        const float wo = fmaf((float)((qo >> (8 * b)) & 0xFF), rs, c0);
-        out[4 * j + b] = pack_bf16(we, wo);
-      }
-    }
-#pragma unroll
-    for (int v = 0; v < 4; v++)
-      *(uint4*)(Bs + b_dst + 8 * v) = make_uint4(out[4 * v], out[4 * v + 1], out[4 * v + 2], out[4 * v + 3]);
-  };
-  auto compute = [&]() {
-#pragma unroll
-    for (int s = 0; s < PF_BK / 16; s++) {
-      const int ko = s * 16 + (lane >> 5) * 8;
-      bf16x8 bf[2];
-#pragma unroll
-      for (int j = 0; j < 2; j++) bf[j] = *(const bf16x8*)(Bs + (nh * 64 + j * 32 + (lane & 31)) * PF_LDK + ko);
-#pragma unroll
-      for (int i = 0; i < 3; i++) {
-        const int frag = mh + 2 * i;
-        if (frag < n_frag_total) {
-          const bf16x8 af = *(const bf16x8*)(As + (frag * 32 + (lane & 31)) * PF_LDK + ko);
+        for (int i = 0; i < NF; i++) {
+          const bf16x8 af = *(const bf16x8*)(As + ((mh + 2 * i) * 32 + (lane & 31)) * PF_LDK + ko);
 #pragma unroll
           for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf[j], acc[i][j], 0, 0, 0);
         }
       }
+    };
+    // issue order of one K step: the LDS reads of the first 16 columns, then every MFMA followed by
+    // its share of the expansion's VALU work, the remaining LDS reads, LDS writes and global loads
+    auto interleave = [&]() __attribute__((always_inline)) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 + NF, 0);
+#pragma unroll
+      for (int m = 0; m < 2 * NF * (PF_BK / 16); m++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+        if (m % 2 == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (m % 3 == 0) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        if (m % 3 == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
+    };
+    // The weight planes are prefetched two steps ahead in two register sets; the rows of A go
+    // through one set: they are written to LDS first thing in a step and reloaded at once.
+    Pre p0, p1;
+    Meta m0, m1;
+    PreA pa;
+    const int k1 = min(1, nk - 1) * PF_BK, k2 = min(2, nk - 1) * PF_BK;
+    gload_a(0, pa);
+    gload(0, p0);
+    mload(0, m0);
+    gload(k1, p1);
+    mload(k1, m1);
+    lstore_a(pa, As0);
+    gload_a(k1, pa);
+    lstore(0, p0, m0, Bs0);
+    gload(k2, p0);
+    if (chunk_of(k2) != chunk_of(0)) mload(k2, m0);
+    for (int t = 0; t < nk; t += 2) {
+      lds_barrier();
+      lstore_a(pa, As1);
+      gload_a(min(t + 2, nk - 1) * PF_BK, pa);
+      lstore((t + 1) * PF_BK, p1, m1, Bs1);
+      compute(As0, Bs0);
+      const int ka = min(t + 3, nk - 1) * PF_BK;
+      gload(ka, p1);
+      interleave();
+      if (chunk_of(ka) != chunk_of(min(t + 1, nk - 1) * PF_BK)) mload(ka, m1);
+      if (t + 1 < nk) {
+        lds_barrier();
+        lstore_a(pa, As0);
+        gload_a(min(t + 3, nk - 1) * PF_BK, pa);
+        lstore((t + 2) * PF_BK, p0, m0, Bs0);
+        compute(As1, Bs1);
+        const int kb = min(t + 4, nk - 1) * PF_BK;
+        gload(kb, p0);
+        interleave();
+        if (chunk_of(kb) != chunk_of(min(t + 2, nk - 1) * PF_BK)) mload(kb, m0);
+      }
     }
   };
-
-  const int nk = K / PF_BK;
-  Pre p0, p1;
-  gload(0, p0);
-  if (nk > 1) gload(PF_BK, p1);
-  for (int t = 0; t < nk; t += 2) {
-    lds_barrier();                // previous tile fully consumed
-    lstore(p0);
-    lds_barrier();
-    if (t + 2 < nk) gload((t + 2) * PF_BK, p0);
-    compute();
-    if (t + 1 < nk) {
-      lds_barrier();
-      lstore(p1);
-      lds_barrier();
-      if (t + 3 < nk) gload((t + 3) * PF_BK, p1);
-      compute();
-    }
-  }
+  if (nf == 3) kloop(std::integral_constant<int, 3>());
+  else if (nf == 2) kloop(std::integral_constant<int, 2>());
+  else if (nf == 1) kloop(std::integral_constant<int, 1>());
+  else kloop(std::integral_constant<int, 0>());
 
   // ---- epilogue.  D layout: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32.
 #pragma unroll
   for (int i = 0; i < 3; i++) {
+    if (i >= nf) continue;
     const int frag = mh + 2 * i;
-    if (frag >= n_frag_total) continue;
 #pragma unroll
     for (int r = 0; r < 16; r++) {
       const int m = frag * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
       if (m >= m_cnt) continue;
       const size_t prow = (size_t)(row0 + m0 + m);
       if (MODE == 0) {
-        const int col = nt * 64 + nh * 32 + (lane & 31);
+        const int col = nt * (PF_BN / 2) + nq * 32 + (lane & 31);
         const float g = acc[i][0][r], u = acc[i][1][r];
         const float hv = g / (1.0f + __expf(-g)) * u;
-        a.h[prow * a.d_ff + col] = (uint16_t)f32_to_bf16_bits(hv);
+        if (col < N) a.h[prow * a.d_ff + col] = (uint16_t)f32_to_bf16_bits(hv);
       } else {
         const float wt = a.wgt[a.rows[prow]];
 #pragma unroll
         for (int j = 0; j < 2; j++) {
-          const int col = nt * PF_BN + nh * 64 + j * 32 + (lane & 31);
-          a.o[prow * a.d_model + col] = wt * acc[i][j][r];
+          const int col = nt * PF_BN + nq * 64 + j * 32 + (lane & 31);
+          if (col < N) a.o[prow * a.d_model + col] = wt * acc[i][j][r];
         }
       }
     }
@@ -312,7 +396,8 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
   if (routed->device != ctx->device) return SMOE_EINVAL;
   const int E = routed->desc.n_experts, d = routed->desc.d_model, f = routed->desc.d_ff;
   if (T <= 0 || k <= 0 || k > E || k > SMOE_MAX_TOPK || E > SMOE_MAX_EXPERTS) return SMOE_ESHAPE;
-  if (d % PF_BN || f % PF_BK || d % PF_BK || f % 64 || (routed->desc.group % 32)) return SMOE_ESHAPE;
+  if (f % PF_BK || d % PF_BK || routed->desc.group < 32 || (routed->desc.group & (routed->desc.group - 1))) return SMOE_ESHAPE;
+  if ((size_t)T * d >= 0x7FFFFFFFu || (size_t)T * k * f >= 0x7FFFFFFFu) return SMOE_ESHAPE;   // 32-bit element offsets
   if (!aligned16(x_dev) || !aligned16(y_dev) || !aligned16(idx_dev) || !aligned16(w_dev) || !aligned16(hist_dev) ||
       !aligned16(logits_dev) || !aligned16(w_router_dev) || (((uintptr_t)scratch_dev) & 255u))
     return SMOE_EALIGN;
@@ -333,13 +418,16 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
   group_kernel<<<E, GR_THREADS, 0, st>>>(idx_dev, T * k, E, hist_dev, offsets, tiles, rows, pos);
 
   GemmArgs g{};
-  g.sc_bf16 = routed->dev.sc_bf16; g.group = routed->dev.group; g.offsets = offsets; g.tiles = tiles; g.rows = rows;
+  g.sc_bf16 = routed->dev.sc_bf16; g.group_shift = __builtin_ctz((unsigned)routed->dev.group); g.offsets = offsets; g.tiles = tiles; g.rows = rows;
   g.x = (const uint16_t*)x_dev; g.h = h; g.o = o; g.wgt = w_dev; g.k = k; g.d_model = d; g.d_ff = f;
   const int mt = max_tiles(T, E, k);             // upper bound of the tile count; surplus work-groups return at once
-  g.w = routed->dev.gu;
-  grouped_gemm_kernel<0><<<dim3(f / 64, mt), 256, 0, st>>>(g);
-  g.w = routed->dev.dn;
-  grouped_gemm_kernel<1><<<dim3(d / PF_BN, mt), 256, 0, st>>>(g);
+  const int mt8 = (mt + 7) / 8 * 8;
+  g.w = routed->dev.gu; g.n_col_tiles = (2 * f + PF_BN - 1) / PF_BN;
+  if (g.sc_bf16) grouped_gemm_kernel<0, 1><<<mt8 * g.n_col_tiles, PF_NT, 0, st>>>(g);
+  else grouped_gemm_kernel<0, 0><<<mt8 * g.n_col_tiles, PF_NT, 0, st>>>(g);
+  g.w = routed->dev.dn; g.n_col_tiles = (d + PF_BN - 1) / PF_BN;
+  if (g.sc_bf16) grouped_gemm_kernel<1, 1><<<mt8 * g.n_col_tiles, PF_NT, 0, st>>>(g);
+  else grouped_gemm_kernel<1, 0><<<mt8 * g.n_col_tiles, PF_NT, 0, st>>>(g);
   combine_kernel<<<T, 256, 0, st>>>(o, pos, (const uint16_t*)x_dev, (uint16_t*)y_dev, k, d, add_residual);
   HIPCHK(ctx, hipGetLastError());
   return SMOE_OK;
