@@ -16,6 +16,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
 struct __attribute__((packed)) U32x2Unaligned { uint32_t x, y; };
 
 #define PF_BM 192          // token rows per work-group tile
@@ -160,7 +161,7 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
   // them step by step costs a cache line per thread and step.  Reads are clamped to the expert's
   // section (what is read past the row's end belongs to groups the row does not have).
   constexpr int NSD = SCB ? 4 : 8;
-  struct Meta { u32x4 s[NSD / 4]; u32x2 z; };     // (vector registers: picking one element by a run-time index stays in registers)
+  struct Meta { typename std::conditional<SCB != 0, u32x4, u32x8>::type s; u32x2 z; };     // (vector registers: picking one element by a run-time index stays in registers)
   const uint32_t last_s = (uint32_t)(a.w.sc_stride >> 2) - 1u, last_z = (uint32_t)a.w.zp_stride - 8u;
   auto chunk_of = [&](int k0) __attribute__((always_inline)) { return ((uint32_t)k0 >> a.group_shift) >> 3; };
   auto mload = [&](int k0, Meta& m) __attribute__((always_inline)) {
@@ -169,7 +170,7 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
     const U32x2Unaligned zz = *(const U32x2Unaligned*)(pz + min(zrow + c0, last_z));    // eight bytes at any alignment
     m.z = u32x2{zz.x, zz.y};
 #pragma unroll
-    for (int j = 0; j < NSD; j++) m.s[j / 4][j % 4] = ((const uint32_t*)ps)[min(sd + j, last_s)];
+    for (int j = 0; j < NSD; j++) m.s[j] = ((const uint32_t*)ps)[min(sd + j, last_s)];
   };
   auto gload_a = [&](int k0, PreA& p) __attribute__((always_inline)) {
 #pragma unroll
@@ -188,11 +189,10 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
     const uint32_t g = (uint32_t)(k0 + 32 * hb) >> a.group_shift, gi = g & 7u;
     float rs;
     if (SCB) {
-      const uint32_t d = m.s[0][gi >> 1];
+      const uint32_t d = m.s[gi >> 1];
       rs = __uint_as_float((gi & 1u) ? d & 0xFFFF0000u : d << 16);
     } else {
-      const uint32_t lo = m.s[0][gi & 3u], hi = m.s[NSD / 4 - 1][gi & 3u];
-      rs = __uint_as_float(gi < 4 ? lo : hi);
+      rs = __uint_as_float(m.s[gi]);
     }
     const uint32_t zb = zrow + (g & ~7u);
     const uint32_t zo = zb - min(zb, last_z) + gi;                 // byte of the zero-point inside m.z
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
 
   // K loop for a wave with NF live fragments: step t multiplies out of LDS buffer t&1 while the
   // inputs of step t+1 are expanded into the other buffer; the expansion (VALU) and the products
-  // (MFMA) are independent instruction streams of one basic block.  Loads run two steps ahead;
+  // (MFMA) are independent instruction streams of one basic block, which the compiler interleaves.  Loads run two steps ahead;
   // past the end they repeat the last step (their results are not used).
   auto kloop = [&](auto nf_c) __attribute__((always_inline)) {
     constexpr int NF = decltype(nf_c)::value;
@@ -248,19 +248,6 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
 #pragma unroll
           for (int j = 0; j < 2; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf[j], acc[i][j], 0, 0, 0);
         }
-      }
-    };
-    // issue order of one K step: the LDS reads of the first 16 columns, then every MFMA followed by
-    // its share of the expansion's VALU work, the remaining LDS reads, LDS writes and global loads
-    auto interleave = [&]() __attribute__((always_inline)) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 + NF, 0);
-#pragma unroll
-      for (int m = 0; m < 2 * NF * (PF_BK / 16); m++) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
-        if (m % 2 == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        if (m % 3 == 0) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-        if (m % 3 == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
       }
     };
     // The weight planes are prefetched two steps ahead in two register sets; the rows of A go
@@ -287,7 +274,6 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
       compute(As0, Bs0);
       const int ka = min(t + 3, nk - 1) * PF_BK;
       gload(ka, p1);
-      interleave();
       if (chunk_of(ka) != chunk_of(min(t + 1, nk - 1) * PF_BK)) mload(ka, m1);
       if (t + 1 < nk) {
         lds_barrier();
@@ -297,8 +283,7 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
         compute(As1, Bs1);
         const int kb = min(t + 4, nk - 1) * PF_BK;
         gload(kb, p0);
-        interleave();
-        if (chunk_of(kb) != chunk_of(min(t + 2, nk - 1) * PF_BK)) mload(kb, m0);
+          if (chunk_of(kb) != chunk_of(min(t + 2, nk - 1) * PF_BK)) mload(kb, m0);
       }
     }
   };
