@@ -209,7 +209,7 @@ def prefill_bench(args):
         "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
                      "frac": flops / (ms * 1e-3) / 1e12 / 2500.0, "flops_per_step": flops,
                      "weight_bytes_per_step": wbytes, "weight_gbps": wbytes / (ms * 1e-3) / 1e9, "traffic": None,
-                     "kernel": "whole layer pass (route_hist, scan, permute, grouped_gemm<0>, grouped_gemm<1>, combine)"}}))
+                     "kernel": "whole layer pass (route_batch, group, grouped_gemm<0>, grouped_gemm<1>, combine)"}}))
 
 
 def cpu_baseline(wl, n_steps, idx_np, prec_np):
