@@ -109,6 +109,32 @@ def main():
     gpu_ms = ev0.elapsed_time(ev1)
     ms_per_step = gpu_ms / args.steps
 
+    # Five more windows of the same K steps: their median and spread show how repeatable `value` is.
+    windows = []
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for t in range(args.warmup, args.warmup + args.steps):
+            step(t)
+        e1.record()
+        torch.cuda.synchronize()
+        windows.append(e0.elapsed_time(e1) / args.steps * 1e3)
+    windows.sort()
+
+    # A plain device-to-device copy of 256 MiB, for scale: what this machine's HBM delivers to a streaming
+    # kernel (bytes read + bytes written per second).
+    csrc = torch.full((256 << 20,), 7, dtype=torch.uint8, device=dev)
+    cdst = torch.empty_like(csrc)
+    cdst.copy_(csrc)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(4):
+        cdst.copy_(csrc)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 4 * 2 * csrc.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del csrc, cdst
+
     # Dominant kernel (gate/up streams 2/3 of the bytes): a second pass over the SAME steps with HIP
     # a start and a stop event attached by the library to each of the two dispatches of a call.
     ctx.timing(True)
@@ -147,6 +173,8 @@ def main():
                    "mean_high_slots": float(prec_np.mean() * shp.top_k), "launches_per_step": 2},
         "hbm_gbps": achieved, "hbm_frac": achieved / HBM_PEAK_GBPS, "bytes_per_token": bytes_per_step,
         "host_wall_ms_per_step": wall_ms / args.steps,
+        "repeat_windows_us_per_token": {"median": windows[2], "min": windows[0], "max": windows[-1], "n": 5},
+        "copy_256mib_gbps": copy_gbps,
         "roofline": {"bound": "hbm", "kernel": "gateup_kernel<bf16> (route + gate/up + SwiGLU of all 8 slots)",
                      "achieved": gu_achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gu_achieved / HBM_PEAK_GBPS,
                      "bytes_per_launch": gu_bytes_per_launch, "avg_launch_us": gu_us,

@@ -176,6 +176,40 @@ int smoe_cache_stats_get(const smoe_cache* c, smoe_cache_stats* out);
 /* Copies the resident slice ids, most recent first; returns their number in *n_out. */
 int smoe_cache_order(const smoe_cache* c, uint32_t* slice_ids_host, int max_n, int* n_out);
 
+/* ---- modeled cost of a decode trace on the paper's target system (Section 5; Figs. 9, 10) --- */
+/* The paper evaluates energy and latency on a modeled device: an 8-bit PE array fed from LPDDR4
+ * DRAM that holds the slice cache, with UFS Flash behind it holding every slice.  Host only. */
+typedef struct {
+  double flash_gbit_s;      /* Flash -> DRAM bandwidth, Gbit/s */
+  double dram_gbit_s;       /* DRAM bandwidth, Gbit/s */
+  double xpu_tops;          /* PE array throughput, tera-operations/s */
+  double flash_pj_bit;      /* Flash access energy, pJ/bit */
+  double dram_pj_bit;       /* DRAM read or write energy, pJ/bit */
+  double xpu_tops_w;        /* PE array efficiency, tera-operations/s per watt */
+} smoe_system_spec;
+
+typedef struct {
+  double flash_bits;        /* every missed slice is read from Flash once */
+  double dram_bits;         /* every requested slice is read from DRAM; a missed one is written there first */
+  double ops;               /* as passed in */
+  double energy_j;          /* flash_bits*flash_pj + dram_bits*dram_pj + ops / (xpu_tops_w * 1e12) */
+  double latency_s;         /* flash_bits/flash rate + dram_bits/dram rate + ops/xpu rate: the three served one
+                               after the other (a missed slice is loaded before it is used) */
+  double miss_rate_high;    /* high-bit-normalised miss rate: Flash bytes / (MSB requests * bytes of a
+                               whole high-bit expert), i.e. relative to a cache of whole high-bit experts
+                               that misses on every request */
+} smoe_cost;
+
+/* The system of Section 5: 10 Gbit/s and 103 pJ/bit Flash, 104 Gbit/s and 1.5 pJ/bit DRAM,
+ * 16.4 TOPS at 3.18 TOPS/W. */
+int smoe_system_spec_paper(smoe_system_spec* out);
+/* Cost of the accesses counted in `stats`: msb_slice_bytes / lsb_slice_bytes are the bytes of one
+ * MSB / LSB slice of one expert (planes of its three matrices + metadata with the MSB slice);
+ * ops = operations of the expert FFNs of the trace (2 per multiply-accumulate).  SMOE_EINVAL for
+ * null pointers or a non-positive rate. */
+int smoe_cost_model(const smoe_system_spec* spec, const smoe_cache_stats* stats, uint64_t msb_slice_bytes,
+                    uint64_t lsb_slice_bytes, double ops, smoe_cost* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -369,6 +369,35 @@ class SliceLRU:
 
 
 # --------------------------------------------------------------------------
+# modeled cost on the paper's target system (Section 5)
+# --------------------------------------------------------------------------
+PAPER_SYSTEM = dict(flash_gbit_s=10.0, dram_gbit_s=104.0, xpu_tops=16.4,      # bandwidths, throughput
+                    flash_pj_bit=103.0, dram_pj_bit=1.5, xpu_tops_w=3.18)     # energies, efficiency
+
+
+def cost_model(stats, msb_slice_bytes: int, lsb_slice_bytes: int, ops: float, system=None) -> dict:
+    """Energy and latency of the slice accesses counted in `stats` (Section 5's device).
+
+    A missed slice is read from Flash and written to DRAM; every requested slice (hit or miss) is
+    then read from DRAM by the PE array.  Energy adds the three terms; latency serves Flash, DRAM
+    and compute one after the other.  The high-bit-normalised miss rate relates the Flash bytes
+    to what a cache of whole high-bit experts would fetch if every request missed.
+    """
+    sy = PAPER_SYSTEM if system is None else system
+    miss = stats["msb_miss"] * msb_slice_bytes + stats["lsb_miss"] * lsb_slice_bytes
+    used = ((stats["msb_hit"] + stats["msb_miss"]) * msb_slice_bytes +
+            (stats["lsb_hit"] + stats["lsb_miss"]) * lsb_slice_bytes)
+    flash_bits = 8.0 * miss
+    dram_bits = 8.0 * (used + miss)
+    energy = flash_bits * sy["flash_pj_bit"] * 1e-12 + dram_bits * sy["dram_pj_bit"] * 1e-12 + ops / (sy["xpu_tops_w"] * 1e12)
+    latency = flash_bits / (sy["flash_gbit_s"] * 1e9) + dram_bits / (sy["dram_gbit_s"] * 1e9) + ops / (sy["xpu_tops"] * 1e12)
+    req = stats["msb_hit"] + stats["msb_miss"]
+    rate = miss / (req * (msb_slice_bytes + lsb_slice_bytes)) if req else 0.0
+    return dict(flash_bits=flash_bits, dram_bits=dram_bits, ops=float(ops), energy_j=energy, latency_s=latency,
+                miss_rate_high=rate)
+
+
+# --------------------------------------------------------------------------
 # comparison metric
 # --------------------------------------------------------------------------
 def max_abs_rel(y, y_ref) -> float:

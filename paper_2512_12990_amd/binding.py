@@ -33,6 +33,15 @@ class CacheStats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("msb_hit", "msb_miss", "lsb_hit", "lsb_miss")]
 
 
+class SystemSpec(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("flash_gbit_s", "dram_gbit_s", "xpu_tops", "flash_pj_bit", "dram_pj_bit",
+                                          "xpu_tops_w")]
+
+
+class Cost(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("flash_bits", "dram_bits", "ops", "energy_j", "latency_s", "miss_rate_high")]
+
+
 _lib = None
 
 EXPORTS = [
@@ -43,6 +52,7 @@ EXPORTS = [
     "smoe_prefill_bytes", "smoe_prefill_histogram", "smoe_topn_slices",
     "smoe_cache_create", "smoe_cache_destroy", "smoe_cache_init_order", "smoe_cache_snapshot",
     "smoe_cache_access", "smoe_cache_stats_get", "smoe_cache_order",
+    "smoe_system_spec_paper", "smoe_cost_model",
 ]
 
 
@@ -244,6 +254,20 @@ def smoe_topn_slices(hist: np.ndarray, n: int) -> np.ndarray:
     _chk(lib().smoe_topn_slices(hist.ctypes.data_as(C.c_void_p), C.c_int(L), C.c_int(E), C.c_int(n),
                                 out.ctypes.data_as(C.c_void_p), C.byref(cnt)), "smoe_topn_slices")
     return out[: cnt.value].copy()
+
+
+def smoe_system_spec_paper() -> SystemSpec:
+    spec = SystemSpec()
+    _chk(lib().smoe_system_spec_paper(C.byref(spec)), "smoe_system_spec_paper")
+    return spec
+
+
+def smoe_cost_model(spec: SystemSpec, stats: dict, msb_slice_bytes: int, lsb_slice_bytes: int, ops: float) -> dict:
+    st = CacheStats(stats["msb_hit"], stats["msb_miss"], stats["lsb_hit"], stats["lsb_miss"])
+    out = Cost()
+    _chk(lib().smoe_cost_model(C.byref(spec), C.byref(st), C.c_uint64(msb_slice_bytes), C.c_uint64(lsb_slice_bytes),
+                               C.c_double(ops), C.byref(out)), "smoe_cost_model")
+    return {n: getattr(out, n) for n, _ in Cost._fields_}
 
 
 class Cache:

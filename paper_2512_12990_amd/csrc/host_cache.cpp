@@ -125,3 +125,31 @@ extern "C" int smoe_topn_slices(const uint32_t* hist_host, int L, int E, int N, 
   *n_out = n;
   return SMOE_OK;
 }
+
+// ---- modeled cost on the paper's target system (Section 5) ---------------------------------
+extern "C" int smoe_system_spec_paper(smoe_system_spec* out) {
+  if (!out) return SMOE_EINVAL;
+  out->flash_gbit_s = 10.0; out->dram_gbit_s = 104.0; out->xpu_tops = 16.4;
+  out->flash_pj_bit = 103.0; out->dram_pj_bit = 1.5; out->xpu_tops_w = 3.18;
+  return SMOE_OK;
+}
+
+extern "C" int smoe_cost_model(const smoe_system_spec* spec, const smoe_cache_stats* stats, uint64_t msb_slice_bytes,
+                               uint64_t lsb_slice_bytes, double ops, smoe_cost* out) {
+  if (!spec || !stats || !out) return SMOE_EINVAL;
+  if (!(spec->flash_gbit_s > 0) || !(spec->dram_gbit_s > 0) || !(spec->xpu_tops > 0) || !(spec->xpu_tops_w > 0) || ops < 0)
+    return SMOE_EINVAL;
+  const double bm = (double)msb_slice_bytes, bl = (double)lsb_slice_bytes;
+  const double miss_bytes = (double)stats->msb_miss * bm + (double)stats->lsb_miss * bl;
+  const double used_bytes = (double)(stats->msb_hit + stats->msb_miss) * bm + (double)(stats->lsb_hit + stats->lsb_miss) * bl;
+  out->flash_bits = 8.0 * miss_bytes;
+  out->dram_bits = 8.0 * (used_bytes + miss_bytes);
+  out->ops = ops;
+  out->energy_j = out->flash_bits * spec->flash_pj_bit * 1e-12 + out->dram_bits * spec->dram_pj_bit * 1e-12 +
+                  ops / (spec->xpu_tops_w * 1e12);
+  out->latency_s = out->flash_bits / (spec->flash_gbit_s * 1e9) + out->dram_bits / (spec->dram_gbit_s * 1e9) +
+                   ops / (spec->xpu_tops * 1e12);
+  const double req = (double)(stats->msb_hit + stats->msb_miss);
+  out->miss_rate_high = req > 0 ? miss_bytes / (req * (bm + bl)) : 0.0;
+  return SMOE_OK;
+}

@@ -186,3 +186,69 @@ def test_dsv2lite_stack_26_layers_with_slice_lru(ctx):
         err_moe = O.max_abs_rel(t2np(y_moe), yref - xin)
         say("    max-abs-rel with residual %.3g, MoE term %.3g" % (err, err_moe))
         assert err <= TOL and err_moe <= TOL
+
+
+def test_prefill_warmup_then_decode_small_stack(ctx):
+    """Predictive cache warmup end to end (Section 4.3) on a small 3-layer stack: the prompt goes
+    through the prefill entry point layer by layer (supplied popularity-skewed logits), the
+    per-layer histograms rank the slices, the ranked list initialises the slice LRU, and the decode
+    steps that follow take their masks and routing bias from it.  Every integer result (histogram,
+    ranking, routing, precision, LRU state) is compared exactly with the oracle's pipeline on every
+    step, the layer outputs within tolerance; the warmed cache must miss less than an empty one."""
+    L, T, steps = 3, 160, 12
+    shp = synth.LayerShape(256, 16, 128, 2, 64, act="bf16")
+    E, k, d = shp.n_experts, shp.top_k, shp.d_model
+    layers = [LayerPair(ctx, shp, seed=33, layer=l) for l in range(L)]
+    z_all = [synth.zipf_logits(33, l, T + steps, E, period=T + steps) for l in range(L)]   # one hot set throughout
+    x_pre = synth.activations(33, T, d, "bf16").cuda()
+    say("warmup stack: prefill of", T, "tokens through", L, "layers")
+    hist = np.zeros((L, E), np.uint32)
+    x = x_pre
+    for l in range(L):
+        zl = z_all[l][:T].cuda().contiguous()
+        y, idx, w, h = B.smoe_prefill_histogram(ctx, layers[l].routed, None, x, k, logits=zl, add_residual=True)
+        ridx, rw = O.route(z_all[l][:T].numpy(), None, k)
+        assert np.array_equal(idx.cpu().numpy(), ridx)
+        hist[l] = h.cpu().numpy().view(np.uint32)
+        assert np.array_equal(hist[l], O.histogram(ridx, E))
+        yref = O.prefill_layer(t2np(x).astype(np.float64), layers[l].oracle_routed(), ridx,
+                               w.cpu().numpy().astype(np.float64), add_residual=True)
+        assert O.max_abs_rel(t2np(y), yref) <= TOL
+        x = renorm(y)
+    cap = (2 * L * E) // 4
+    ids = B.smoe_topn_slices(hist, cap)
+    assert np.array_equal(ids, O.topn_slices(hist, cap))
+    cache, ocache, empty = B.Cache(L, E, cap), O.SliceLRU(L, E, cap), B.Cache(L, E, cap)
+    cache.init_order(ids)
+    ocache.init_order(ids)
+    x_dec = synth.activations(34, steps, d, "bf16").cuda()
+    say("  decode of", steps, "tokens from the warmed cache")
+    for t in range(steps):
+        x = x_dec[t].clone()
+        for l in range(L):
+            (m1, b1), (m2, b2) = cache.snapshot(l, 1.0), ocache.snapshot(l, 1.0)
+            assert np.array_equal(m1, m2) and np.array_equal(b1, b2)
+            zt = z_all[l][T + t]
+            idx = torch.empty(k, dtype=torch.int32, device="cuda:0")
+            w = torch.empty(k, dtype=torch.float32, device="cuda:0")
+            prec = torch.empty(k, dtype=torch.uint8, device="cuda:0")
+            y = B.smoe_decode_layer(ctx, layers[l].routed, None, x, k, logits=zt.cuda(), bias=dev(b1),
+                                    slice_mask=dev(m1), add_residual=True, idx_out=idx, w_out=w, prec_out=prec)
+            ridx, rw = O.route(zt.numpy()[None], b1, k)
+            rprec = O.precision_select(ridx[0], rw[0], m1)
+            idx, prec = idx.cpu().numpy(), prec.cpu().numpy()
+            assert np.array_equal(idx, ridx[0]) and np.array_equal(prec, rprec), (t, l)
+            yref = O.moe_layer(t2np(x).astype(np.float64), layers[l].oracle_routed(), ridx[0],
+                               w.cpu().numpy().astype(np.float64), rprec, add_residual=True)
+            assert O.max_abs_rel(t2np(y), yref) <= TOL, (t, l)
+            want = np.ones(k, np.uint8)
+            cache.access(l, idx, want)
+            ocache.access(l, ridx[0], want)
+            # the same requests against a cache that starts empty (it does not steer the routing here)
+            empty.access(l, idx, want)
+            x = renorm(y)
+        assert cache.order() == ocache.order
+    sw, se = cache.stats(), empty.stats()
+    assert sw == ocache.stats
+    say("  MSB misses in", steps, "steps: warmed", sw["msb_miss"], "empty", se["msb_miss"])
+    assert sw["msb_miss"] < se["msb_miss"]
