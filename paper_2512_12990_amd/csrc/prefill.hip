@@ -32,7 +32,8 @@ struct __attribute__((packed)) U32x2Unaligned { uint32_t x, y; };
 //   hist[e]    number of (token, slot) pairs routed to e (the per-expert access count of the layer)
 //   offsets[e] first row of expert e in the grouped layout (offsets[E] = total)
 //   tiles[0]   number of row tiles; tiles[1 + 2i], tiles[2 + 2i] = expert and first row (inside the
-//              expert) of tile i, experts ascending
+//              expert) of tile i, tiles with more rows first (equal sizes: expert, then row,
+//              ascending), so that the work-groups that start last are the short ones
 //   rows[p]    flat (token*k + slot) index of the p-th row of the grouped layout, ascending inside an
 //              expert; pos = inverse of rows.
 __global__ __launch_bounds__(GR_THREADS) void group_kernel(const int32_t* idx, int n, int E, uint32_t* hist,
@@ -61,12 +62,30 @@ __global__ __launch_bounds__(GR_THREADS) void group_kernel(const int32_t* idx, i
   p += off;
   for (int i = i0; i < i1; i++)
     if (idx[i] == e) { rows[p] = i; pos[i] = p; p++; }
+  const int ne = cnt[e];
   if (tid == 0) {
-    const int ne = cnt[e];
     hist[e] = (uint32_t)ne;
     offsets[e] = off;
-    for (int m0 = 0; m0 < ne; m0 += PF_BM) { tiles[1 + 2 * nt] = e; tiles[2 + 2 * nt] = m0; nt++; }
-    if (e == E - 1) { offsets[E] = off + ne; tiles[0] = nt; }
+    if (e == E - 1) { offsets[E] = off + ne; tiles[0] = nt + (ne + PF_BM - 1) / PF_BM; }
+  }
+  // Position of each of this expert's tiles in the list = number of tiles that precede it: every
+  // full tile precedes a ragged one; full tiles among themselves and ragged tiles of equal size go
+  // by expert (an expert has at most one ragged tile, its last).
+  const int n_full = ne / PF_BM, rem = ne - n_full * PF_BM;
+  for (int j = tid; j < n_full + (rem > 0); j += GR_THREADS) {
+    int rank;
+    if (j < n_full) {
+      rank = j;
+      for (int x = 0; x < e; x++) rank += cnt[x] / PF_BM;
+    } else {
+      rank = 0;
+      for (int x = 0; x < E; x++) {
+        const int fx = cnt[x] / PF_BM, rx = cnt[x] - fx * PF_BM;
+        rank += fx + (rx > rem || (rx == rem && x < e));
+      }
+    }
+    tiles[1 + 2 * rank] = e;
+    tiles[2 + 2 * rank] = j * PF_BM;
   }
 }
 
