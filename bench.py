@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=4)
     ap.add_argument("--workload", choices=["decode", "prefill"], default="decode",
                     help="decode (default, the headline metric) or the prefill grouped GEMM of one Qwen-shaped layer")
+    ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64, 128],
+                    help="decode: quantisation group of the expert weights (default: the workload's 128; 32 is the "
+                         "paper's expert format, with four times the scales and zero-points)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed passes, copy this many MiB device-to-device four times (a kernel of known "
                          "traffic, used to scale the HBM byte counters of a profiler run)")
@@ -60,6 +63,9 @@ def main():
     if args.workload == "prefill":
         return prefill_bench(args)
     wl = synth.DSV2_LAYER
+    if args.group:
+        import dataclasses
+        wl = dataclasses.replace(wl, layer=dataclasses.replace(wl.layer, group=args.group))
     shp = wl.layer
     dev = "cuda:0"
     ctx = B.Ctx(0)

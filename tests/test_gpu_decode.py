@@ -192,6 +192,23 @@ def test_medium_bf16_layer_ragged(ctx):
         say("  fused", fused, "worst max-abs-rel", worst)
 
 
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_group32_layer(ctx, dt):
+    # the paper's expert format: groups of 32 (Section 5.1, "G32 asymmetric"): one scale and one
+    # zero-point per 32-chunk of every row; d_ff = 416 leaves a ragged chunk count (13)
+    say("group-32 layer", dt)
+    shp = synth.LayerShape(512, 10, 416, 3, 32, n_shared=1, shared_d_ff=224, act=dt)
+    wl = synth.Workload("g32", shp, steps=5, seed=17)
+    pair = LayerPair(ctx, shp, seed=wl.seed)
+    x_all = synth.activations(wl.seed, wl.steps, shp.d_model, shp.act)
+    masks = synth.bernoulli_masks(wl.seed, wl.steps, shp.n_experts)
+    masks[1, :] = 3
+    logits = synth.normal_logits(wl.seed, wl.steps, shp.n_experts)
+    for fused in (False, True):
+        worst = _run_layer_steps(ctx, wl, pair, range(wl.steps), masks, None, logits, x_all, fused, add_residual=fused)
+        say("  fused", fused, "worst max-abs-rel", worst)
+
+
 def test_dense_ffn_through_shared_bank(ctx):
     # no routed bank at all: a dense SwiGLU run HIGH; K of the down projection is not a multiple
     # of the group (416 = 3*128 + 32)
