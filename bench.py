@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64, 128],
                     help="decode: quantisation group of the expert weights (default: the workload's 128; 32 is the "
                          "paper's expert format, with four times the scales and zero-points)")
+    ap.add_argument("--with-shared", action="store_true",
+                    help="prefill: add the Qwen-shaped shared expert (d_ff 5632 behind a sigmoid gate) that every "
+                         "token passes through; reported as its own line, not the headline")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed passes, copy this many MiB device-to-device four times (a kernel of known "
                          "traffic, used to scale the HBM byte counters of a profiler run)")
@@ -219,26 +222,39 @@ def prefill_bench(args):
         B.smoe_quantize_slice(ctx, routed, e, wg[None], wu[None], wd[None])
     x = synth.activations(wl.seed, T, shp.d_model, "bf16").to(dev)
     wr = synth.router_weight(wl.seed, 0, shp.n_experts, shp.d_model).to(dev)
-    scratch = torch.empty(B.smoe_prefill_bytes(T, shp.n_experts, shp.top_k, shp.d_model, shp.d_ff), dtype=torch.uint8, device=dev)
+    shared, wsg, f_s = None, None, 0
+    if args.with_shared:
+        f_s = synth.QWEN_STACK.layer.shared_d_ff
+        shared = B.Bank(ctx, 1, shp.d_model, f_s, shp.group, "bf16", "bf16")
+        wg, wu, wd = synth.expert_weights(wl.seed, 0, 1000, shp.d_model, f_s, "bf16", dev)
+        B.smoe_quantize_slice(ctx, shared, 0, wg[None], wu[None], wd[None])
+        wsg = synth.shared_gate_weight(wl.seed, 0, shp.d_model, "bf16").to(dev)
+    scratch = torch.empty(B.smoe_prefill_bytes(T, shp.n_experts, shp.top_k, shp.d_model, shp.d_ff, f_s), dtype=torch.uint8,
+                          device=dev)
     steps = min(args.steps, 50)
     for _ in range(3):
-        B.smoe_prefill_histogram(ctx, routed, None, x, shp.top_k, w_router=wr, add_residual=True, scratch=scratch)
+        B.smoe_prefill_histogram(ctx, routed, shared, x, shp.top_k, w_router=wr, shared_gate_w=wsg, add_residual=True,
+                                 scratch=scratch)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ev0.record()
     for _ in range(steps):
-        B.smoe_prefill_histogram(ctx, routed, None, x, shp.top_k, w_router=wr, add_residual=True, scratch=scratch)
+        B.smoe_prefill_histogram(ctx, routed, shared, x, shp.top_k, w_router=wr, shared_gate_w=wsg, add_residual=True,
+                                 scratch=scratch)
     ev1.record()
     torch.cuda.synchronize()
     ms = ev0.elapsed_time(ev1) / steps
-    flops = 2.0 * T * shp.top_k * 3 * shp.d_model * shp.d_ff
+    flops = 2.0 * T * shp.top_k * 3 * shp.d_model * shp.d_ff + 2.0 * T * 3 * shp.d_model * f_s
     wbytes = shp.n_experts * sum(slot_bytes(shp.d_model, shp.d_ff, shp.group, 1))
+    if f_s:
+        wbytes += sum(slot_bytes(shp.d_model, f_s, shp.group, 1))
     print(json.dumps({
         "metric": "prefill MoE-layer ms (2048 tokens, grouped expert GEMM + histogram)", "value": ms, "unit": "ms/layer",
         "n_gpus": 1, "steps": steps, "warmup": 3, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 MFMA, fp32 accumulate, u4+u4 sliced weights", "data": "synthetic",
         "config": {"workload": "Qwen1.5-MoE-shaped prefill layer (BASELINE configs[4], one layer)", "tokens": T,
-                   "n_experts": shp.n_experts, "top_k": shp.top_k, "d_model": shp.d_model, "d_ff": shp.d_ff},
+                   "n_experts": shp.n_experts, "top_k": shp.top_k, "d_model": shp.d_model, "d_ff": shp.d_ff,
+                   "shared_d_ff": f_s},
         "tokens_per_s": T / (ms * 1e-3),
         "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
                      "frac": flops / (ms * 1e-3) / 1e12 / 2500.0, "flops_per_step": flops,

@@ -138,13 +138,17 @@ int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* s
                       int32_t* idx_out_dev, float* w_out_dev, uint8_t* prec_out_dev);
 
 /* ---- prefill_histogram (Section 4.3) ------------------------------------------------------ */
-/* Bytes of device scratch smoe_prefill_histogram needs for T tokens. */
+/* Bytes of device scratch smoe_prefill_histogram needs for T tokens; shared_d_ff = d_ff of the shared
+ * experts (0 without a shared bank). */
 int smoe_prefill_bytes(int T, int E, int k, int d_model, int d_ff, int shared_d_ff, size_t* scratch_bytes);
 /* T tokens through one layer, every expert HIGH: routes each token (as smoe_route), counts
  * hist_dev[e] = number of (token, slot) pairs sent to expert e (uint32 [E], overwritten), runs the
  * experts as a grouped GEMM over the tokens of each expert, and writes
- * y_dev[t] = sum_j w[t,j] * FFN_{idx[t,j]}(x[t]) (+ shared experts, + x[t] if add_residual).
- * x_dev, y_dev: act_dtype [T, d_model] (bf16 only); idx_dev int32 [T,k]; w_dev fp32 [T,k]. */
+ * y_dev[t] = sum_j w[t,j] * FFN_{idx[t,j]}(x[t]) + gamma[t] * sum_shared FFN_s(x[t]) (+ x[t] if
+ * add_residual), gamma[t] = sigmoid(shared_gate_w . x[t]) or 1 without a gate vector (act dtype
+ * [d_model]); the shared experts see every token and run as dense GEMMs.
+ * x_dev, y_dev: act_dtype [T, d_model] (bf16 only); idx_dev int32 [T,k]; w_dev fp32 [T,k].
+ * d_model and every d_ff must be multiples of 64, groups powers of two >= 32. */
 int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, int T,
                            const void* x_dev, int act_dtype, int k, const float* logits_dev,
                            const float* w_router_dev, int norm_topk, float routed_scale,

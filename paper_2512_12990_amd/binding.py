@@ -230,7 +230,7 @@ def smoe_prefill_histogram(ctx: Ctx, routed: Bank, shared: Optional[Bank], x: to
     T, d = x.shape
     E = routed.desc.n_experts
     dev = x.device
-    need = smoe_prefill_bytes(T, E, k, d, routed.desc.d_ff, shared.desc.d_ff * shared.desc.n_experts if shared else 0)
+    need = smoe_prefill_bytes(T, E, k, d, routed.desc.d_ff, shared.desc.d_ff if shared else 0)
     if scratch is None:
         scratch = torch.empty(need, dtype=torch.uint8, device=dev)
     y = torch.empty_like(x)

@@ -102,6 +102,10 @@ struct GemmArgs {
   const float* wgt;         // [T*k] gate weights (flat token*k + slot)
   int k, d_model, d_ff;
   int n_col_tiles;          // column tiles of this GEMM (grid = 8 * ceil(max row tiles / 8) * n_col_tiles)
+  // dense_rows > 0: one expert (dense_expert) takes rows 0..dense_rows-1 = tokens in their own order
+  // (a shared expert): no tile list, no row list, H and O rows are token rows; wgt[t] scales row t
+  int dense_rows, dense_expert;
+  int accumulate;           // MODE 1: add to O instead of overwriting it
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -128,10 +132,17 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
   // stay there while they are re-read.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int ti = (slot / a.n_col_tiles) * 8 + xcd, nt = slot % a.n_col_tiles;
-  if (ti >= a.tiles[0]) return;
-  const int e = a.tiles[1 + 2 * ti], m0 = a.tiles[2 + 2 * ti];
-  const int row0 = a.offsets[e];
-  const int m_cnt = min(PF_BM, a.offsets[e + 1] - row0 - m0);
+  int e, m0, row0, m_cnt;
+  if (a.dense_rows) {
+    if (ti * PF_BM >= a.dense_rows) return;
+    e = a.dense_expert; m0 = ti * PF_BM; row0 = 0;
+    m_cnt = min(PF_BM, a.dense_rows - m0);
+  } else {
+    if (ti >= a.tiles[0]) return;
+    e = a.tiles[1 + 2 * ti]; m0 = a.tiles[2 + 2 * ti];
+    row0 = a.offsets[e];
+    m_cnt = min(PF_BM, a.offsets[e + 1] - row0 - m0);
+  }
   const int K = MODE == 0 ? a.d_model : a.d_ff;
   const int N = MODE == 0 ? a.d_ff : a.d_model;         // output columns of this GEMM
   const int mh = wave >> 2, nq = wave & 3;
@@ -146,7 +157,7 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
 #pragma unroll
   for (int q = 0; q < 3; q++) {
     const int i = tid + PF_NT * q, r = min(i >> 3, m_cnt - 1), c = i & 7;
-    if (MODE == 0) a_src[q] = (uint32_t)(a.rows[row0 + m0 + r] / a.k) * (uint32_t)a.d_model + c * 8;
+    if (MODE == 0) a_src[q] = (uint32_t)(a.dense_rows ? m0 + r : a.rows[row0 + m0 + r] / a.k) * (uint32_t)a.d_model + c * 8;
     else a_src[q] = (uint32_t)(row0 + m0 + r) * (uint32_t)a.d_ff + c * 8;
   }
   // B: thread -> (weight row b of the tile, half hb of the 64 columns of the K slice).  MODE 0: the 64
@@ -327,25 +338,47 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
         const float hv = g / (1.0f + __expf(-g)) * u;
         if (col < N) a.h[prow * a.d_ff + col] = (uint16_t)f32_to_bf16_bits(hv);
       } else {
-        const float wt = a.wgt[a.rows[prow]];
+        const float wt = a.wgt[a.dense_rows ? (int)prow : a.rows[prow]];
 #pragma unroll
         for (int j = 0; j < 2; j++) {
           const int col = nt * PF_BN + nq * 64 + j * 32 + (lane & 31);
-          if (col < N) a.o[prow * a.d_model + col] = wt * acc[i][j][r];
+          if (col < N) {
+            float* dst = a.o + prow * a.d_model + col;
+            *dst = a.accumulate ? *dst + wt * acc[i][j][r] : wt * acc[i][j][r];
+          }
         }
       }
     }
   }
 }
 
-// Y[t, c] = sum_j O[pos[t*k + j], c]  (+ x[t, c]); 4 columns per thread.
-__global__ __launch_bounds__(256) void combine_kernel(const float* o, const int32_t* pos, const uint16_t* x, uint16_t* y,
-                                                      int k, int d_model, int add_residual) {
+// gamma[t] = sigmoid(w_sg . x[t]) (one wave per token), or 1 without a gate vector: the weight of
+// the shared experts' output for token t.
+__global__ __launch_bounds__(256) void shared_gate_kernel(const uint16_t* x, const uint16_t* w_sg, int T, int d, float* gamma) {
+  const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  float g = 1.0f;
+  if (w_sg) {
+    float s = 0.0f;
+    for (int i = lane; i < d; i += 64) s = fmaf(bf16_bits_to_f32(w_sg[i]), bf16_bits_to_f32(x[(size_t)t * d + i]), s);
+    s = wave_sum(s);
+    g = 1.0f / (1.0f + __expf(-s));
+  }
+  if (lane == 0) gamma[t] = g;
+}
+
+// Y[t, c] = sum_j O[pos[t*k + j], c]  (+ OS[t, c], the shared experts' sum)  (+ x[t, c]); 4 columns per thread.
+__global__ __launch_bounds__(256) void combine_kernel(const float* o, const int32_t* pos, const float* o_s, const uint16_t* x,
+                                                      uint16_t* y, int k, int d_model, int add_residual) {
   const int t = blockIdx.x;
   for (int c = threadIdx.x * 4; c < d_model; c += 256 * 4) {
     float4 s = make_float4(0, 0, 0, 0);
     for (int j = 0; j < k; j++) {
       const float4 v = *(const float4*)(o + (size_t)pos[t * k + j] * d_model + c);
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    if (o_s) {
+      const float4 v = *(const float4*)(o_s + (size_t)t * d_model + c);
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
     if (add_residual) {
@@ -363,11 +396,11 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* o, const int3
 // ------------------------------------------------------------------------------- host entry
 static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-struct PrefillLayout { size_t rows, pos, offsets, tiles, h, o, total; };
+struct PrefillLayout { size_t rows, pos, offsets, tiles, h, o, gamma, h_s, o_s, total; };
 
 static inline int max_tiles(int T, int E, int k) { return E + (T * k) / PF_BM; }
 
-static PrefillLayout prefill_layout(int T, int E, int k, int d_model, int d_ff) {
+static PrefillLayout prefill_layout(int T, int E, int k, int d_model, int d_ff, int shared_d_ff) {
   PrefillLayout L;
   size_t off = 0;
   L.rows = off;    off = up256(off + (size_t)T * k * 4);
@@ -376,6 +409,12 @@ static PrefillLayout prefill_layout(int T, int E, int k, int d_model, int d_ff) 
   L.tiles = off;   off = up256(off + (size_t)(1 + 2 * max_tiles(T, E, k)) * 4);
   L.h = off;       off = up256(off + (size_t)T * k * d_ff * 2);
   L.o = off;       off = up256(off + (size_t)T * k * d_model * 4);
+  L.gamma = L.h_s = L.o_s = off;
+  if (shared_d_ff > 0) {       // one shared expert at a time: its H rows, and the running sum of their outputs
+    L.gamma = off; off = up256(off + (size_t)T * 4);
+    L.h_s = off;   off = up256(off + (size_t)T * shared_d_ff * 2);
+    L.o_s = off;   off = up256(off + (size_t)T * d_model * 4);
+  }
   L.total = off;
   return L;
 }
@@ -383,7 +422,7 @@ static PrefillLayout prefill_layout(int T, int E, int k, int d_model, int d_ff) 
 extern "C" int smoe_prefill_bytes(int T, int E, int k, int d_model, int d_ff, int shared_d_ff, size_t* scratch_bytes) {
   if (!scratch_bytes) return SMOE_EINVAL;
   if (T <= 0 || E <= 0 || k <= 0 || k > E || d_model <= 0 || d_ff <= 0 || shared_d_ff < 0) return SMOE_ESHAPE;
-  *scratch_bytes = prefill_layout(T, E, k, d_model, d_ff).total;
+  *scratch_bytes = prefill_layout(T, E, k, d_model, d_ff, shared_d_ff).total;
   return SMOE_OK;
 }
 
@@ -395,17 +434,23 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
                                       uint32_t* hist_dev) {
   if (!ctx || !routed || !x_dev || !scratch_dev || !y_dev || !idx_dev || !w_dev || !hist_dev) return SMOE_EINVAL;
   if (!logits_dev && !w_router_dev) return SMOE_EINVAL;
-  if (shared || shared_gate_w_dev) return SMOE_ENOTIMPL;          // shared-expert group: decode path only
+  if (shared_gate_w_dev && !shared) return SMOE_EINVAL;
   if (act_dtype != SMOE_BF16) return SMOE_ENOTIMPL;
-  if (routed->device != ctx->device) return SMOE_EINVAL;
+  if (routed->device != ctx->device || (shared && shared->device != ctx->device)) return SMOE_EINVAL;
   const int E = routed->desc.n_experts, d = routed->desc.d_model, f = routed->desc.d_ff;
   if (T <= 0 || k <= 0 || k > E || k > SMOE_MAX_TOPK || E > SMOE_MAX_EXPERTS) return SMOE_ESHAPE;
   if (f % PF_BK || d % PF_BK || routed->desc.group < 32 || (routed->desc.group & (routed->desc.group - 1))) return SMOE_ESHAPE;
   if ((size_t)T * d >= 0x7FFFFFFFu || (size_t)T * k * f >= 0x7FFFFFFFu) return SMOE_ESHAPE;   // 32-bit element offsets
+  const int f_s = shared ? shared->desc.d_ff : 0;
+  if (shared) {
+    const int gs = shared->desc.group;
+    if (shared->desc.d_model != d || f_s % PF_BK || gs < 32 || (gs & (gs - 1))) return SMOE_ESHAPE;
+    if ((size_t)T * f_s >= 0x7FFFFFFFu) return SMOE_ESHAPE;
+  }
   if (!aligned16(x_dev) || !aligned16(y_dev) || !aligned16(idx_dev) || !aligned16(w_dev) || !aligned16(hist_dev) ||
-      !aligned16(logits_dev) || !aligned16(w_router_dev) || (((uintptr_t)scratch_dev) & 255u))
+      !aligned16(logits_dev) || !aligned16(w_router_dev) || !aligned16(shared_gate_w_dev) || (((uintptr_t)scratch_dev) & 255u))
     return SMOE_EALIGN;
-  const PrefillLayout L = prefill_layout(T, E, k, d, f);
+  const PrefillLayout L = prefill_layout(T, E, k, d, f, f_s);
   if (scratch_bytes < L.total) return SMOE_ESIZE;
   HIPCHK(ctx, hipSetDevice(ctx->device));
   uint8_t* s = (uint8_t*)scratch_dev;
@@ -432,7 +477,29 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
   g.w = routed->dev.dn; g.n_col_tiles = (d + PF_BN - 1) / PF_BN;
   if (g.sc_bf16) grouped_gemm_kernel<1, 1><<<mt8 * g.n_col_tiles, PF_NT, 0, st>>>(g);
   else grouped_gemm_kernel<1, 0><<<mt8 * g.n_col_tiles, PF_NT, 0, st>>>(g);
-  combine_kernel<<<T, 256, 0, st>>>(o, pos, (const uint16_t*)x_dev, (uint16_t*)y_dev, k, d, add_residual);
+  float* o_s = nullptr;
+  if (shared) {
+    // the shared experts see every token: dense GEMMs over the token rows in their own order, one
+    // expert after the other into one H buffer, their gate-weighted outputs summed in O_s
+    float* gamma = (float*)(s + L.gamma);
+    o_s = (float*)(s + L.o_s);
+    shared_gate_kernel<<<(T + 3) / 4, 256, 0, st>>>((const uint16_t*)x_dev, (const uint16_t*)shared_gate_w_dev, T, d, gamma);
+    GemmArgs q{};
+    q.sc_bf16 = shared->dev.sc_bf16; q.group_shift = __builtin_ctz((unsigned)shared->dev.group);
+    q.x = (const uint16_t*)x_dev; q.h = (uint16_t*)(s + L.h_s); q.o = o_s; q.wgt = gamma; q.k = 1; q.d_model = d; q.d_ff = f_s;
+    q.dense_rows = T;
+    const int nt8 = ((T + PF_BM - 1) / PF_BM + 7) / 8 * 8;
+    for (int e = 0; e < shared->desc.n_experts; e++) {
+      q.dense_expert = e; q.accumulate = e > 0;
+      q.w = shared->dev.gu; q.n_col_tiles = (2 * f_s + PF_BN - 1) / PF_BN;
+      if (q.sc_bf16) grouped_gemm_kernel<0, 1><<<nt8 * q.n_col_tiles, PF_NT, 0, st>>>(q);
+      else grouped_gemm_kernel<0, 0><<<nt8 * q.n_col_tiles, PF_NT, 0, st>>>(q);
+      q.w = shared->dev.dn; q.n_col_tiles = (d + PF_BN - 1) / PF_BN;
+      if (q.sc_bf16) grouped_gemm_kernel<1, 1><<<nt8 * q.n_col_tiles, PF_NT, 0, st>>>(q);
+      else grouped_gemm_kernel<1, 0><<<nt8 * q.n_col_tiles, PF_NT, 0, st>>>(q);
+    }
+  }
+  combine_kernel<<<T, 256, 0, st>>>(o, pos, o_s, (const uint16_t*)x_dev, (uint16_t*)y_dev, k, d, add_residual);
   HIPCHK(ctx, hipGetLastError());
   return SMOE_OK;
 }

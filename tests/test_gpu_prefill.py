@@ -60,6 +60,36 @@ def test_prefill_small_all_tokens(ctx, T, E, k, d, f, G):
         assert O.max_abs_rel(yg, yref) <= TOL
 
 
+@pytest.mark.parametrize("n_shared,f_s,gate", [(1, 320, True), (2, 128, False)])
+def test_prefill_with_shared_experts(ctx, n_shared, f_s, gate):
+    # the shared-expert group sees every token (dense GEMMs over the token rows): one wide shared expert
+    # behind a sigmoid gate (Qwen shape) or two plain ones (DeepSeek shape); 230 tokens = one full
+    # 192-row tile and a ragged one; 320 = 2.5 column tiles of the gate/up GEMM
+    T, E, k, d, f, G = 230, 6, 2, 256, 128, 64
+    say("prefill with shared experts", n_shared, f_s, gate)
+    shp = synth.LayerShape(d, E, f, k, G, n_shared=n_shared, shared_d_ff=f_s, shared_gate=gate, act="bf16")
+    pair = LayerPair(ctx, shp, seed=23)
+    x = synth.activations(23, T, d, "bf16").cuda()
+    wr = synth.router_weight(23, 0, E, d, std=0.05).cuda()
+    wsg = synth.shared_gate_weight(23, 0, d, "bf16", std=0.05).cuda() if gate else None
+    for resid in (False, True):
+        y, idx, w, hist = B.smoe_prefill_histogram(ctx, pair.routed, pair.shared, x, k, w_router=wr, shared_gate_w=wsg,
+                                                   add_residual=resid)
+        ridx, rw = _check_routing(ctx, x, wr, k, idx, w, hist, E)
+        yref = O.prefill_layer(t2np(x).astype(np.float64), pair.oracle_routed(), ridx,
+                               rw.astype(np.float32).astype(np.float64), pair.oracle_shared(),
+                               None if wsg is None else t2np(wsg), add_residual=resid)
+        yg = t2np(y)
+        for t in range(T):
+            assert O.max_abs_rel(yg[t], yref[t]) <= TOL, t
+    # a prefill layer and the decode layer agree on a token (both HIGH): same semantics on both paths
+    t = 7
+    mask = np.full(E, 3, np.uint8)
+    yd = B.smoe_expert_ffn(ctx, pair.routed, pair.shared, x[t].clone(), idx[t].clone(), w[t].clone(),
+                           torch.from_numpy(mask).cuda(), shared_gate_w=wsg, add_residual=True)
+    assert O.max_abs_rel(t2np(yd), t2np(y[t])) <= TOL
+
+
 def test_prefill_empty_expert_and_given_logits(ctx):
     say("prefill with an expert nobody selects")
     T, E, k, d, f, G = 64, 4, 2, 128, 64, 32
