@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64, 128],
                     help="decode: quantisation group of the expert weights (default: the workload's 128; 32 is the "
                          "paper's expert format, with four times the scales and zero-points)")
+    ap.add_argument("--tokens", type=int, default=1,
+                    help="decode: tokens per step that pass the layer together in one pair of launches (1 = the headline "
+                         "single-batch workload; 2-16 = smoe_decode_layer_multi, reported per token)")
     ap.add_argument("--with-shared", action="store_true",
                     help="prefill: add the Qwen-shaped shared expert (d_ff 5632 behind a sigmoid gate) that every "
                          "token passes through; reported as its own line, not the headline")
@@ -95,14 +98,24 @@ def main():
     import ctypes as C
     fn = B.lib().smoe_decode_layer
     vp = lambda t: C.c_void_p(t.data_ptr())
-    calls = [(ctx.h, routed.h, shared.h, vp(x_all[i]), C.c_int(B.BF16), C.c_int(shp.top_k), vp(z_all[i]), None,
-              vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), None, C.c_int(0), vp(y[i]),
-              vp(idx[i]), None, vp(prec[i])) for i in range(n_in)]
+    TT = args.tokens
+    if TT == 1:
+        calls = [(ctx.h, routed.h, shared.h, vp(x_all[i]), C.c_int(B.BF16), C.c_int(shp.top_k), vp(z_all[i]), None,
+                  vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), None, C.c_int(0), vp(y[i]),
+                  vp(idx[i]), None, vp(prec[i])) for i in range(n_in)]
+    else:
+        # step t takes the TT consecutive tokens that start at row (t * TT) mod n_in
+        assert 2 <= TT <= 16 and n_in % TT == 0
+        fn = B.lib().smoe_decode_layer_multi
+        calls = [(ctx.h, routed.h, shared.h, C.c_int(TT), vp(x_all[i]), C.c_int(B.BF16), C.c_int(shp.top_k), vp(z_all[i]),
+                  vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), None, C.c_int(0), vp(y[i]),
+                  vp(idx[i]), None, vp(prec[i])) for i in range(0, n_in, TT)]
+    n_calls = len(calls)
 
     def step(t):
-        rc = fn(*calls[t % n_in])
+        rc = fn(*calls[t % n_calls])
         if rc != 0:
-            raise B.SmoeError("smoe_decode_layer failed: %d" % rc)
+            raise B.SmoeError("decode call failed: %d" % rc)
 
     for t in range(args.warmup):
         step(t)
@@ -128,7 +141,7 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         windows.append(e0.elapsed_time(e1) / args.steps * 1e3)
-    windows.sort()
+    windows = sorted(w / TT for w in windows)
 
     # A plain device-to-device copy of 256 MiB, for scale: what this machine's HBM delivers to a streaming
     # kernel (bytes read + bytes written per second).
@@ -159,10 +172,23 @@ def main():
     hi_gu, hi_dn = slot_bytes(shp.d_model, shp.d_ff, shp.group, 1)
     lo_gu, lo_dn = slot_bytes(shp.d_model, shp.d_ff, shp.group, 0)
     total_bytes = gu_bytes = 0
+    idx_np = idx.cpu().numpy()
     for t in range(args.warmup, args.warmup + args.steps):
-        nh = int(prec_np[t % n_in].sum())
-        gu = (nh + shp.n_shared) * hi_gu + (shp.top_k - nh) * lo_gu + shp.d_model * 2 + shp.n_experts * 9
-        dn = (nh + shp.n_shared) * hi_dn + (shp.top_k - nh) * lo_dn + shp.d_model * 2
+        if TT == 1:
+            nh = int(prec_np[t % n_in].sum())
+            nl = shp.top_k - nh
+        else:
+            # what the step must move: every expert some token of the step selected once, with its LSB
+            # plane if some token runs it HIGH
+            r0 = (t % n_calls) * TT
+            need = {}
+            for tt in range(r0, r0 + TT):
+                for e, p in zip(idx_np[tt], prec_np[tt]):
+                    need[int(e)] = max(need.get(int(e), 0), int(p))
+            nh = sum(need.values())
+            nl = len(need) - nh
+        gu = (nh + shp.n_shared) * hi_gu + nl * lo_gu + TT * (shp.d_model * 2 + shp.n_experts * 9)
+        dn = (nh + shp.n_shared) * hi_dn + nl * lo_dn + TT * shp.d_model * 2
         gu_bytes += gu
         total_bytes += gu + dn
     bytes_per_step = total_bytes / args.steps
@@ -172,15 +198,15 @@ def main():
 
     out = {
         "metric": "decode MoE-layer us/token (+ achieved HBM GB/s as a fraction of MI355X peak)",
-        "value": ms_per_step * 1e3, "unit": "us/token", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": ms_per_step * 1e3 / TT, "unit": "us/token", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "u4+u4 bit-sliced weights, bf16 activations rewritten per 32-chunk as 3 balanced hex digits, signed 4-bit dot products, int32/fp32 accumulate",
         "data": "synthetic",
-        "config": {"workload": "DeepSeek-V2-Lite-shaped MoE layer decode, 1 token/step (BASELINE configs[1])",
+        "config": {"workload": "DeepSeek-V2-Lite-shaped MoE layer decode, %d token%s/step (BASELINE configs[1])" % (TT, "" if TT == 1 else "s"),
                    "d_model": shp.d_model, "n_experts": shp.n_experts, "d_ff": shp.d_ff, "top_k": shp.top_k,
                    "n_shared": shp.n_shared, "group": shp.group, "cached": 32, "cached_high": 16,
-                   "mean_high_slots": float(prec_np.mean() * shp.top_k), "launches_per_step": 2},
-        "hbm_gbps": achieved, "hbm_frac": achieved / HBM_PEAK_GBPS, "bytes_per_token": bytes_per_step,
+                   "mean_high_slots": float(prec_np.mean() * shp.top_k), "launches_per_step": 2, "tokens_per_step": TT},
+        "hbm_gbps": achieved, "hbm_frac": achieved / HBM_PEAK_GBPS, "bytes_per_token": bytes_per_step / TT,
         "host_wall_ms_per_step": wall_ms / args.steps,
         "repeat_windows_us_per_token": {"median": windows[2], "min": windows[0], "max": windows[-1], "n": 5},
         "copy_256mib_gbps": copy_gbps,

@@ -137,6 +137,21 @@ int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* s
                       const void* shared_gate_w_dev, int add_residual, void* y_dev,
                       int32_t* idx_out_dev, float* w_out_dev, uint8_t* prec_out_dev);
 
+/* smoe_decode_layer for T tokens (1 <= T <= 16) that pass the same layer in one pair of launches,
+ * e.g. the draft tokens of a speculative step or a small batch: token t uses row t of x_dev
+ * [T, d_model], logits_dev [T, E] (required: no router mat-vec here), y_dev [T, d_model] and of the
+ * optional outputs idx_out_dev / w_out_dev / prec_out_dev [T, k]; bias and slice mask are shared.
+ * Every token is computed exactly as by smoe_decode_layer.  The work-groups that need the same
+ * weight rows for different tokens run side by side on one XCD, so the weights they share (shared
+ * experts, coinciding routed experts) come from HBM once and from L2 afterwards.  T > 1 needs
+ * d_model a multiple of 64 (SMOE_ESHAPE otherwise). */
+int smoe_decode_layer_multi(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, int T,
+                            const void* x_dev, int act_dtype, int k, const float* logits_dev,
+                            const float* bias_dev, int norm_topk, float routed_scale,
+                            const uint8_t* slice_mask_dev, float tau_head, const void* shared_gate_w_dev,
+                            int add_residual, void* y_dev, int32_t* idx_out_dev, float* w_out_dev,
+                            uint8_t* prec_out_dev);
+
 /* ---- prefill_histogram (Section 4.3) ------------------------------------------------------ */
 /* Bytes of device scratch smoe_prefill_histogram needs for T tokens; shared_d_ff = d_ff of the shared
  * experts (0 without a shared bank). */

@@ -48,7 +48,7 @@ EXPORTS = [
     "smoe_ctx_create", "smoe_ctx_destroy", "smoe_strerror", "smoe_last_hip_error", "smoe_ctx_timing",
     "smoe_ctx_timing_read",
     "smoe_bank_bytes", "smoe_bank_create", "smoe_bank_destroy", "smoe_quantize_slice", "smoe_export_codes",
-    "smoe_route", "smoe_expert_ffn", "smoe_decode_layer",
+    "smoe_route", "smoe_expert_ffn", "smoe_decode_layer", "smoe_decode_layer_multi",
     "smoe_prefill_bytes", "smoe_prefill_histogram", "smoe_topn_slices",
     "smoe_cache_create", "smoe_cache_destroy", "smoe_cache_init_order", "smoe_cache_snapshot",
     "smoe_cache_access", "smoe_cache_stats_get", "smoe_cache_order",
@@ -214,6 +214,21 @@ def smoe_decode_layer(ctx: Ctx, routed: Bank, shared: Optional[Bank], x: torch.T
                                  C.c_float(routed_scale), _p(slice_mask), C.c_float(tau_head), _p(shared_gate_w),
                                  C.c_int(int(add_residual)), _p(y), _p(idx_out), _p(w_out), _p(prec_out)),
          "smoe_decode_layer", ctx.h)
+    return y
+
+
+def smoe_decode_layer_multi(ctx: Ctx, routed: Bank, shared: Optional[Bank], x: torch.Tensor, k: int, logits: torch.Tensor,
+                            bias=None, norm_topk: bool = False, routed_scale: float = 1.0, slice_mask=None,
+                            tau_head: float = 0.0, shared_gate_w=None, add_residual: bool = False, y=None, idx_out=None,
+                            w_out=None, prec_out=None):
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty_like(x)
+    _chk(lib().smoe_decode_layer_multi(ctx.h, routed.h, shared.h if shared else None, C.c_int(T), _p(x),
+                                       C.c_int(_DT[x.dtype]), C.c_int(k), _p(logits), _p(bias), C.c_int(int(norm_topk)),
+                                       C.c_float(routed_scale), _p(slice_mask), C.c_float(tau_head), _p(shared_gate_w),
+                                       C.c_int(int(add_residual)), _p(y), _p(idx_out), _p(w_out), _p(prec_out)),
+         "smoe_decode_layer_multi", ctx.h)
     return y
 
 

@@ -7,6 +7,7 @@
 
 #define SMOE_MAX_SLOTS 24      // top-k (<= 16) routed + up to 8 shared experts
 #define SMOE_MAX_EXPERTS 256
+#define SMOE_MAX_MULTI 16          // tokens of one smoe_decode_layer_multi call
 #define SMOE_MAX_TOPK 16
 #define SMOE_WORKSPACE_BYTES (4u << 20)
 

@@ -101,6 +101,9 @@ struct KargTouch { unsigned t[7]; };
   asm volatile("s_waitcnt lgkmcnt(0)" ::"s"(kt.t[0]), "s"(kt.t[1]), "s"(kt.t[2]), "s"(kt.t[3]), "s"(kt.t[4]), "s"(kt.t[5]),   \
                "s"(kt.t[6])                                                                                               \
                : "memory")
+/* floats between the h vectors of consecutive tokens of a multi-token launch (both kernels must
+ * know it from their leading parameters: room for the largest top-k) */
+#define DEC_H_STRIDE(nsf, f_r) ((nsf) + SMOE_MAX_TOPK * (f_r))
 #define DEC_LEAD_BYTES 56      /* both kernels have 56 bytes of leading parameters before the struct */
 static_assert(sizeof(DecodeArgs) + DEC_LEAD_BYTES <= 8 * 64, "KARGS_TOUCH covers eight lines");
 
@@ -557,6 +560,15 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
   __shared__ __align__(16) uint8_t xvec[StageTraits<ACT>::COMBO_BYTES];
   __shared__ float2 xcs[64];
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
+  // Several tokens in one launch: grid (8, tokens, work-groups / 8), so that the work-groups that
+  // read the same weight rows for different tokens are dispatched together on one XCD and share
+  // its L2.  One token: grid (work-groups, 1, 1).  Token t uses row t of logits, x, y and of the
+  // routing outputs, record t and its own h vector.
+  const int tok = blockIdx.y, wg = (int)blockIdx.x + 8 * (int)blockIdx.z;
+  if (tok) {
+    logits += (size_t)tok * E;
+    x_in = (const uint8_t*)x_in + (size_t)tok * d_model * (ACT == SMOE_BF16 ? 2 : 4);
+  }
   const RouteIn in{logits, bias, mask, E, k, do_route};
   const int d = d_model, C = d >> 5;
   // ---- first instructions: the loads that need only the leading parameters -- x (stager waves)
@@ -574,6 +586,15 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
   if (router) route_load(in, lane, rr);
   KARGS_WAIT(kt);
   __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+  if (tok) {
+    a.h += (size_t)tok * DEC_H_STRIDE(a.n_shared * a.f_s, a.f_r);
+    a.rec += tok;
+    if (a.idx_in) a.idx_in += tok * k;
+    if (a.w_in) a.w_in += tok * k;
+    if (a.idx_out) a.idx_out += tok * k;
+    if (a.w_out) a.w_out += tok * k;
+    if (a.prec_out) a.prec_out += tok * k;
+  }
 
   const unsigned rowb32 = (unsigned)d >> 1;
   const bool live_lane = lane < C;
@@ -588,7 +609,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
   // s = slot (shared experts first), q0 = first entry of the piece inside the slot
   auto setup = [&](bool is_sh, int s, int q0, int e, int prec, const MatK& md) {
     GuPiece pc;
-    int bp = (int)blockIdx.x + s * a.rot;
+    int bp = wg + s * a.rot;
     bp = bp >= n_wg ? bp - n_wg : bp;
     pc.r0 = bp + n_wg * q0;
     pc.po = (unsigned)e * md.ps32 + (unsigned)(2 * pc.r0) * rowb32;
@@ -667,7 +688,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
     issue(pc0, nb0, a.f_s, make_sec(a.sgu, a.n_shared), a.sgu, a.gu_sh_s);
   }
   lds_barrier();
-  if (blockIdx.x == 0) {
+  if (wg == 0) {
     if (router) {                                        // publish for the down kernel and the caller
       if (!have_w) myw = E <= 64 ? route_weights<1>(in, a, lane, rr, mysel) : route_weights<4>(in, a, lane, rr, mysel);
       if (lane < k) {
@@ -752,7 +773,12 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
   uint8_t* xbuf = dyn + wave * WS;
   float2* xcs = (float2*)(xbuf + XB);
   float* part = (float*)(dyn + DEC_NW * WS);         // [combo][row]
-  const int n0 = blockIdx.x * DEC_RPW;
+  const int tok = blockIdx.y;                          // see gateup_kernel
+  const int n0 = ((int)blockIdx.x + 8 * (int)blockIdx.z) * DEC_RPW;
+  if (tok) {
+    rec += tok * (int)(sizeof(RouteRec) / 4);
+    h += (size_t)tok * DEC_H_STRIDE(nsf, f_r);
+  }
   KargTouch kt;
   KARGS_TOUCH(kt, DEC_LEAD_BYTES + (int)sizeof(DecodeArgs));      // two pointers and ten 4-byte leading parameters, then the struct
   bool kargs_here = false;
@@ -847,7 +873,7 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
     float acc = 0.0f;
     for (int c = n_combo_s; c < n_combo; c++) acc += part[c * DEC_RPW + tid];      // routed slots in slot order
     for (int c = 0; c < n_combo_s; c++) acc += part[c * DEC_RPW + tid];            // then the shared experts
-    const int n = n0 + tid;
+    const size_t n = (size_t)tok * a.d_model + n0 + tid;
     if (a.add_residual) acc += load_act<ACT>(a.x, n);
     store_act<ACT>(a.y, n, acc);
   }
@@ -861,7 +887,7 @@ static int ilog2_exact(int v) {
 }
 
 template <int ACT, int SCB>
-static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int n_wg) {
+static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int n_wg, int T) {
   // down kernel: pieces = combos x parts
   const int n_combo_s = a.n_shared * a.ks_s, n_combo = n_combo_s + a.k * a.ks_r;
   int psh = 3;
@@ -880,7 +906,9 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
     }
   }
   std::vector<hipEvent_t>* evs = (ctx->timing && ctx->timing_events) ? (std::vector<hipEvent_t>*)ctx->timing_events : nullptr;
-  const dim3 g1(n_wg), g2(a.d_model / DEC_RPW), blk(DEC_NT);
+  const int n_dn = a.d_model / DEC_RPW;
+  if (T > 1 && ((n_wg & 7) || (n_dn & 7))) return SMOE_ESHAPE;      // the multi-token grid is (8, T, n / 8)
+  const dim3 g1 = T > 1 ? dim3(8, T, n_wg / 8) : dim3(n_wg), g2 = T > 1 ? dim3(8, T, n_dn / 8) : dim3(n_dn), blk(DEC_NT);
   const int n_se = a.n_shared * a.cap_s;
   const int* recw = (const int*)a.rec;
   const int nsf = a.n_shared * a.f_s;
@@ -903,7 +931,7 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
 }
 
 static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, int act_dtype, int k,
-                         RouteIn in, DecodeArgs& a) {
+                         RouteIn in, DecodeArgs& a, int T = 1) {
   if (!routed && !shared) return SMOE_EINVAL;
   if (routed && routed->device != ctx->device) return SMOE_EINVAL;
   if (shared && shared->device != ctx->device) return SMOE_EINVAL;
@@ -920,6 +948,8 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   a.f_s = shared ? shared->desc.d_ff : 0;
   const int total_f = k * a.f_r + ns * a.f_s;
   if ((size_t)total_f * 4 + WS_H_OFF > SMOE_WORKSPACE_BYTES) return SMOE_ESIZE;
+  if (T < 1 || T > SMOE_MAX_MULTI) return SMOE_ESHAPE;
+  if (T > 1 && (size_t)T * DEC_H_STRIDE(ns * a.f_s, a.f_r) * 4 + WS_H_OFF > SMOE_WORKSPACE_BYTES) return SMOE_ESIZE;
   a.gu_sh_r = a.dn_sh_r = routed ? ilog2_exact(routed->desc.group / 32) : 0;
   a.gu_sh_s = a.dn_sh_s = shared ? ilog2_exact(shared->desc.group / 32) : 0;
   if (a.gu_sh_r < 0 || a.gu_sh_s < 0) return SMOE_ENOTIMPL;   // group must be 32 * 2^n for the decode kernels
@@ -938,6 +968,7 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   // gate/up split: n_wg work-groups, each takes ceil(f / n_wg) row pairs of every slot
   int n_wg = (total_f + DEC_NW - 1) / DEC_NW;              // at least one row pair per wave
   n_wg = n_wg < 1 ? 1 : (n_wg > ctx->n_cu ? ctx->n_cu : n_wg);
+  if (T > 1) n_wg = n_wg < 8 ? 8 : (n_wg & ~7);            // the multi-token grid is (8, T, n_wg / 8)
   a.cap_r = a.f_r ? (a.f_r + n_wg - 1) / n_wg : 1;
   a.cap_s = a.f_s ? (a.f_s + n_wg - 1) / n_wg : 1;
   a.inv_cap_r = (65536 + a.cap_r - 1) / a.cap_r;
@@ -952,8 +983,8 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   a.inv_ks_s = (65536 + a.ks_s - 1) / a.ks_s;
   const int scb = routed ? routed->dev.sc_bf16 : shared->dev.sc_bf16;
   if (routed && shared && routed->dev.sc_bf16 != shared->dev.sc_bf16) return SMOE_ENOTIMPL;   // one scale dtype per layer
-  if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1>(ctx, in, a, n_wg) : launch_decode_t<SMOE_F32, 0>(ctx, in, a, n_wg);
-  return scb ? launch_decode_t<SMOE_BF16, 1>(ctx, in, a, n_wg) : launch_decode_t<SMOE_BF16, 0>(ctx, in, a, n_wg);
+  if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_F32, 0>(ctx, in, a, n_wg, T);
+  return scb ? launch_decode_t<SMOE_BF16, 1>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_BF16, 0>(ctx, in, a, n_wg, T);
 }
 
 extern "C" int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
@@ -999,4 +1030,26 @@ extern "C" int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const s
   const RouteIn in{logits, bias_dev, slice_mask_dev, 0, 0, 1};
   a.idx_out = idx_out_dev; a.w_out = w_out_dev; a.prec_out = prec_out_dev; a.y = y_dev; a.add_residual = add_residual;
   return launch_decode(ctx, routed, shared, act_dtype, k, in, a);
+}
+
+extern "C" int smoe_decode_layer_multi(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, int T,
+                                       const void* x_dev, int act_dtype, int k, const float* logits_dev,
+                                       const float* bias_dev, int norm_topk, float routed_scale,
+                                       const uint8_t* slice_mask_dev, float tau_head, const void* shared_gate_w_dev,
+                                       int add_residual, void* y_dev, int32_t* idx_out_dev, float* w_out_dev,
+                                       uint8_t* prec_out_dev) {
+  if (!ctx || !x_dev || !y_dev || x_dev == y_dev || !routed || !logits_dev) return SMOE_EINVAL;
+  if (act_dtype != SMOE_F32 && act_dtype != SMOE_BF16) return SMOE_EINVAL;
+  if (T < 1 || T > SMOE_MAX_MULTI) return SMOE_ESHAPE;
+  // token rows must keep the 16-byte alignment of the first one
+  const int esz = act_dtype == SMOE_BF16 ? 2 : 4;
+  if (T > 1 && (((size_t)routed->desc.d_model * esz) & 15u)) return SMOE_ESHAPE;
+  if (!aligned16(x_dev) || !aligned16(y_dev) || !aligned16(logits_dev) || !aligned16(bias_dev) || !aligned16(shared_gate_w_dev))
+    return SMOE_EALIGN;
+  DecodeArgs a{};
+  a.norm_topk = norm_topk; a.routed_scale = routed_scale;
+  a.tau = tau_head; a.x = x_dev; a.shared_gate_w = shared_gate_w_dev;
+  const RouteIn in{logits_dev, bias_dev, slice_mask_dev, 0, 0, 1};
+  a.idx_out = idx_out_dev; a.w_out = w_out_dev; a.prec_out = prec_out_dev; a.y = y_dev; a.add_residual = add_residual;
+  return launch_decode(ctx, routed, shared, act_dtype, k, in, a, T);
 }

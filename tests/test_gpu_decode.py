@@ -209,6 +209,51 @@ def test_group32_layer(ctx, dt):
         say("  fused", fused, "worst max-abs-rel", worst)
 
 
+@pytest.mark.parametrize("T,dt", [(2, "f32"), (5, "bf16"), (16, "bf16")])
+def test_multi_token_layer(ctx, T, dt):
+    # T tokens through one layer in one pair of launches: every token must come out exactly as from
+    # its own smoe_decode_layer call (bit for bit: same kernels, same order of operations) and
+    # within tolerance of the oracle; routing outputs row by row
+    say("multi-token layer", T, dt)
+    shp = synth.LayerShape(512, 12, 352, 3, 128, n_shared=1, shared_d_ff=608, shared_gate=True, act=dt)
+    pair = LayerPair(ctx, shp, seed=19)
+    k, E, d = shp.top_k, shp.n_experts, shp.d_model
+    x = synth.activations(19, T, d, dt).cuda()
+    z = synth.normal_logits(19, T, E)
+    mask_np = synth.bernoulli_masks(19, 1, E)[0]
+    bias_np = np.where(mask_np & 1, np.float32(0.5), np.float32(0)).astype(np.float32)
+    wsg = synth.shared_gate_weight(19, 0, d, dt)
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda:0")
+    w = torch.empty((T, k), dtype=torch.float32, device="cuda:0")
+    prec = torch.empty((T, k), dtype=torch.uint8, device="cuda:0")
+    y = B.smoe_decode_layer_multi(ctx, pair.routed, pair.shared, x, k, z.cuda(), bias=dev(bias_np), slice_mask=dev(mask_np),
+                                  tau_head=0.3, shared_gate_w=dev(wsg), add_residual=True, idx_out=idx, w_out=w,
+                                  prec_out=prec)
+    idx_np, w_np, prec_np = idx.cpu().numpy(), w.cpu().numpy(), prec.cpu().numpy()
+    for t in range(T):
+        y1 = B.smoe_decode_layer(ctx, pair.routed, pair.shared, x[t].clone(), k, logits=z[t].cuda(), bias=dev(bias_np),
+                                 slice_mask=dev(mask_np), tau_head=0.3, shared_gate_w=dev(wsg), add_residual=True)
+        assert torch.equal(y1, y[t]), t
+        ridx, rw = O.route(z[t].numpy()[None], bias_np, k)
+        assert np.array_equal(idx_np[t], ridx[0]), t
+        np.testing.assert_allclose(w_np[t], rw[0], rtol=2e-5, atol=1e-7)
+        w_used = w_np[t].astype(np.float64)
+        rprec = O.precision_select(ridx[0], w_used, mask_np, 0.3)
+        assert np.array_equal(prec_np[t], rprec), t
+        yref = O.moe_layer(t2np(x[t]).astype(np.float64), pair.oracle_routed(), ridx[0], w_used, rprec,
+                           pair.oracle_shared(), t2np(wsg), True)
+        assert O.max_abs_rel(t2np(y[t]), yref) <= TOL[dt], t
+    # argument checks: too many tokens, missing logits
+    lib = B.lib()
+    import ctypes as C
+    assert lib.smoe_decode_layer_multi(ctx.h, pair.routed.h, None, 17, C.c_void_p(x.data_ptr()), B._DT[x.dtype], k,
+                                       C.c_void_p(z.cuda().data_ptr()), None, 0, C.c_float(1.0), None, C.c_float(0.0), None, 0,
+                                       C.c_void_p(y.data_ptr()), None, None, None) == -2
+    assert lib.smoe_decode_layer_multi(ctx.h, pair.routed.h, None, 2, C.c_void_p(x.data_ptr()), B._DT[x.dtype], k,
+                                       None, None, 0, C.c_float(1.0), None, C.c_float(0.0), None, 0,
+                                       C.c_void_p(y.data_ptr()), None, None, None) == -1
+
+
 def test_dense_ffn_through_shared_bank(ctx):
     # no routed bank at all: a dense SwiGLU run HIGH; K of the down projection is not a multiple
     # of the group (416 = 3*128 + 32)
