@@ -37,7 +37,7 @@ def main():
     ap.add_argument("--steps", type=int, default=1024)
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=4)
+    ap.add_argument("--cpu-steps", type=int, default=40)
     ap.add_argument("--workload", choices=["decode", "prefill"], default="decode",
                     help="decode (default, the headline metric) or the prefill grouped GEMM of one Qwen-shaped layer")
     ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64, 128],
