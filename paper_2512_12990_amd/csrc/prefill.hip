@@ -31,9 +31,9 @@ struct __attribute__((packed)) U32x2Unaligned { uint32_t x, y; };
 // every expert's selections in LDS, so it knows its own row offset and tile offset.  Writes
 //   hist[e]    number of (token, slot) pairs routed to e (the per-expert access count of the layer)
 //   offsets[e] first row of expert e in the grouped layout (offsets[E] = total)
-//   tiles[0]   number of row tiles; tiles[1 + 2i], tiles[2 + 2i] = expert and first row (inside the
-//              expert) of tile i, tiles with more rows first (equal sizes: expert, then row,
-//              ascending), so that the work-groups that start last are the short ones
+//   tiles[0]   number of row tiles; tiles[4 + 4i ..] = {expert, first row inside the expert, first row
+//              in the grouped layout, rows} of tile i, tiles with more rows first (equal sizes:
+//              expert, then row, ascending), so that the work-groups that start last are the short ones
 //   rows[p]    flat (token*k + slot) index of the p-th row of the grouped layout, ascending inside an
 //              expert; pos = inverse of rows.
 __global__ __launch_bounds__(GR_THREADS) void group_kernel(const int32_t* idx, int n, int E, uint32_t* hist,
@@ -84,8 +84,9 @@ __global__ __launch_bounds__(GR_THREADS) void group_kernel(const int32_t* idx, i
         rank += fx + (rx > rem || (rx == rem && x < e));
       }
     }
-    tiles[1 + 2 * rank] = e;
-    tiles[2 + 2 * rank] = j * PF_BM;
+    int4 rec;
+    rec.x = e; rec.y = j * PF_BM; rec.z = off + j * PF_BM; rec.w = min(PF_BM, ne - j * PF_BM);
+    *(int4*)(tiles + 4 + 4 * rank) = rec;
   }
 }
 
@@ -138,13 +139,18 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
     e = a.dense_expert; m0 = ti * PF_BM; row0 = 0;
     m_cnt = min(PF_BM, a.dense_rows - m0);
   } else {
-    if (ti >= a.tiles[0]) return;
-    e = a.tiles[1 + 2 * ti]; m0 = a.tiles[2 + 2 * ti];
-    row0 = a.offsets[e];
-    m_cnt = min(PF_BM, a.offsets[e + 1] - row0 - m0);
+    const int n_tiles = a.tiles[0];
+    const int4 rec = *(const int4*)(a.tiles + 4 + 4 * ti);      // (read before the count is known: inside the list's allocation)
+    if (ti >= n_tiles) return;
+    e = rec.x; m0 = rec.y; row0 = rec.z - rec.y; m_cnt = rec.w;
   }
   const int K = MODE == 0 ? a.d_model : a.d_ff;
   const int N = MODE == 0 ? a.d_ff : a.d_model;         // output columns of this GEMM
+  // MODE 1: the weight of every row of the tile, fetched now for the epilogue (the barriers of the
+  // K loop order it)
+  __shared__ float row_wt[PF_BM];
+  if (MODE == 1 && tid < PF_BM)
+    row_wt[tid] = tid < m_cnt ? a.wgt[a.dense_rows ? m0 + tid : a.rows[row0 + m0 + tid]] : 0.0f;
   const int mh = wave >> 2, nq = wave & 3;
 
   // ---- loader roles
@@ -338,7 +344,7 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
         const float hv = g / (1.0f + __expf(-g)) * u;
         if (col < N) a.h[prow * a.d_ff + col] = (uint16_t)f32_to_bf16_bits(hv);
       } else {
-        const float wt = a.wgt[a.dense_rows ? (int)prow : a.rows[prow]];
+        const float wt = row_wt[m];
 #pragma unroll
         for (int j = 0; j < 2; j++) {
           const int col = nt * PF_BN + nq * 64 + j * 32 + (lane & 31);
@@ -406,7 +412,7 @@ static PrefillLayout prefill_layout(int T, int E, int k, int d_model, int d_ff, 
   L.rows = off;    off = up256(off + (size_t)T * k * 4);
   L.pos = off;     off = up256(off + (size_t)T * k * 4);
   L.offsets = off; off = up256(off + (size_t)(E + 1) * 4);
-  L.tiles = off;   off = up256(off + (size_t)(1 + 2 * max_tiles(T, E, k)) * 4);
+  L.tiles = off;   off = up256(off + (size_t)(4 + 4 * (max_tiles(T, E, k) + 8)) * 4);   // the grid rounds the tile count up to 8
   L.h = off;       off = up256(off + (size_t)T * k * d_ff * 2);
   L.o = off;       off = up256(off + (size_t)T * k * d_model * 4);
   L.gamma = L.h_s = L.o_s = off;
