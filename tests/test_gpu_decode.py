@@ -332,3 +332,32 @@ def test_dsv2lite_layer_full_size_sampled_steps(ctx):
             got = B.smoe_export_codes(ctx, bank, slot, mi)
             assert np.array_equal(got["q"], qm.q) and np.array_equal(got["zp"], qm.zp)
             assert np.array_equal(got["scale"].view(np.uint32), qm.scale.view(np.uint32))
+
+
+def test_random_small_shapes(ctx):
+    # a seeded sweep over layer shapes: ragged d_ff (any multiple of 32), every group size, both
+    # activation dtypes, with and without shared experts, a sigmoid gate, a residual and a threshold;
+    # one step per shape through the fused call and through route + expert_ffn
+    rng = np.random.default_rng(2024)
+    for case in range(14):
+        d = int(rng.choice([64, 96, 256, 544, 1024, 2048]))
+        G = int(rng.choice([32, 64, 128]))
+        f = int(rng.integers(1, 12)) * 32
+        E = int(rng.integers(2, 20))
+        k = int(rng.integers(1, min(E, 6) + 1))
+        n_sh = int(rng.integers(0, 3))
+        f_s = int(rng.integers(1, 9)) * 32 if n_sh else 0
+        dt = "bf16" if rng.random() < 0.6 else "f32"
+        gate = bool(n_sh and rng.random() < 0.5)
+        say("random shape", case, dict(d=d, G=G, f=f, E=E, k=k, n_sh=n_sh, f_s=f_s, dt=dt, gate=gate))
+        shp = synth.LayerShape(d, E, f, k, G, n_shared=n_sh, shared_d_ff=f_s, shared_gate=gate, act=dt)
+        wl = synth.Workload("rand%d" % case, shp, steps=2, seed=100 + case)
+        pair = LayerPair(ctx, shp, seed=wl.seed)
+        x_all = synth.activations(wl.seed, wl.steps, d, dt)
+        masks = synth.bernoulli_masks(wl.seed, wl.steps, E)
+        logits = synth.normal_logits(wl.seed, wl.steps, E)
+        wsg = synth.shared_gate_weight(wl.seed, 0, d, dt, std=0.05) if gate else None
+        tau = float(rng.choice([0.0, 0.25]))
+        for fused in (False, True):
+            _run_layer_steps(ctx, wl, pair, range(wl.steps), masks, None, logits, x_all, fused, wsg=wsg,
+                             add_residual=bool(case & 1), tau=tau)

@@ -134,3 +134,34 @@ def test_prefill_qwen_layer_full_size_sampled_tokens(ctx):
         err = O.max_abs_rel(yg[t], yref)
         say("    max-abs-rel", err)
         assert err <= TOL
+
+
+def test_prefill_random_small_shapes(ctx):
+    # a seeded sweep over prefill shapes: token counts around the 192-row tile, d_model and d_ff any
+    # multiple of 64 (ragged column tiles), every group size, with and without shared experts
+    rng = np.random.default_rng(77)
+    for case in range(8):
+        T = int(rng.choice([1, 3, 31, 64, 190, 193, 260, 400]))
+        d = int(rng.choice([64, 128, 192, 320]))
+        f = int(rng.integers(1, 6)) * 64
+        G = int(rng.choice([32, 64, 128]))
+        E = int(rng.integers(1, 9))
+        k = int(rng.integers(1, min(E, 4) + 1))
+        n_sh = int(rng.integers(0, 3))
+        f_s = int(rng.integers(1, 5)) * 64 if n_sh else 0
+        gate = bool(n_sh and rng.random() < 0.5)
+        say("random prefill shape", case, dict(T=T, d=d, f=f, G=G, E=E, k=k, n_sh=n_sh, f_s=f_s, gate=gate))
+        shp = synth.LayerShape(d, E, f, k, G, n_shared=n_sh, shared_d_ff=f_s, shared_gate=gate, act="bf16")
+        pair = LayerPair(ctx, shp, seed=300 + case)
+        x = synth.activations(300 + case, T, d, "bf16").cuda()
+        wr = synth.router_weight(300 + case, 0, E, d, std=0.05).cuda()
+        wsg = synth.shared_gate_weight(300 + case, 0, d, "bf16", std=0.05).cuda() if gate else None
+        y, idx, w, hist = B.smoe_prefill_histogram(ctx, pair.routed, pair.shared, x, k, w_router=wr, shared_gate_w=wsg,
+                                                   add_residual=bool(case & 1))
+        ridx, rw = _check_routing(ctx, x, wr, k, idx, w, hist, E)
+        yref = O.prefill_layer(t2np(x).astype(np.float64), pair.oracle_routed(), ridx,
+                               rw.astype(np.float32).astype(np.float64), pair.oracle_shared(),
+                               None if wsg is None else t2np(wsg), add_residual=bool(case & 1))
+        yg = t2np(y)
+        for t in range(T):
+            assert O.max_abs_rel(yg[t], yref[t]) <= TOL, (case, t)
