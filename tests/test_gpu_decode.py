@@ -361,3 +361,46 @@ def test_random_small_shapes(ctx):
         for fused in (False, True):
             _run_layer_steps(ctx, wl, pair, range(wl.steps), masks, None, logits, x_all, fused, wsg=wsg,
                              add_residual=bool(case & 1), tau=tau)
+
+
+def test_decode_steps_replay_from_a_hip_graph():
+    # a serving loop can record its decode calls once and replay them: every call only enqueues two
+    # kernels on the context's stream.  Four steps are captured on a side stream, replayed three times
+    # with eager calls and synchronisations between the replays, and every replay must reproduce the
+    # eager outputs bit for bit.
+    say("graph capture of decode steps")
+    side = torch.cuda.Stream()
+    gctx = B.Ctx(0, stream=side)
+    shp = synth.LayerShape(512, 12, 352, 3, 128, n_shared=1, shared_d_ff=608, act="bf16")
+    pair = LayerPair(gctx, shp, seed=29)
+    k, E, d, n = shp.top_k, shp.n_experts, shp.d_model, 4
+    x = synth.activations(29, n, d, "bf16").cuda()
+    z = synth.normal_logits(29, n, E).cuda()
+    mask = dev(synth.bernoulli_masks(29, 1, E)[0])
+    side.wait_stream(torch.cuda.current_stream())
+
+    def steps(y, idx):
+        for i in range(n):
+            B.smoe_decode_layer(gctx, pair.routed, pair.shared, x[i], k, logits=z[i], slice_mask=mask, add_residual=True,
+                                y=y[i], idx_out=idx[i])
+
+    y_e = torch.zeros((n, d), dtype=torch.bfloat16, device="cuda:0")
+    idx_e = torch.zeros((n, 4), dtype=torch.int32, device="cuda:0")      # 16-byte rows
+    y_g, idx_g = torch.zeros_like(y_e), torch.zeros_like(idx_e)
+    with torch.cuda.stream(side):
+        steps(y_e, idx_e)                       # eager reference (also the warm-up before the capture)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        steps(y_g, idx_g)
+    for rep in range(3):
+        y_g.fill_(0)
+        idx_g.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_g, y_e) and torch.equal(idx_g[:, :k], idx_e[:, :k]), rep
+        with torch.cuda.stream(side):           # eager work between the replays
+            steps(y_e, idx_e)
+        side.synchronize()
+    gctx.close()
