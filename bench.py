@@ -43,6 +43,10 @@ def main():
     ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64, 128],
                     help="decode: quantisation group of the expert weights (default: the workload's 128; 32 is the "
                          "paper's expert format, with four times the scales and zero-points)")
+    ap.add_argument("--shape", choices=["dsv2", "qwen"], default="dsv2",
+                    help="decode: dsv2 = the headline DeepSeek-V2-Lite-shaped layer; qwen = one Qwen1.5-MoE-shaped layer "
+                         "(60 experts top-4, one shared expert of d_ff 5632 behind a sigmoid gate, 18 experts HIGH, all "
+                         "MSB slices resident), reported as its own line")
     ap.add_argument("--tokens", type=int, default=1,
                     help="decode: tokens per step that pass the layer together in one pair of launches (1 = the headline "
                          "single-batch workload; 2-16 = smoe_decode_layer_multi, reported per token)")
@@ -69,6 +73,9 @@ def main():
     if args.workload == "prefill":
         return prefill_bench(args)
     wl = synth.DSV2_LAYER
+    if args.shape == "qwen":
+        import dataclasses
+        wl = dataclasses.replace(synth.QWEN_STACK, n_layers=1, steps=1024)
     if args.group:
         import dataclasses
         wl = dataclasses.replace(wl, layer=dataclasses.replace(wl.layer, group=args.group))
@@ -86,9 +93,14 @@ def main():
     n_in = wl.steps
     x_all = synth.activations(wl.seed, n_in, shp.d_model, "bf16").to(dev)
     z_all = synth.normal_logits(wl.seed, n_in, shp.n_experts).to(dev)
-    mask_np, bias_np = synth.cached_set_mask(wl.seed, shp.n_experts, 32, 16, 1.0)
+    if args.shape == "qwen":
+        mask_np = synth.fraction_masks(wl.seed, 1, 0, shp.n_experts, 0.3)[0]
+        bias_np = np.zeros(shp.n_experts, np.float32)
+    else:
+        mask_np, bias_np = synth.cached_set_mask(wl.seed, shp.n_experts, 32, 16, 1.0)
     mask = torch.from_numpy(mask_np).to(dev)
     bias = torch.from_numpy(bias_np).to(dev)
+    wsg = synth.shared_gate_weight(wl.seed, 0, shp.d_model, "bf16").to(dev) if shp.shared_gate else None
     y = torch.empty((n_in, shp.d_model), dtype=torch.bfloat16, device=dev)
     prec = torch.zeros((n_in, shp.top_k), dtype=torch.uint8, device=dev)
     idx = torch.zeros((n_in, shp.top_k), dtype=torch.int32, device=dev)
@@ -101,15 +113,15 @@ def main():
     TT = args.tokens
     if TT == 1:
         calls = [(ctx.h, routed.h, shared.h, vp(x_all[i]), C.c_int(B.BF16), C.c_int(shp.top_k), vp(z_all[i]), None,
-                  vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), None, C.c_int(0), vp(y[i]),
-                  vp(idx[i]), None, vp(prec[i])) for i in range(n_in)]
+                  vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), vp(wsg) if wsg is not None else None,
+                  C.c_int(0), vp(y[i]), vp(idx[i]), None, vp(prec[i])) for i in range(n_in)]
     else:
         # step t takes the TT consecutive tokens that start at row (t * TT) mod n_in
         assert 2 <= TT <= 16 and n_in % TT == 0
         fn = B.lib().smoe_decode_layer_multi
         calls = [(ctx.h, routed.h, shared.h, C.c_int(TT), vp(x_all[i]), C.c_int(B.BF16), C.c_int(shp.top_k), vp(z_all[i]),
-                  vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), None, C.c_int(0), vp(y[i]),
-                  vp(idx[i]), None, vp(prec[i])) for i in range(0, n_in, TT)]
+                  vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), vp(wsg) if wsg is not None else None,
+                  C.c_int(0), vp(y[i]), vp(idx[i]), None, vp(prec[i])) for i in range(0, n_in, TT)]
     n_calls = len(calls)
 
     def step(t):
@@ -171,6 +183,8 @@ def main():
     prec_np = prec.cpu().numpy()
     hi_gu, hi_dn = slot_bytes(shp.d_model, shp.d_ff, shp.group, 1)
     lo_gu, lo_dn = slot_bytes(shp.d_model, shp.d_ff, shp.group, 0)
+    sh_gu, sh_dn = slot_bytes(shp.d_model, shp.shared_d_ff, shp.group, 1)
+    sh_gu, sh_dn = sh_gu * shp.n_shared, sh_dn * shp.n_shared
     total_bytes = gu_bytes = 0
     idx_np = idx.cpu().numpy()
     for t in range(args.warmup, args.warmup + args.steps):
@@ -187,8 +201,8 @@ def main():
                     need[int(e)] = max(need.get(int(e), 0), int(p))
             nh = sum(need.values())
             nl = len(need) - nh
-        gu = (nh + shp.n_shared) * hi_gu + nl * lo_gu + TT * (shp.d_model * 2 + shp.n_experts * 9)
-        dn = (nh + shp.n_shared) * hi_dn + nl * lo_dn + TT * shp.d_model * 2
+        gu = sh_gu + nh * hi_gu + nl * lo_gu + TT * (shp.d_model * 2 + shp.n_experts * 9)
+        dn = sh_dn + nh * hi_dn + nl * lo_dn + TT * shp.d_model * 2
         gu_bytes += gu
         total_bytes += gu + dn
     bytes_per_step = total_bytes / args.steps
@@ -202,9 +216,11 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "u4+u4 bit-sliced weights, bf16 activations rewritten per 32-chunk as 3 balanced hex digits, signed 4-bit dot products, int32/fp32 accumulate",
         "data": "synthetic",
-        "config": {"workload": "DeepSeek-V2-Lite-shaped MoE layer decode, %d token%s/step (BASELINE configs[1])" % (TT, "" if TT == 1 else "s"),
+        "config": {"workload": ("DeepSeek-V2-Lite-shaped MoE layer decode, %d token%s/step (BASELINE configs[1])" if args.shape == "dsv2" else
+                                "Qwen1.5-MoE-shaped MoE layer decode, %d token%s/step (one layer of BASELINE configs[2])") % (TT, "" if TT == 1 else "s"),
                    "d_model": shp.d_model, "n_experts": shp.n_experts, "d_ff": shp.d_ff, "top_k": shp.top_k,
-                   "n_shared": shp.n_shared, "group": shp.group, "cached": 32, "cached_high": 16,
+                   "n_shared": shp.n_shared, "shared_d_ff": shp.shared_d_ff, "group": shp.group,
+                   "cached": int((mask_np & 1).sum()), "cached_high": int((mask_np == 3).sum()),
                    "mean_high_slots": float(prec_np.mean() * shp.top_k), "launches_per_step": 2, "tokens_per_step": TT},
         "hbm_gbps": achieved, "hbm_frac": achieved / HBM_PEAK_GBPS, "bytes_per_token": bytes_per_step / TT,
         "host_wall_ms_per_step": wall_ms / args.steps,
@@ -228,7 +244,7 @@ def main():
         for _ in range(4):
             dst.copy_(src)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.shape == "dsv2":      # the oracle leg times the headline workload only
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_steps, idx.cpu().numpy(), prec_np)
     print(json.dumps(out))
 

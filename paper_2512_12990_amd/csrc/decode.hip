@@ -701,8 +701,23 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
     if (wave == DEC_NW - 3) {                            // weight of the shared experts
       float g = 1.0f;
       if (a.shared_gate_w) {
+        // d <= 2048: at most four 8-element pieces per lane; all loads go out before the first use
+        Raw8 wr[4], xr[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const int i0 = (lane + 64 * j) * 8;
+          wr[j] = Raw8{}; xr[j] = Raw8{};
+          if (i0 < d) { load8_raw<ACT>(a.shared_gate_w, (size_t)i0, wr[j]); load8_raw<ACT>(x_in, (size_t)i0, xr[j]); }
+        }
         float p = 0.0f;
-        for (int i = lane; i < d; i += 64) p = fmaf(load_act<ACT>(a.shared_gate_w, i), load_act<ACT>(x_in, i), p);
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          float wv[8], xv8[8];
+          unpack8<ACT>(wr[j], wv);
+          unpack8<ACT>(xr[j], xv8);
+#pragma unroll
+          for (int i = 0; i < 8; i++) p = fmaf(wv[i], xv8[i], p);
+        }
         g = 1.0f / (1.0f + expf(-wave_sum(p)));
       }
       if (lane == 0) a.rec->gamma = g;
