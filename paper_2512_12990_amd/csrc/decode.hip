@@ -407,7 +407,7 @@ __device__ __forceinline__ void route_load(const RouteIn& in, int lane, RouteReg
   const unsigned E = (unsigned)in.E;
   const __amdgpu_buffer_rsrc_t rz = make_rsrc(in.logits, in.do_route ? E * 4u : 0u);
   const __amdgpu_buffer_rsrc_t rb = make_rsrc(in.bias, (in.do_route && in.bias) ? E * 4u : 0u);
-  const __amdgpu_buffer_rsrc_t rm = make_rsrc(in.mask, (in.do_route && in.mask) ? E : 0u);
+  const __amdgpu_buffer_rsrc_t rm = make_rsrc(in.mask, in.mask ? E : 0u);      // (also read when the decision is given)
 #pragma unroll
   for (int j = 0; j < 4; j++) {
     const unsigned e = (unsigned)(lane + 64 * j);
@@ -483,13 +483,21 @@ __device__ __forceinline__ void route_topk(const RouteIn& in, const DecodeArgs& 
 }
 
 // The decision was made elsewhere: slot r's expert and weight are read from idx_in / w_in.
-__device__ __forceinline__ void route_given(const RouteIn& in, const DecodeArgs& a, int lane, int& mysel, int& mymask, float& myw) {
+// The slice mask of every expert is already in rr.mk (route_load), so the mask of the selected
+// expert is a lane exchange and not a second, dependent load.
+__device__ __forceinline__ void route_given(const RouteIn& in, const DecodeArgs& a, int lane, const RouteRegs& rr, int& mysel,
+                                            int& mymask, float& myw) {
   const int k = in.k;
   const unsigned vo = lane < k ? (unsigned)lane * 4u : DEC_OOB;
   const int idx = (int)bload32(make_rsrc(a.idx_in, (unsigned)k * 4u), vo, 0);
   myw = __uint_as_float(bload32(make_rsrc(a.w_in, (unsigned)k * 4u), vo, 0));
   mysel = min(max(idx, 0), in.E - 1);
-  const int mk = (int)bload8(make_rsrc(in.mask, in.mask ? (unsigned)in.E : 0u), lane < k ? (unsigned)mysel : DEC_OOB, 0);
+  int mk = 0;
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    const int t = __shfl(rr.mk[j], mysel & 63);
+    if ((mysel >> 6) == j) mk = t;
+  }
   mymask = in.mask ? mk : 3;
 }
 
@@ -499,7 +507,7 @@ template <bool FULL>
 __device__ __forceinline__ void route_wave(const RouteIn& in, const DecodeArgs& a, int lane, const RouteRegs& rr, int& mysel,
                                            int& myprec, float& myw) {
   int mymask;
-  if (!in.do_route) route_given(in, a, lane, mysel, mymask, myw);
+  if (!in.do_route) route_given(in, a, lane, rr, mysel, mymask, myw);
   else if (in.E <= 64) route_topk<1, FULL>(in, a, lane, rr, mysel, mymask, myw);
   else route_topk<4, FULL>(in, a, lane, rr, mysel, mymask, myw);
   myprec = ((mymask & 3) == 3) && (a.tau <= 0.0f || myw >= a.tau);
