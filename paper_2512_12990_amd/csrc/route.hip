@@ -15,9 +15,27 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const float* __restr
                                                             int E, int d, float* __restrict__ z) {
   const int lane = threadIdx.x & 63, e = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (e >= E) return;
-  float p[1];
-  router_row_dots<1>(w_router + (size_t)e * d, d, lane, [&](int, int i) { return load_act<ACT>(x, i); }, p);
-  if (lane == 0) z[e] = p[0];
+  // Same sum as router_row_dots (lane l adds columns l, l+64, ... in that order by fused
+  // multiply-add, then the wave sum), but 32 columns per lane are fetched before the first is used:
+  // one memory round trip per 2048 columns instead of four.
+  const float* wrow = w_router + (size_t)e * d;
+  float p = 0.0f;
+  for (int i0 = 0; i0 < d; i0 += 2048) {
+    float w[32], xv[32];
+#pragma unroll
+    for (int u = 0; u < 32; u++) {
+      const int i = i0 + u * 64 + lane;
+      w[u] = i < d ? wrow[i] : 0.0f;
+      xv[u] = i < d ? load_act<ACT>(x, i) : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < 32; u++) {
+      const float q = fmaf(w[u], xv[u], p);
+      p = (i0 + u * 64 + lane) < d ? q : p;
+    }
+  }
+  p = wave_sum(p);
+  if (lane == 0) z[e] = p;
 }
 
 int smoe_launch_router_logits(smoe_ctx* ctx, int E, int d, const void* x, int act_dtype, const float* w_router, float* z) {
