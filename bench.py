@@ -47,6 +47,9 @@ def main():
                     help="decode: dsv2 = the headline DeepSeek-V2-Lite-shaped layer; qwen = one Qwen1.5-MoE-shaped layer "
                          "(60 experts top-4, one shared expert of d_ff 5632 behind a sigmoid gate, 18 experts HIGH, all "
                          "MSB slices resident), reported as its own line")
+    ap.add_argument("--router-matvec", action="store_true",
+                    help="decode (one token per step): logits from the router mat-vec W_r x (a third launch) instead of "
+                         "supplied logits")
     ap.add_argument("--tokens", type=int, default=1,
                     help="decode: tokens per step that pass the layer together in one pair of launches (1 = the headline "
                          "single-batch workload; 2-16 = smoe_decode_layer_multi, reported per token)")
@@ -111,8 +114,10 @@ def main():
     fn = B.lib().smoe_decode_layer
     vp = lambda t: C.c_void_p(t.data_ptr())
     TT = args.tokens
+    wr = synth.router_weight(wl.seed, 0, shp.n_experts, shp.d_model).to(dev) if args.router_matvec else None
     if TT == 1:
-        calls = [(ctx.h, routed.h, shared.h, vp(x_all[i]), C.c_int(B.BF16), C.c_int(shp.top_k), vp(z_all[i]), None,
+        calls = [(ctx.h, routed.h, shared.h, vp(x_all[i]), C.c_int(B.BF16), C.c_int(shp.top_k),
+                  None if wr is not None else vp(z_all[i]), vp(wr) if wr is not None else None,
                   vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), vp(wsg) if wsg is not None else None,
                   C.c_int(0), vp(y[i]), vp(idx[i]), None, vp(prec[i])) for i in range(n_in)]
     else:
@@ -221,7 +226,8 @@ def main():
                    "d_model": shp.d_model, "n_experts": shp.n_experts, "d_ff": shp.d_ff, "top_k": shp.top_k,
                    "n_shared": shp.n_shared, "shared_d_ff": shp.shared_d_ff, "group": shp.group,
                    "cached": int((mask_np & 1).sum()), "cached_high": int((mask_np == 3).sum()),
-                   "mean_high_slots": float(prec_np.mean() * shp.top_k), "launches_per_step": 2, "tokens_per_step": TT},
+                   "mean_high_slots": float(prec_np.mean() * shp.top_k), "launches_per_step": 3 if wr is not None else 2,
+                   "tokens_per_step": TT},
         "hbm_gbps": achieved, "hbm_frac": achieved / HBM_PEAK_GBPS, "bytes_per_token": bytes_per_step / TT,
         "host_wall_ms_per_step": wall_ms / args.steps,
         "repeat_windows_us_per_token": {"median": windows[2], "min": windows[0], "max": windows[-1], "n": 5},

@@ -18,19 +18,22 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const float* __restr
   // Same sum as router_row_dots (lane l adds columns l, l+64, ... in that order by fused
   // multiply-add, then the wave sum), but 32 columns per lane are fetched before the first is used:
   // one memory round trip per 2048 columns instead of four.
-  const float* wrow = w_router + (size_t)e * d;
+  const uint32_t* wrow = (const uint32_t*)(w_router + (size_t)e * d);
   float p = 0.0f;
   for (int i0 = 0; i0 < d; i0 += 2048) {
-    float w[32], xv[32];
+    // raw load results only (a column past the end re-reads the last one and is masked below):
+    // any arithmetic on a loaded value here would make the wave wait for that load at once
+    uint32_t w[32], xv[32];
 #pragma unroll
     for (int u = 0; u < 32; u++) {
-      const int i = i0 + u * 64 + lane;
-      w[u] = i < d ? wrow[i] : 0.0f;
-      xv[u] = i < d ? load_act<ACT>(x, i) : 0.0f;
+      const int i = min(i0 + u * 64 + lane, d - 1);
+      w[u] = wrow[i];
+      xv[u] = ACT == SMOE_BF16 ? (uint32_t)((const uint16_t*)x)[i] : ((const uint32_t*)x)[i];
     }
 #pragma unroll
     for (int u = 0; u < 32; u++) {
-      const float q = fmaf(w[u], xv[u], p);
+      const float xf = __uint_as_float(ACT == SMOE_BF16 ? xv[u] << 16 : xv[u]);
+      const float q = fmaf(__uint_as_float(w[u]), xf, p);
       p = (i0 + u * 64 + lane) < d ? q : p;
     }
   }
