@@ -365,8 +365,24 @@ __global__ __launch_bounds__(256) void shared_gate_kernel(const uint16_t* x, con
   if (t >= T) return;
   float g = 1.0f;
   if (w_sg) {
+    // 32 columns per lane are fetched into raw registers before the first is used (arithmetic on a
+    // loaded value at the load site would make the wave wait for every load in turn)
+    const uint16_t* xr = x + (size_t)t * d;
     float s = 0.0f;
-    for (int i = lane; i < d; i += 64) s = fmaf(bf16_bits_to_f32(w_sg[i]), bf16_bits_to_f32(x[(size_t)t * d + i]), s);
+    for (int i0 = 0; i0 < d; i0 += 2048) {
+      uint32_t wv[32], xv[32];
+#pragma unroll
+      for (int u = 0; u < 32; u++) {
+        const int i = min(i0 + u * 64 + lane, d - 1);
+        wv[u] = w_sg[i];
+        xv[u] = xr[i];
+      }
+#pragma unroll
+      for (int u = 0; u < 32; u++) {
+        const float q = fmaf(__uint_as_float(wv[u] << 16), __uint_as_float(xv[u] << 16), s);
+        s = (i0 + u * 64 + lane) < d ? q : s;
+      }
+    }
     s = wave_sum(s);
     g = 1.0f / (1.0f + __expf(-s));
   }
