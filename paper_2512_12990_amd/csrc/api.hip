@@ -86,7 +86,7 @@ static int check_desc(const smoe_bank_desc* d) {
   if ((d->w_dtype != SMOE_F32 && d->w_dtype != SMOE_BF16) || (d->scale_dtype != SMOE_F32 && d->scale_dtype != SMOE_BF16))
     return SMOE_EINVAL;
   if (d->b_high <= d->b_low || d->b_low < 1 || d->b_high > 8) return SMOE_ESHAPE;
-  if (d->b_high != 8 || d->b_low != 4) return SMOE_ENOTIMPL;
+  if (!((d->b_high == 8 && d->b_low == 4) || (d->b_high == 4 && d->b_low == 2))) return SMOE_ENOTIMPL;   // 6/3: 3-bit planes
   return SMOE_OK;
 }
 
@@ -102,7 +102,8 @@ static size_t layout(const smoe_bank_desc* d, BankDev* b, MatOff* ogu, MatOff* o
   for (int i = 0; i < 2; i++) {
     m[i]->ng = (m[i]->K + d->group - 1) / d->group;
     m[i]->cpg = d->group / 32;
-    m[i]->plane_stride = (size_t)m[i]->N * m[i]->K / 2;
+    m[i]->bits = d->b_low;
+    m[i]->plane_stride = (size_t)m[i]->N * m[i]->K * d->b_low / 8;
     m[i]->zp_stride = up16((size_t)m[i]->N * m[i]->ng);
     m[i]->sng = (m[i]->ng + 1) & ~1;
     m[i]->sc_stride = up16((size_t)m[i]->N * m[i]->sng * ssz);
@@ -117,6 +118,7 @@ static size_t layout(const smoe_bank_desc* d, BankDev* b, MatOff* ogu, MatOff* o
   for (int i = 0; i < 2; i++) { o[i]->lsb = off; off = up256(off + E * m[i]->plane_stride); }
   b->n_experts = d->n_experts; b->d_model = d->d_model; b->d_ff = d->d_ff; b->group = d->group;
   b->sc_bf16 = d->scale_dtype == SMOE_BF16;
+  b->bits = d->b_low;
   return off;
 }
 
@@ -170,7 +172,8 @@ extern "C" int smoe_export_codes(smoe_ctx* ctx, const smoe_bank* bank, int exper
   if (expert < 0 || expert >= bank->desc.n_experts || matrix < 0 || matrix > 2) return SMOE_ESHAPE;
   const MatDev& m = matrix == 2 ? bank->dev.dn : bank->dev.gu;
   const int N = matrix == 2 ? m.N : m.N / 2, K = m.K, ng = m.ng;
-  const size_t row_b = (size_t)K / 2, ssz = bank->dev.sc_bf16 ? 2 : 4;
+  const int bits = m.bits;
+  const size_t row_b = (size_t)K * bits / 8, ssz = bank->dev.sc_bf16 ? 2 : 4;
   HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
   std::vector<uint8_t> pm(m.plane_stride), pl(m.plane_stride), zp((size_t)m.N * ng), sc((size_t)m.N * m.sng * ssz);
   HIPCHK(ctx, hipMemcpy(pm.data(), m.msb + (size_t)expert * m.plane_stride, pm.size(), hipMemcpyDeviceToHost));
@@ -181,12 +184,17 @@ extern "C" int smoe_export_codes(smoe_ctx* ctx, const smoe_bank* bank, int exper
     // gate rows are the even rows of the interleaved family, up rows the odd ones
     const size_t sr = matrix == 2 ? (size_t)r : (size_t)2 * r + (matrix == 1);
     for (int kk = 0; kk < K; kk++) {
-      const uint8_t bm = pm[sr * row_b + kk / 2] ^ 0x88, bl = pl[sr * row_b + kk / 2] ^ 0x88;   // stored as n ^ 8
-      const uint8_t mv = (kk & 1) ? (bm >> 4) : (bm & 15), lv = (kk & 1) ? (bl >> 4) : (bl & 15);
+      uint8_t mv, lv;
+      if (bits == 4) {
+        const uint8_t bm = pm[sr * row_b + kk / 2] ^ 0x88, bl = pl[sr * row_b + kk / 2] ^ 0x88;   // stored as n ^ 8
+        mv = (kk & 1) ? (bm >> 4) : (bm & 15); lv = (kk & 1) ? (bl >> 4) : (bl & 15);
+      } else {                                                  // four 2-bit codes per byte, column 4j in bits 0-1
+        mv = (pm[sr * row_b + kk / 4] >> (2 * (kk & 3))) & 3; lv = (pl[sr * row_b + kk / 4] >> (2 * (kk & 3))) & 3;
+      }
       const size_t o = (size_t)r * K + kk;
       if (msb_host) msb_host[o] = mv;
       if (lsb_host) lsb_host[o] = lv;
-      if (q_host) q_host[o] = (uint8_t)((mv << 4) | lv);
+      if (q_host) q_host[o] = (uint8_t)((mv << bits) | lv);
     }
     for (int g = 0; g < ng; g++) {
       if (zp_host) zp_host[(size_t)r * ng + g] = zp[sr * ng + g];

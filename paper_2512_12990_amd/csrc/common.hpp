@@ -21,6 +21,7 @@ struct MatDev {
   const uint8_t* msb; const uint8_t* lsb; const uint8_t* zp; const uint8_t* sc;
   unsigned long long plane_stride, zp_stride, sc_stride;   // bytes per expert
   int N, K, ng, cpg;                                       // cpg = 32-column chunks per group
+  int bits;                                                // bits per code in a plane: 4 (8/4 nest) or 2 (4/2 nest)
   int sng;                                                 // scales per row as stored: ng rounded up to even, so that
                                                            // every row of scales starts on a 4-byte boundary
   unsigned ps32, zs32, ss32, fits32;                       // the strides as 32-bit numbers; fits32 = every
@@ -30,6 +31,7 @@ struct MatDev {
 struct BankDev {
   MatDev gu, dn;
   int n_experts, d_model, d_ff, group, sc_bf16;
+  int bits;             // plane bits per code (4: 8-bit codes of nibble planes; 2: 4-bit codes of 2-bit planes)
 };
 
 struct smoe_ctx {

@@ -959,6 +959,7 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   if (routed && routed->device != ctx->device) return SMOE_EINVAL;
   if (shared && shared->device != ctx->device) return SMOE_EINVAL;
   if (routed && shared && routed->desc.d_model != shared->desc.d_model) return SMOE_ESHAPE;
+  if ((routed && routed->dev.bits != 4) || (shared && shared->dev.bits != 4)) return SMOE_ENOTIMPL;
   if (!routed && k != 0) return SMOE_ESHAPE;
   if (routed && (k <= 0 || k > routed->desc.n_experts || k > SMOE_MAX_TOPK)) return SMOE_ESHAPE;
   if (routed && routed->desc.n_experts > SMOE_MAX_EXPERTS) return SMOE_ESHAPE;

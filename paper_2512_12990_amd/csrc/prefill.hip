@@ -458,6 +458,7 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
   if (!logits_dev && !w_router_dev) return SMOE_EINVAL;
   if (shared_gate_w_dev && !shared) return SMOE_EINVAL;
   if (act_dtype != SMOE_BF16) return SMOE_ENOTIMPL;
+  if (routed->dev.bits != 4 || (shared && shared->dev.bits != 4)) return SMOE_ENOTIMPL;
   if (routed->device != ctx->device || (shared && shared->device != ctx->device)) return SMOE_EINVAL;
   const int E = routed->desc.n_experts, d = routed->desc.d_model, f = routed->desc.d_ff;
   if (T <= 0 || k <= 0 || k > E || k > SMOE_MAX_TOPK || E > SMOE_MAX_EXPERTS) return SMOE_ESHAPE;

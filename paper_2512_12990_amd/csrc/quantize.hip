@@ -39,8 +39,10 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restri
   }
   const size_t sbase = src_row * (size_t)K;
   const size_t e = (size_t)(e0 + el);
-  uint8_t* pm = const_cast<uint8_t*>(m.msb) + e * m.plane_stride + (size_t)row * (K / 2);
-  uint8_t* pl = const_cast<uint8_t*>(m.lsb) + e * m.plane_stride + (size_t)row * (K / 2);
+  const int bits = m.bits;                             // 4: 8-bit codes, nibble planes; 2: 4-bit codes, 2-bit planes
+  const float qmax = bits == 4 ? 255.0f : 15.0f;
+  uint8_t* pm = const_cast<uint8_t*>(m.msb) + e * m.plane_stride + (size_t)row * (K * bits / 8);
+  uint8_t* pl = const_cast<uint8_t*>(m.lsb) + e * m.plane_stride + (size_t)row * (K * bits / 8);
   uint8_t* pz = const_cast<uint8_t*>(m.zp) + e * m.zp_stride + (size_t)row * ng;
   uint8_t* ps = const_cast<uint8_t*>(m.sc) + e * m.sc_stride;
 
@@ -56,10 +58,25 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restri
     }
     lo = wave_min(lo);
     hi = wave_max(hi);
-    float s = (hi - lo) / 255.0f;
+    float s = (hi - lo) / qmax;
     if (sc_bf16) s = bf16_bits_to_f32(f32_to_bf16_bits(s));
     if (!(s > 0.0f)) s = 1.0f;
-    const int zp = (int)fminf(fmaxf(rintf((-lo) / s), 0.0f), 255.0f);
+    const int zp = (int)fminf(fmaxf(rintf((-lo) / s), 0.0f), qmax);
+    if (bits == 2) {
+      // 4-bit codes: upper two bits = the low-bit code; four codes per plane byte, column 4j in bits 0-1
+      for (int p = lane; p < (gsz >> 2); p += 64) {
+        int bm = 0, bl = 0;
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+          const float a = load_w<WDT>(src, sbase + k0 + 4 * p + c);
+          const int q = min(max((int)rintf(a / s) + zp, 0), 15);
+          bm |= (q >> 2) << (2 * c);
+          bl |= (q & 3) << (2 * c);
+        }
+        pm[(k0 >> 2) + p] = (uint8_t)bm;
+        pl[(k0 >> 2) + p] = (uint8_t)bl;
+      }
+    } else
     for (int p = lane; p < np; p += 64) {
       const float a = load_w<WDT>(src, sbase + k0 + 2 * p), b = load_w<WDT>(src, sbase + k0 + 2 * p + 1);
       const int qa = min(max((int)rintf(a / s) + zp, 0), 255);

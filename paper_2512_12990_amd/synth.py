@@ -31,6 +31,8 @@ class LayerShape:
     shared_d_ff: int = 0
     shared_gate: bool = False          # sigmoid gate on the shared expert (Qwen shape)
     act: str = "bf16"                  # activation / scale dtype: "f32" or "bf16"
+    b_high: int = 8                    # bits of the full code and of its upper (low-bit) part: 8/4 or 4/2
+    b_low: int = 4
 
 
 @dataclass(frozen=True)

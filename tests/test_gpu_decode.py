@@ -56,6 +56,24 @@ def test_quantize_slice_bit_exact(ctx, d, f, G, dt):
             assert np.array_equal(got["scale"].view(np.uint32), qm.scale.view(np.uint32))
 
 
+@pytest.mark.parametrize("d,f,G,dt", [(256, 160, 64, "bf16"), (96, 64, 32, "f32"), (2048, 1408, 32, "bf16")])
+def test_quantize_slice_4_2_nest_bit_exact(ctx, d, f, G, dt):
+    # the 4/2 nest: 4-bit codes whose upper two bits are the low-bit model, 2-bit planes
+    say("quantize 4/2", d, f, G, dt)
+    shape = synth.LayerShape(d, 2, f, 1, G, act=dt, b_high=4, b_low=2)
+    pair = LayerPair(ctx, shape, seed=3)
+    assert pair.routed.nbytes < 0.6 * B.smoe_bank_bytes(B.BankDesc(2, d, f, G, 8, 4, B._DT[dt], B._DT[dt]))
+    for e in range(2):
+        ex = pair.oracle_expert(e)
+        for mi, qm in enumerate((ex.gate, ex.up, ex.down)):
+            got = B.smoe_export_codes(ctx, pair.routed, e, mi)
+            assert int(got["q"].max()) <= 15
+            assert np.array_equal(got["q"], qm.q)
+            assert np.array_equal(got["msb"], qm.msb()) and np.array_equal(got["lsb"], qm.lsb())
+            assert np.array_equal(got["zp"], qm.zp)
+            assert np.array_equal(got["scale"].view(np.uint32), qm.scale.view(np.uint32))
+
+
 def test_quantize_special_groups_bit_exact(ctx):
     # flat groups, one-sided groups, exact zeros, a huge and a tiny group next to each other
     say("quantize special")
