@@ -23,11 +23,14 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 
 
+PLANE_BITS = 4      # bits per code in a plane: 4 for the 8/4 nest, 2 for the 4/2 nest (--nest 42)
+
+
 def slot_bytes(d, f, group, prec, scale_bytes=2):
-    """Algorithmic bytes one expert moves at a precision: nibble planes read + metadata."""
+    """Algorithmic bytes one expert moves at a precision: planes read + metadata."""
     planes = 2 if prec else 1
-    gu = planes * (2 * f * d // 2) + 2 * f * (-(-d // group)) * (scale_bytes + 1)
-    dn = planes * (d * f // 2) + d * (-(-f // group)) * (scale_bytes + 1)
+    gu = planes * (2 * f * d * PLANE_BITS // 8) + 2 * f * (-(-d // group)) * (scale_bytes + 1)
+    dn = planes * (d * f * PLANE_BITS // 8) + d * (-(-f // group)) * (scale_bytes + 1)
     return gu, dn
 
 
@@ -50,6 +53,9 @@ def main():
     ap.add_argument("--router-matvec", action="store_true",
                     help="decode (one token per step): logits from the router mat-vec W_r x (a third launch) instead of "
                          "supplied logits")
+    ap.add_argument("--nest", choices=["84", "42"], default="84",
+                    help="decode: bit nest of the expert weights: 84 = 8-bit codes / 4-bit low-bit model (headline), "
+                         "42 = 4-bit codes / 2-bit low-bit model (half the plane bytes)")
     ap.add_argument("--tokens", type=int, default=1,
                     help="decode: tokens per step that pass the layer together in one pair of launches (1 = the headline "
                          "single-batch workload; 2-16 = smoe_decode_layer_multi, reported per token)")
@@ -75,6 +81,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU fallback)"
     if args.workload == "prefill":
         return prefill_bench(args)
+    global PLANE_BITS
+    bh, bl = (8, 4) if args.nest == "84" else (4, 2)
+    PLANE_BITS = bl
     wl = synth.DSV2_LAYER
     if args.shape == "qwen":
         import dataclasses
@@ -85,8 +94,8 @@ def main():
     shp = wl.layer
     dev = "cuda:0"
     ctx = B.Ctx(0)
-    routed = B.Bank(ctx, shp.n_experts, shp.d_model, shp.d_ff, shp.group, "bf16", "bf16")
-    shared = B.Bank(ctx, shp.n_shared, shp.d_model, shp.shared_d_ff, shp.group, "bf16", "bf16")
+    routed = B.Bank(ctx, shp.n_experts, shp.d_model, shp.d_ff, shp.group, "bf16", "bf16", bh, bl)
+    shared = B.Bank(ctx, shp.n_shared, shp.d_model, shp.shared_d_ff, shp.group, "bf16", "bf16", bh, bl)
     for e in range(shp.n_experts):
         wg, wu, wd = synth.expert_weights(wl.seed, 0, e, shp.d_model, shp.d_ff, "bf16", dev)
         B.smoe_quantize_slice(ctx, routed, e, wg[None], wu[None], wd[None])
@@ -224,7 +233,7 @@ def main():
         "config": {"workload": ("DeepSeek-V2-Lite-shaped MoE layer decode, %d token%s/step (BASELINE configs[1])" if args.shape == "dsv2" else
                                 "Qwen1.5-MoE-shaped MoE layer decode, %d token%s/step (one layer of BASELINE configs[2])") % (TT, "" if TT == 1 else "s"),
                    "d_model": shp.d_model, "n_experts": shp.n_experts, "d_ff": shp.d_ff, "top_k": shp.top_k,
-                   "n_shared": shp.n_shared, "shared_d_ff": shp.shared_d_ff, "group": shp.group,
+                   "n_shared": shp.n_shared, "shared_d_ff": shp.shared_d_ff, "group": shp.group, "nest": "%d/%d" % (bh, bl),
                    "cached": int((mask_np & 1).sum()), "cached_high": int((mask_np == 3).sum()),
                    "mean_high_slots": float(prec_np.mean() * shp.top_k), "launches_per_step": 3 if wr is not None else 2,
                    "tokens_per_step": TT},
@@ -250,7 +259,7 @@ def main():
         for _ in range(4):
             dst.copy_(src)
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline and args.shape == "dsv2":      # the oracle leg times the headline workload only
+    if not args.no_cpu_baseline and args.shape == "dsv2" and args.nest == "84":      # the oracle leg times the headline workload only
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_steps, idx.cpu().numpy(), prec_np)
     print(json.dumps(out))
 

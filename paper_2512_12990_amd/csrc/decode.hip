@@ -147,6 +147,7 @@ template <int CTRL> __device__ __forceinline__ int quad_xchg(int v) {
 // line, and the compiler can count outstanding loads exactly (partial s_waitcnt instead of
 // waiting for everything).  A zero scale makes a lane's contribution exactly 0.
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 #define DEC_OOB 0x80000000u
 
 struct SecRsrc { __amdgpu_buffer_rsrc_t msb, lsb, zp, sc; };
@@ -166,6 +167,17 @@ __device__ __forceinline__ uint4 bload128(__amdgpu_buffer_rsrc_t r, unsigned vof
   const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
+__device__ __forceinline__ uint2 bload64(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+  const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0);
+  return make_uint2(v.x, v.y);
+}
+// A lane's 32 codes of one plane as loaded.  FMT 0: 8/4 nest, nibble planes (16 bytes, every nibble n
+// stored as n ^ 8); FMT 1: 4/2 nest, 2-bit planes (8 bytes, column c of a word in bits 2c, 2c+1).
+template <int FMT> struct PlaneT { typedef uint4 t; enum { BYTES = 16 }; };
+template <> struct PlaneT<1> { typedef uint2 t; enum { BYTES = 8 }; };
+template <int FMT> __device__ __forceinline__ typename PlaneT<FMT>::t pload(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff);
+template <> __device__ __forceinline__ uint4 pload<0>(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) { return bload128(r, voff, soff); }
+template <> __device__ __forceinline__ uint2 pload<1>(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) { return bload64(r, voff, soff); }
 __device__ __forceinline__ uint32_t bload32(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
   return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
 }
@@ -228,6 +240,48 @@ __device__ __forceinline__ float lane_value(const XR<SMOE_BF16>& x, const uint4&
   dot_plane_i4(m, x, p0, p1, p2);
   const int t = ((((p2 << 4) + p1) << 4) + p0) + __mul24(8 - (zp >> 4), x.xs);
   return (16.0f * s * x.sx) * (float)t;
+}
+
+// 2-bit planes: the sixteen 2-bit codes of half a plane word, one per nibble (values 0..3)
+__device__ __forceinline__ uint32_t spread2(uint32_t h) {
+  h = (h | (h << 8)) & 0x00FF00FFu;
+  h = (h | (h << 4)) & 0x0F0F0F0Fu;
+  return (h | (h << 2)) & 0x33333333u;
+}
+__device__ __forceinline__ uint4 nibbles_of(const uint2& p) {
+  return make_uint4(spread2(p.x & 0xFFFFu), spread2(p.x >> 16), spread2(p.y & 0xFFFFu), spread2(p.y >> 16));
+}
+// 4/2 nest, codes as plain nibbles 0..3 (no offset):
+//   HIGH: s (4 m + l - zp) x = s sx (4 m.q + l.q - zp sum q)
+//   LOW : 4 s (m - (zp >> 2)) x = 4 s sx (m.q - (zp >> 2) sum q)
+__device__ __forceinline__ float lane_value(const XR<SMOE_BF16>& x, const uint2& m2, const uint2& l2, int high, int zp,
+                                            float s) {
+  int m0 = 0, m1 = 0, mm2 = 0;
+  dot_plane_i4(nibbles_of(m2), x, m0, m1, mm2);
+  const int tm = (((mm2 << 4) + m1) << 4) + m0;
+  if (high) {
+    int l0 = 0, l1 = 0, ll2 = 0;
+    dot_plane_i4(nibbles_of(l2), x, l0, l1, ll2);
+    const int tl = (((ll2 << 4) + l1) << 4) + l0;
+    return (s * x.sx) * (float)(4 * tm + tl - __mul24(zp, x.xs));
+  }
+  return (4.0f * s * x.sx) * (float)(tm - __mul24(zp >> 2, x.xs));
+}
+__device__ __forceinline__ float lane_value(const XR<SMOE_F32>& x, const uint2& m2, const uint2& l2, int high, int zp,
+                                            float s) {
+  const uint32_t wm[2] = {m2.x, m2.y}, wl[2] = {l2.x, l2.y};
+  float a0 = 0.0f, a1 = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 2; j++)
+#pragma unroll
+    for (int c = 0; c < 16; c += 2) {
+      const uint32_t q0 = high ? (((wm[j] >> (2 * c)) & 3u) << 2) | ((wl[j] >> (2 * c)) & 3u) : (wm[j] >> (2 * c)) & 3u;
+      const uint32_t q1 = high ? (((wm[j] >> (2 * c + 2)) & 3u) << 2) | ((wl[j] >> (2 * c + 2)) & 3u) : (wm[j] >> (2 * c + 2)) & 3u;
+      a0 = fmaf((float)q0, x.v[16 * j + c], a0);
+      a1 = fmaf((float)q1, x.v[16 * j + c + 1], a1);
+    }
+  if (high) return s * fmaf(-(float)zp, x.xs, a0 + a1);
+  return (4.0f * s) * fmaf(-(float)(zp >> 2), x.xs, a0 + a1);
 }
 
 __device__ __forceinline__ float dot_bytes(uint32_t e, uint32_t o, const float* x, float acc0, float& acc1) {
@@ -560,7 +614,7 @@ struct GuPiece {
   int prec;
 };
 
-template <int ACT, int SCB>
+template <int ACT, int SCB, int FMT>
 __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, const float* bias, const uint8_t* mask, const void* x_in,
                                                         int E, int k, int do_route, int d_model, int n_wg, int n_se,
                                                         DecodeArgs a) {
@@ -604,14 +658,15 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
     if (a.prec_out) a.prec_out += tok * k;
   }
 
-  const unsigned rowb32 = (unsigned)d >> 1;
+  constexpr unsigned PB = PlaneT<FMT>::BYTES;          // plane bytes of one 32-column chunk
+  const unsigned rowb32 = ((unsigned)d >> 5) * PB;
   const bool live_lane = lane < C;
-  const unsigned voff = live_lane ? (unsigned)lane * 16u : DEC_OOB;
+  const unsigned voff = live_lane ? (unsigned)lane * PB : DEC_OOB;
   const int nsf = a.n_shared * a.f_s;
   const int N_e = n_se + k * a.cap_r;
   const int e_lo = wave * a.gu_L, e_hi = uni(min(e_lo + a.gu_L, N_e));
 
-  uint4 gm[DEC_MAXP], um[DEC_MAXP], gl[DEC_MAXP], ul[DEC_MAXP];
+  typename PlaneT<FMT>::t gm[DEC_MAXP], um[DEC_MAXP], gl[DEC_MAXP], ul[DEC_MAXP];
   uint32_t zg[DEC_MAXP], zu[DEC_MAXP], sg[DEC_MAXP], su[DEC_MAXP];      // raw zero-points and scale bits
 
   // s = slot (shared experts first), q0 = first entry of the piece inside the slot
@@ -649,10 +704,10 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
     for (int t = 0; t < DEC_MAXP; t++) {
       const bool valid = t < nb && pc.r0 + n_wg * t < f;
       const unsigned vo = valid ? voff : DEC_OOB, vl = (valid && pc.prec) ? voff : DEC_OOB;
-      gm[t] = bload128(R.msb, vo, pc.po + (unsigned)t * dp);
-      gl[t] = bload128(R.lsb, vl, pc.po + (unsigned)t * dp);
-      um[t] = bload128(R.msb, vo, pc.po + (unsigned)t * dp + rowb32);
-      ul[t] = bload128(R.lsb, vl, pc.po + (unsigned)t * dp + rowb32);
+      gm[t] = pload<FMT>(R.msb, vo, pc.po + (unsigned)t * dp);
+      gl[t] = pload<FMT>(R.lsb, vl, pc.po + (unsigned)t * dp);
+      um[t] = pload<FMT>(R.msb, vo, pc.po + (unsigned)t * dp + rowb32);
+      ul[t] = pload<FMT>(R.lsb, vl, pc.po + (unsigned)t * dp + rowb32);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -785,7 +840,7 @@ __device__ __forceinline__ float wave_sum4_to_last(float v0, float v1, float v2,
 
 #define DEC_HQ 4      // h words of 8 values per lane that cover one combo (64 chunks)
 
-template <int ACT, int SCB>
+template <int ACT, int SCB, int FMT>
 __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const float* h, int n_combo_s, int n_pieces, int psh, int f_s,
                                                       int f_r, int ks_s, int ks_r, int inv_ks_s, int inv_ks_r, int nsf,
                                                       DecodeArgs a) {
@@ -838,20 +893,21 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
     const SecRsrc R = make_sec(md, is_sh ? a.n_shared : a.E);
     const int sh = is_sh ? a.dn_sh_s : a.dn_sh_r;
     const bool live = lane < cw;
-    const unsigned vo = live ? (unsigned)lane * 16u : DEC_OOB, vl = (live && prec) ? vo : DEC_OOB;
+    constexpr unsigned PB = PlaneT<FMT>::BYTES;
+    const unsigned vo = live ? (unsigned)lane * PB : DEC_OOB, vl = (live && prec) ? vo : DEC_OOB;
     const int g0 = (ks * 64) >> sh;                                  // first group of the k-slice
     const int tg = (lane >> sh) + (g0 & 1);                          // scale position relative to an even element
     const unsigned vz = live ? (unsigned)(lane >> sh) : DEC_OOB;
     const unsigned vs = live ? (SCB ? (unsigned)(tg >> 1) << 2 : (unsigned)(lane >> sh) << 2) : DEC_OOB;
     const int odd = SCB ? (tg & 1) : 0;
-    const unsigned rowb = (unsigned)f >> 1, ng = (unsigned)md.ng, srow = (unsigned)md.sng * (SCB ? 2u : 4u);
-    unsigned po = (unsigned)e * md.ps32 + (unsigned)(n0 + row0) * rowb + (unsigned)ks * 1024u;
+    const unsigned rowb = ((unsigned)f >> 5) * PB, ng = (unsigned)md.ng, srow = (unsigned)md.sng * (SCB ? 2u : 4u);
+    unsigned po = (unsigned)e * md.ps32 + (unsigned)(n0 + row0) * rowb + (unsigned)ks * (64u * PB);
     unsigned zo = (unsigned)e * md.zs32 + (unsigned)(n0 + row0) * ng + (unsigned)g0;
     unsigned so = (unsigned)e * md.ss32 + (unsigned)(n0 + row0) * srow + (SCB ? (unsigned)(g0 & ~1) * 2u : (unsigned)g0 * 4u);
     XR<ACT> x = {};
     for (int b0 = 0; b0 < n_rows; b0 += DEC_RB) {
       const int nr = min(DEC_RB, n_rows - b0);
-      uint4 wm[DEC_RB], wl[DEC_RB];
+      typename PlaneT<FMT>::t wm[DEC_RB], wl[DEC_RB];
       uint32_t zz[DEC_RB], ss[DEC_RB];
 #pragma unroll
       for (int r = 0; r < DEC_RB; r++) {
@@ -861,8 +917,8 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int r = 0; r < DEC_RB; r++) {
-        wm[r] = bload128(R.msb, r < nr ? vo : DEC_OOB, po + (unsigned)r * rowb);
-        wl[r] = bload128(R.lsb, r < nr ? vl : DEC_OOB, po + (unsigned)r * rowb);
+        wm[r] = pload<FMT>(R.msb, r < nr ? vo : DEC_OOB, po + (unsigned)r * rowb);
+        wl[r] = pload<FMT>(R.lsb, r < nr ? vl : DEC_OOB, po + (unsigned)r * rowb);
       }
       __builtin_amdgcn_sched_barrier(0);
       po += DEC_RB * rowb; zo += DEC_RB * ng; so += DEC_RB * srow;
@@ -909,7 +965,7 @@ static int ilog2_exact(int v) {
   return (1 << s) == v ? s : -1;
 }
 
-template <int ACT, int SCB>
+template <int ACT, int SCB, int FMT>
 static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int n_wg, int T) {
   // down kernel: pieces = combos x parts
   const int n_combo_s = a.n_shared * a.ks_s, n_combo = n_combo_s + a.k * a.ks_r;
@@ -921,7 +977,7 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
   if (lds > 64u * 1024u) {       // beyond the default per-work-group limit: ask for the larger carve-out
     static size_t granted = 0;
     if (lds > granted) {
-      if (hipFuncSetAttribute((const void*)down_kernel<ACT, SCB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+      if (hipFuncSetAttribute((const void*)down_kernel<ACT, SCB, FMT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
         return SMOE_ESIZE;
       }
@@ -939,14 +995,14 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
     // measurement aid: the dispatches themselves carry start/stop events (no extra marker packets)
     hipEvent_t ev[4];
     for (int i = 0; i < 4; i++) { HIPCHK(ctx, hipEventCreate(&ev[i])); evs->push_back(ev[i]); }
-    hipExtLaunchKernelGGL((gateup_kernel<ACT, SCB>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
+    hipExtLaunchKernelGGL((gateup_kernel<ACT, SCB, FMT>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
                           in.E, in.k, in.do_route, a.d_model, n_wg, n_se, a);
-    hipExtLaunchKernelGGL((down_kernel<ACT, SCB>), g2, blk, (unsigned)lds, ctx->stream, ev[2], ev[3], 0, recw, (const float*)a.h,
+    hipExtLaunchKernelGGL((down_kernel<ACT, SCB, FMT>), g2, blk, (unsigned)lds, ctx->stream, ev[2], ev[3], 0, recw, (const float*)a.h,
                           n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s, a.ks_r, a.inv_ks_s, a.inv_ks_r, nsf, a);
   } else {
-    gateup_kernel<ACT, SCB><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, n_wg, n_se,
+    gateup_kernel<ACT, SCB, FMT><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, n_wg, n_se,
                                                          a);
-    down_kernel<ACT, SCB><<<g2, blk, lds, ctx->stream>>>(recw, (const float*)a.h, n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s,
+    down_kernel<ACT, SCB, FMT><<<g2, blk, lds, ctx->stream>>>(recw, (const float*)a.h, n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s,
                                                          a.ks_r, a.inv_ks_s, a.inv_ks_r, nsf, a);
   }
   HIPCHK(ctx, hipGetLastError());
@@ -959,7 +1015,7 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   if (routed && routed->device != ctx->device) return SMOE_EINVAL;
   if (shared && shared->device != ctx->device) return SMOE_EINVAL;
   if (routed && shared && routed->desc.d_model != shared->desc.d_model) return SMOE_ESHAPE;
-  if ((routed && routed->dev.bits != 4) || (shared && shared->dev.bits != 4)) return SMOE_ENOTIMPL;
+  if (routed && shared && routed->dev.bits != shared->dev.bits) return SMOE_ENOTIMPL;          // one nest per layer
   if (!routed && k != 0) return SMOE_ESHAPE;
   if (routed && (k <= 0 || k > routed->desc.n_experts || k > SMOE_MAX_TOPK)) return SMOE_ESHAPE;
   if (routed && routed->desc.n_experts > SMOE_MAX_EXPERTS) return SMOE_ESHAPE;
@@ -1007,8 +1063,13 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   a.inv_ks_s = (65536 + a.ks_s - 1) / a.ks_s;
   const int scb = routed ? routed->dev.sc_bf16 : shared->dev.sc_bf16;
   if (routed && shared && routed->dev.sc_bf16 != shared->dev.sc_bf16) return SMOE_ENOTIMPL;   // one scale dtype per layer
-  if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_F32, 0>(ctx, in, a, n_wg, T);
-  return scb ? launch_decode_t<SMOE_BF16, 1>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_BF16, 0>(ctx, in, a, n_wg, T);
+  const int bits = routed ? routed->dev.bits : shared->dev.bits;
+  if (bits == 2) {
+    if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1, 1>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_F32, 0, 1>(ctx, in, a, n_wg, T);
+    return scb ? launch_decode_t<SMOE_BF16, 1, 1>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_BF16, 0, 1>(ctx, in, a, n_wg, T);
+  }
+  if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1, 0>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_F32, 0, 0>(ctx, in, a, n_wg, T);
+  return scb ? launch_decode_t<SMOE_BF16, 1, 0>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_BF16, 0, 0>(ctx, in, a, n_wg, T);
 }
 
 extern "C" int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,

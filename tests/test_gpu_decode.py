@@ -272,6 +272,33 @@ def test_multi_token_layer(ctx, T, dt):
                                        C.c_void_p(y.data_ptr()), None, None, None) == -1
 
 
+@pytest.mark.parametrize("dt,G", [("bf16", 128), ("bf16", 32), ("f32", 64)])
+def test_4_2_nest_layer(ctx, dt, G):
+    # the 4/2 nest (4-bit codes, 2-bit planes): LOW = upper two bits with the zero-point shifted by
+    # two, HIGH = both planes; ragged chunk counts, a shared expert, masks of every kind
+    say("4/2 nest layer", dt, G)
+    shp = synth.LayerShape(512, 10, 416, 3, G, n_shared=1, shared_d_ff=224, act=dt, b_high=4, b_low=2)
+    wl = synth.Workload("mat42", shp, steps=5, seed=37)
+    pair = LayerPair(ctx, shp, seed=wl.seed)
+    x_all = synth.activations(wl.seed, wl.steps, shp.d_model, shp.act)
+    masks = synth.bernoulli_masks(wl.seed, wl.steps, shp.n_experts)
+    masks[1, :] = 3
+    masks[2, :] = 1
+    logits = synth.normal_logits(wl.seed, wl.steps, shp.n_experts)
+    for fused in (False, True):
+        worst = _run_layer_steps(ctx, wl, pair, range(wl.steps), masks, None, logits, x_all, fused, add_residual=fused)
+        say("  fused", fused, "worst max-abs-rel", worst)
+    # HIGH and LOW differ, and a full-size layer shape runs too (one step, against the oracle)
+    shp2 = synth.LayerShape(2048, 8, 1408, 2, 128, n_shared=1, shared_d_ff=1408, act=dt, b_high=4, b_low=2)
+    if dt == "bf16" and G == 128:
+        wl2 = synth.Workload("mat42-full", shp2, steps=1, seed=38)
+        pair2 = LayerPair(ctx, shp2, seed=wl2.seed)
+        x2 = synth.activations(wl2.seed, 1, 2048, dt)
+        m2 = synth.bernoulli_masks(wl2.seed, 1, 8)
+        z2 = synth.normal_logits(wl2.seed, 1, 8)
+        _run_layer_steps(ctx, wl2, pair2, range(1), m2, None, z2, x2, True)
+
+
 def test_dense_ffn_through_shared_bank(ctx):
     # no routed bank at all: a dense SwiGLU run HIGH; K of the down projection is not a multiple
     # of the group (416 = 3*128 + 32)
