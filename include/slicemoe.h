@@ -2,8 +2,8 @@
  * slicemoe.h -- C ABI of the MI355X (gfx950) SliceMoE expert-FFN library.
  *
  * The calls follow the paper's statement of the problem (SliceMoE, arXiv 2512.12990):
- *   quantize/slice   AMAT: group-wise asymmetric 8-bit codes whose upper 4 bits are the
- *                    low-bit model (Section 4.2 and its equation, Table 1 note 1)
+ *   quantize/slice   AMAT: group-wise asymmetric b_high-bit codes whose upper b_low bits are the
+ *                    low-bit model (Section 4.2 and its equation, Table 1 note 1); 8/4 and 4/2
  *   route            cache-aware top-k: resident experts get a score boost (Section 2.1)
  *   expert_ffn(mask) per selected expert a SwiGLU FFN run from the MSB slice alone or from
  *                    MSB+LSB, decided by slice residency (Section 4.1)
@@ -51,7 +51,9 @@ typedef struct smoe_cache smoe_cache; /* host-only slice LRU */
 
 /* One set of equally shaped SwiGLU experts: gate, up are [d_ff, d_model], down is [d_model, d_ff].
  * d_model, d_ff and group must be multiples of 32 (a K that is not a multiple of `group` gets a
- * short last group).  b_high/b_low: only 8/4 is implemented. */
+ * short last group).  b_high/b_low: 8/4 (8-bit codes, two nibble planes) and 4/2 (4-bit codes, two
+ * 2-bit planes: half the bytes) are implemented; the low-bit model is always the upper b_low bits
+ * with the zero-point shifted by the same amount.  6/3 returns SMOE_ENOTIMPL. */
 typedef struct {
   int32_t n_experts, d_model, d_ff, group;
   int32_t b_high, b_low;

@@ -122,7 +122,7 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // One work-group of eight waves (two per SIMD) per CU: the tile is 192 token rows x 256 weight rows,
 // a wave owns 96 x 64 of it (3 x 2 MFMA fragments), and LDS holds two copies of the K slice so that
 // one barrier per K step is enough.
-template <int MODE, int SCB>
+template <int MODE, int SCB, int FMT>      // FMT 0: 8/4 nest, nibble planes; 1: 4/2 nest, 2-bit planes
 __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
   // (separate arrays, so that the compiler knows a write into one buffer cannot alias a read of the other)
   __shared__ __align__(16) uint16_t As0[PF_BM * PF_LDK], As1[PF_BM * PF_LDK];
@@ -182,7 +182,8 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
   const uint8_t* pl = a.w.lsb + (size_t)e * a.w.plane_stride;
   const uint8_t* ps = a.w.sc + (size_t)e * a.w.sc_stride;
   const uint8_t* pz = a.w.zp + (size_t)e * a.w.zp_stride;       // 4-byte aligned: zp_stride is a multiple of 4
-  const uint32_t poff = (uint32_t)grow * (uint32_t)(K >> 1) + hb * 16;
+  constexpr int PSH = FMT ? 2 : 1;                      // columns per plane byte = 1 << PSH
+  const uint32_t poff = (uint32_t)grow * (uint32_t)(K >> PSH) + hb * (32 >> PSH);
   const uint32_t srow = (uint32_t)grow * (uint32_t)a.w.sng;
   const uint32_t zrow = (uint32_t)grow * (uint32_t)a.w.ng;
   const int b_dst = b * PF_LDK + hb * 32;
@@ -191,7 +192,8 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
   // computed.  The registers hold what the loads return, untouched: arithmetic on them at this
   // point would make the wave wait for the loads.
   struct PreA { u32x4 ra[3]; };
-  struct Pre { u32x4 rm, rl; };
+  typedef typename std::conditional<FMT != 0, u32x2, u32x4>::type PlaneV;      // a thread's 32 codes of one plane
+  struct Pre { PlaneV rm, rl; };
   // Scales and zero-points of eight consecutive groups of the thread's row (the chunk that holds the
   // groups of a K step), kept in registers and reloaded only when a step enters a new chunk: loading
   // them step by step costs a cache line per thread and step.  Reads are clamped to the expert's
@@ -217,11 +219,10 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
     for (int q = 0; q < 3; q++) *(u32x4*)(As + a_dst0 + q * 64 * PF_LDK) = p.ra[q];
   };
   auto gload = [&](int k0, Pre& p) __attribute__((always_inline)) {
-    p.rm = *(const u32x4*)(pm + (poff + (uint32_t)(k0 >> 1)));
-    p.rl = *(const u32x4*)(pl + (poff + (uint32_t)(k0 >> 1)));
+    p.rm = *(const PlaneV*)(pm + (poff + (uint32_t)(k0 >> PSH)));
+    p.rl = *(const PlaneV*)(pl + (poff + (uint32_t)(k0 >> PSH)));
   };
   auto lstore = [&](int k0, const Pre& p, const Meta& m, uint16_t* Bs) __attribute__((always_inline)) {
-    const uint32_t wm[4] = {p.rm.x, p.rm.y, p.rm.z, p.rm.w}, wl[4] = {p.rl.x, p.rl.y, p.rl.z, p.rl.w};
     const uint32_t g = (uint32_t)(k0 + 32 * hb) >> a.group_shift, gi = g & 7u;
     float rs;
     if (SCB) {
@@ -237,9 +238,25 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
     uint32_t out[16];
 #pragma unroll
     for (int j = 0; j < 4; j++) {
-      // the planes hold n ^ 8 per nibble
-      const uint32_t qe = (((wm[j] & 0x0F0F0F0Fu) << 4) | (wl[j] & 0x0F0F0F0Fu)) ^ 0x88888888u;      // even columns
-      const uint32_t qo = ((wm[j] & 0xF0F0F0F0u) | ((wl[j] >> 4) & 0x0F0F0F0Fu)) ^ 0x88888888u;     // odd columns
+      uint32_t qe, qo;                          // codes of the even / odd columns of columns 8j .. 8j+7, one per byte
+      if (FMT == 0) {
+        // the planes hold n ^ 8 per nibble
+        const uint32_t wm = p.rm[j], wl = p.rl[j];
+        qe = (((wm & 0x0F0F0F0Fu) << 4) | (wl & 0x0F0F0F0Fu)) ^ 0x88888888u;
+        qo = ((wm & 0xF0F0F0F0u) | ((wl >> 4) & 0x0F0F0F0Fu)) ^ 0x88888888u;
+      } else {
+        // sixteen 2-bit codes per plane word, column c in bits 2c, 2c+1: spread half a word to one
+        // code per nibble, then code = 4 msb + lsb
+        auto spread = [](uint32_t h) {
+          h = (h | (h << 8)) & 0x00FF00FFu;
+          h = (h | (h << 4)) & 0x0F0F0F0Fu;
+          return (h | (h << 2)) & 0x33333333u;
+        };
+        const uint32_t hm = (p.rm[j >> 1] >> (16 * (j & 1))) & 0xFFFFu, hl = (p.rl[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+        const uint32_t qn = (spread(hm) << 2) | spread(hl);
+        qe = qn & 0x0F0F0F0Fu;
+        qo = (qn >> 4) & 0x0F0F0F0Fu;
+      }
 #pragma unroll
       for (int bb = 0; bb < 4; bb++) {
         const float we = fmaf((float)((qe >> (8 * bb)) & 0xFF), rs, c0);
@@ -418,6 +435,18 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* o, const int3
 // ------------------------------------------------------------------------------- host entry
 static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// bits = plane bits per code of the bank (4: 8/4 nest, 2: 4/2 nest)
+template <int MODE>
+static void launch_gemm(const GemmArgs& g, int bits, int grid, hipStream_t st) {
+  if (bits == 2) {
+    if (g.sc_bf16) grouped_gemm_kernel<MODE, 1, 1><<<grid, PF_NT, 0, st>>>(g);
+    else grouped_gemm_kernel<MODE, 0, 1><<<grid, PF_NT, 0, st>>>(g);
+  } else {
+    if (g.sc_bf16) grouped_gemm_kernel<MODE, 1, 0><<<grid, PF_NT, 0, st>>>(g);
+    else grouped_gemm_kernel<MODE, 0, 0><<<grid, PF_NT, 0, st>>>(g);
+  }
+}
+
 struct PrefillLayout { size_t rows, pos, offsets, tiles, h, o, gamma, h_s, o_s, total; };
 
 static inline int max_tiles(int T, int E, int k) { return E + (T * k) / PF_BM; }
@@ -458,7 +487,6 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
   if (!logits_dev && !w_router_dev) return SMOE_EINVAL;
   if (shared_gate_w_dev && !shared) return SMOE_EINVAL;
   if (act_dtype != SMOE_BF16) return SMOE_ENOTIMPL;
-  if (routed->dev.bits != 4 || (shared && shared->dev.bits != 4)) return SMOE_ENOTIMPL;
   if (routed->device != ctx->device || (shared && shared->device != ctx->device)) return SMOE_EINVAL;
   const int E = routed->desc.n_experts, d = routed->desc.d_model, f = routed->desc.d_ff;
   if (T <= 0 || k <= 0 || k > E || k > SMOE_MAX_TOPK || E > SMOE_MAX_EXPERTS) return SMOE_ESHAPE;
@@ -495,11 +523,9 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
   const int mt = max_tiles(T, E, k);             // upper bound of the tile count; surplus work-groups return at once
   const int mt8 = (mt + 7) / 8 * 8;
   g.w = routed->dev.gu; g.n_col_tiles = (2 * f + PF_BN - 1) / PF_BN;
-  if (g.sc_bf16) grouped_gemm_kernel<0, 1><<<mt8 * g.n_col_tiles, PF_NT, 0, st>>>(g);
-  else grouped_gemm_kernel<0, 0><<<mt8 * g.n_col_tiles, PF_NT, 0, st>>>(g);
+  launch_gemm<0>(g, routed->dev.bits, mt8 * g.n_col_tiles, st);
   g.w = routed->dev.dn; g.n_col_tiles = (d + PF_BN - 1) / PF_BN;
-  if (g.sc_bf16) grouped_gemm_kernel<1, 1><<<mt8 * g.n_col_tiles, PF_NT, 0, st>>>(g);
-  else grouped_gemm_kernel<1, 0><<<mt8 * g.n_col_tiles, PF_NT, 0, st>>>(g);
+  launch_gemm<1>(g, routed->dev.bits, mt8 * g.n_col_tiles, st);
   float* o_s = nullptr;
   if (shared) {
     // the shared experts see every token: dense GEMMs over the token rows in their own order, one
@@ -515,11 +541,9 @@ extern "C" int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, co
     for (int e = 0; e < shared->desc.n_experts; e++) {
       q.dense_expert = e; q.accumulate = e > 0;
       q.w = shared->dev.gu; q.n_col_tiles = (2 * f_s + PF_BN - 1) / PF_BN;
-      if (q.sc_bf16) grouped_gemm_kernel<0, 1><<<nt8 * q.n_col_tiles, PF_NT, 0, st>>>(q);
-      else grouped_gemm_kernel<0, 0><<<nt8 * q.n_col_tiles, PF_NT, 0, st>>>(q);
+      launch_gemm<0>(q, shared->dev.bits, nt8 * q.n_col_tiles, st);
       q.w = shared->dev.dn; q.n_col_tiles = (d + PF_BN - 1) / PF_BN;
-      if (q.sc_bf16) grouped_gemm_kernel<1, 1><<<nt8 * q.n_col_tiles, PF_NT, 0, st>>>(q);
-      else grouped_gemm_kernel<1, 0><<<nt8 * q.n_col_tiles, PF_NT, 0, st>>>(q);
+      launch_gemm<1>(q, shared->dev.bits, nt8 * q.n_col_tiles, st);
     }
   }
   combine_kernel<<<T, 256, 0, st>>>(o, pos, o_s, (const uint16_t*)x_dev, (uint16_t*)y_dev, k, d, add_residual);

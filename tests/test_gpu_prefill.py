@@ -90,6 +90,31 @@ def test_prefill_with_shared_experts(ctx, n_shared, f_s, gate):
     assert O.max_abs_rel(t2np(yd), t2np(y[t])) <= TOL
 
 
+@pytest.mark.parametrize("G,sdt", [(64, "bf16"), (32, "bf16")])
+def test_prefill_4_2_nest(ctx, G, sdt):
+    # the 4/2 nest (4-bit codes in 2-bit planes) through the prefill path, with a gated shared expert
+    T, E, k, d, f = 230, 6, 2, 256, 192
+    say("prefill 4/2 nest", G)
+    shp = synth.LayerShape(d, E, f, k, G, n_shared=1, shared_d_ff=128, shared_gate=True, act=sdt, b_high=4, b_low=2)
+    pair = LayerPair(ctx, shp, seed=41)
+    x = synth.activations(41, T, d, "bf16").cuda()
+    wr = synth.router_weight(41, 0, E, d, std=0.05).cuda()
+    wsg = synth.shared_gate_weight(41, 0, d, "bf16", std=0.05).cuda()
+    y, idx, w, hist = B.smoe_prefill_histogram(ctx, pair.routed, pair.shared, x, k, w_router=wr, shared_gate_w=wsg,
+                                               add_residual=True)
+    ridx, rw = _check_routing(ctx, x, wr, k, idx, w, hist, E)
+    yref = O.prefill_layer(t2np(x).astype(np.float64), pair.oracle_routed(), ridx,
+                           rw.astype(np.float32).astype(np.float64), pair.oracle_shared(), t2np(wsg), add_residual=True)
+    yg = t2np(y)
+    for t in range(T):
+        assert O.max_abs_rel(yg[t], yref[t]) <= TOL, t
+    # and it agrees with the decode path on one token (both HIGH)
+    t = 3
+    yd = B.smoe_expert_ffn(ctx, pair.routed, pair.shared, x[t].clone(), idx[t].clone(), w[t].clone(),
+                           torch.from_numpy(np.full(E, 3, np.uint8)).cuda(), shared_gate_w=wsg, add_residual=True)
+    assert O.max_abs_rel(t2np(yd), t2np(y[t])) <= TOL
+
+
 def test_prefill_empty_expert_and_given_logits(ctx):
     say("prefill with an expert nobody selects")
     T, E, k, d, f, G = 64, 4, 2, 128, 64, 32
