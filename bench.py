@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=1,
                     help="decode: tokens per step that pass the layer together in one pair of launches (1 = the headline "
                          "single-batch workload; 2-16 = smoe_decode_layer_multi, reported per token)")
+    ap.add_argument("--prefill-tokens", type=int, default=0,
+                    help="prefill: tokens of the prompt (default: the workload's 2048)")
     ap.add_argument("--with-shared", action="store_true",
                     help="prefill: add the Qwen-shaped shared expert (d_ff 5632 behind a sigmoid gate) that every "
                          "token passes through; reported as its own line, not the headline")
@@ -271,7 +273,7 @@ def prefill_bench(args):
     from paper_2512_12990_amd import binding as B, synth
     wl = synth.QWEN_PREFILL
     shp = wl.layer
-    T, dev = wl.prefill_tokens, "cuda:0"
+    T, dev = args.prefill_tokens or wl.prefill_tokens, "cuda:0"
     ctx = B.Ctx(0)
     routed = B.Bank(ctx, shp.n_experts, shp.d_model, shp.d_ff, shp.group, "bf16", "bf16")
     for e in range(shp.n_experts):
@@ -306,7 +308,7 @@ def prefill_bench(args):
     if f_s:
         wbytes += sum(slot_bytes(shp.d_model, f_s, shp.group, 1))
     print(json.dumps({
-        "metric": "prefill MoE-layer ms (2048 tokens, grouped expert GEMM + histogram)", "value": ms, "unit": "ms/layer",
+        "metric": "prefill MoE-layer ms (%d tokens, grouped expert GEMM + histogram)" % T, "value": ms, "unit": "ms/layer",
         "n_gpus": 1, "steps": steps, "warmup": 3, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 MFMA, fp32 accumulate, u4+u4 sliced weights", "data": "synthetic",
         "config": {"workload": "Qwen1.5-MoE-shaped prefill layer (BASELINE configs[4], one layer)", "tokens": T,
