@@ -47,7 +47,7 @@ struct MatK {
 
 // Kernel arguments, kept compact and ordered by use: a dispatch's arguments are cold in every
 // cache, each 64-byte line of them costs a memory round trip when first touched, and the kernels
-// therefore fetch all their lines at once in their first instructions (KARGS_TOUCH).
+// therefore fetch all their lines at once in their first instructions (KARGS_FETCH).
 struct DecodeArgs {
   MatK rgu, sgu;                   // gate/up families of the routed / shared bank        [gate/up kernel]
   const int32_t* idx_in; const float* w_in;
@@ -83,29 +83,30 @@ struct RouteIn {
   int E, k, do_route;              // do_route 0: idx_in / w_in of DecodeArgs hold the decision
 };
 
-// Kernel-argument fetch: KARGS_TOUCH issues one scalar load per 64-byte line of the argument
-// segment (eight lines) into scratch registers, KARGS_WAIT waits for them; afterwards the
-// compiler's own argument loads hit the scalar cache.  The scratch registers stay reserved between
-// the two statements, so nothing can be overwritten by a load that is still in flight.
-struct KargTouch { unsigned t[7]; };
+// Kernel-argument fetch: KARGS_FETCH issues one scalar load per 64-byte line of the argument
+// segment (eight lines) and waits for them; afterwards the compiler's own argument loads hit the
+// scalar cache.  It stands behind the first vector loads of a kernel (which need only the leading
+// parameters), so the argument lines and those loads are in flight together.  Issue and wait are one
+// statement on purpose: the destination registers hold dead values, and between two statements the
+// compiler is free to give them to live values, which a load still in flight then overwrites.
 #define KARG_OFF(i, size) ((i) * 64 < (size) ? (i) * 64 : (size) - 4)      /* never past the last argument */
-#define KARGS_TOUCH(kt, size)                                                                                             \
-  asm volatile("s_load_dword %0, %7, %8\n\ts_load_dword %1, %7, %9\n\ts_load_dword %2, %7, %10\n\t"                    \
-               "s_load_dword %3, %7, %11\n\ts_load_dword %4, %7, %12\n\ts_load_dword %5, %7, %13\n\t"                  \
-               "s_load_dword %6, %7, %14"                                                                                 \
-               : "=&s"(kt.t[0]), "=&s"(kt.t[1]), "=&s"(kt.t[2]), "=&s"(kt.t[3]), "=&s"(kt.t[4]), "=&s"(kt.t[5]), "=&s"(kt.t[6])  \
-               : "s"(__builtin_amdgcn_kernarg_segment_ptr()), "n"(KARG_OFF(1, size)), "n"(KARG_OFF(2, size)),             \
-                 "n"(KARG_OFF(3, size)), "n"(KARG_OFF(4, size)), "n"(KARG_OFF(5, size)), "n"(KARG_OFF(6, size)),          \
-                 "n"(KARG_OFF(7, size)))
-#define KARGS_WAIT(kt)                                                                                                    \
-  asm volatile("s_waitcnt lgkmcnt(0)" ::"s"(kt.t[0]), "s"(kt.t[1]), "s"(kt.t[2]), "s"(kt.t[3]), "s"(kt.t[4]), "s"(kt.t[5]),   \
-               "s"(kt.t[6])                                                                                               \
-               : "memory")
+#define KARGS_FETCH(size)                                                                                                 \
+  do {                                                                                                                    \
+    unsigned kt0_, kt1_, kt2_, kt3_, kt4_, kt5_, kt6_;                                                                    \
+    asm volatile("s_load_dword %0, %7, %8\n\ts_load_dword %1, %7, %9\n\ts_load_dword %2, %7, %10\n\t"                  \
+                 "s_load_dword %3, %7, %11\n\ts_load_dword %4, %7, %12\n\ts_load_dword %5, %7, %13\n\t"                \
+                 "s_load_dword %6, %7, %14\n\ts_waitcnt lgkmcnt(0)"                                                       \
+                 : "=&s"(kt0_), "=&s"(kt1_), "=&s"(kt2_), "=&s"(kt3_), "=&s"(kt4_), "=&s"(kt5_), "=&s"(kt6_)              \
+                 : "s"(__builtin_amdgcn_kernarg_segment_ptr()), "n"(KARG_OFF(1, size)), "n"(KARG_OFF(2, size)),           \
+                   "n"(KARG_OFF(3, size)), "n"(KARG_OFF(4, size)), "n"(KARG_OFF(5, size)), "n"(KARG_OFF(6, size)),        \
+                   "n"(KARG_OFF(7, size))                                                                                 \
+                 : "memory");                                                                                             \
+  } while (0)
 /* floats between the h vectors of consecutive tokens of a multi-token launch (both kernels must
  * know it from their leading parameters: room for the largest top-k) */
 #define DEC_H_STRIDE(nsf, f_r) ((nsf) + SMOE_MAX_TOPK * (f_r))
 #define DEC_LEAD_BYTES 56      /* both kernels have 56 bytes of leading parameters before the struct */
-static_assert(sizeof(DecodeArgs) + DEC_LEAD_BYTES <= 8 * 64, "KARGS_TOUCH covers eight lines");
+static_assert(sizeof(DecodeArgs) + DEC_LEAD_BYTES <= 8 * 64, "KARGS_FETCH covers eight lines");
 
 __device__ __forceinline__ void lds_barrier() {
   // orders LDS traffic only; outstanding global loads stay in flight across it
@@ -456,8 +457,10 @@ __device__ __forceinline__ float unorderable(uint32_t o) {
 // expert e; the loads are issued by route_load so that they overlap other work.
 struct RouteRegs { float z[4]; float b[4]; int mk[4]; };
 
-// Unconditional loads: an absent input is a buffer of zero records, which reads as 0.
-__device__ __forceinline__ void route_load(const RouteIn& in, int lane, RouteRegs& r) {
+// Unconditional loads: an absent input is a buffer of zero records, which reads as 0, and a wave
+// that does not route (`on` false) reads out of range.  No branch, so no value has to be complete
+// where control flow merges: the byte -> int conversions wait where the values are first used.
+__device__ __forceinline__ void route_load(const RouteIn& in, int lane, RouteRegs& r, bool on) {
   const unsigned E = (unsigned)in.E;
   const __amdgpu_buffer_rsrc_t rz = make_rsrc(in.logits, in.do_route ? E * 4u : 0u);
   const __amdgpu_buffer_rsrc_t rb = make_rsrc(in.bias, (in.do_route && in.bias) ? E * 4u : 0u);
@@ -465,9 +468,9 @@ __device__ __forceinline__ void route_load(const RouteIn& in, int lane, RouteReg
 #pragma unroll
   for (int j = 0; j < 4; j++) {
     const unsigned e = (unsigned)(lane + 64 * j);
-    r.z[j] = __uint_as_float(bload32(rz, e * 4u, 0));
-    r.b[j] = __uint_as_float(bload32(rb, e * 4u, 0));
-    r.mk[j] = (int)bload8(rm, e, 0);
+    r.z[j] = __uint_as_float(bload32(rz, on ? e * 4u : DEC_OOB, 0));
+    r.b[j] = __uint_as_float(bload32(rb, on ? e * 4u : DEC_OOB, 0));
+    r.mk[j] = (int)bload8(rm, on ? e : DEC_OOB, 0);
   }
 }
 
@@ -640,13 +643,11 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
   const int xt = tid - (k > 0 ? (DEC_NW - 5) * 64 : 0);
   const bool stager = xt >= 0 && xt < 4 * C;
   const bool router = k > 0 && wave == DEC_NW - 1;
-  KargTouch kt;
-  KARGS_TOUCH(kt, DEC_LEAD_BYTES + (int)sizeof(DecodeArgs));      // four pointers and six 4-byte leading parameters, then the struct
   Raw8 xraw = {};
   RouteRegs rr = {};
   if (stager) load8_raw<ACT>(x_in, (size_t)xt * 8, xraw);
-  if (router) route_load(in, lane, rr);
-  KARGS_WAIT(kt);
+  route_load(in, lane, rr, router);
+  KARGS_FETCH(DEC_LEAD_BYTES + (int)sizeof(DecodeArgs));      // four pointers and six 4-byte leading parameters, then the struct
   __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
   if (tok) {
     a.h += (size_t)tok * DEC_H_STRIDE(a.n_shared * a.f_s, a.f_r);
@@ -857,8 +858,6 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
     rec += tok * (int)(sizeof(RouteRec) / 4);
     h += (size_t)tok * DEC_H_STRIDE(nsf, f_r);
   }
-  KargTouch kt;
-  KARGS_TOUCH(kt, DEC_LEAD_BYTES + (int)sizeof(DecodeArgs));      // two pointers and ten 4-byte leading parameters, then the struct
   bool kargs_here = false;
 
   for (int p = wave; p < n_pieces; p += DEC_NW) {
@@ -881,7 +880,10 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
       hraw[q][1] = bload128(RH, (unsigned)(lane + 64 * q) * 32u, 16);
     }
     const int rec_word = rec[lane];
-    if (!kargs_here) { KARGS_WAIT(kt); kargs_here = true; }
+    if (!kargs_here) {      // two pointers and ten 4-byte leading parameters, then the struct
+      KARGS_FETCH(DEC_LEAD_BYTES + (int)sizeof(DecodeArgs));
+      kargs_here = true;
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
     const int e = is_sh ? slot : __builtin_amdgcn_readlane(rec_word, slot);
     const int prec = is_sh ? 1 : __builtin_amdgcn_readlane(rec_word, SMOE_MAX_TOPK + slot);
@@ -945,7 +947,6 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
       if (lane >= 60 && lane - 60 < nr) part[combo * DEC_RPW + row0 + b0 + lane - 60] = wt * tot;
     }
   }
-  if (!kargs_here) KARGS_WAIT(kt);
   __syncthreads();
   if (tid < DEC_RPW) {
     const int n_combo = n_pieces >> psh;
