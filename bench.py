@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 
 
-PLANE_BITS = 4      # bits per code in a plane: 4 for the 8/4 nest, 2 for the 4/2 nest (--nest 42)
+PLANE_BITS = 4      # bits per code in a plane: 4 for the 8/4 nest, 3 for 6/3 (--nest 63), 2 for 4/2 (--nest 42)
 
 
 def slot_bytes(d, f, group, prec, scale_bytes=2):
@@ -53,9 +53,9 @@ def main():
     ap.add_argument("--router-matvec", action="store_true",
                     help="decode (one token per step): logits from the router mat-vec W_r x (a third launch) instead of "
                          "supplied logits")
-    ap.add_argument("--nest", choices=["84", "42"], default="84",
+    ap.add_argument("--nest", choices=["84", "63", "42"], default="84",
                     help="decode: bit nest of the expert weights: 84 = 8-bit codes / 4-bit low-bit model (headline), "
-                         "42 = 4-bit codes / 2-bit low-bit model (half the plane bytes)")
+                         "63 = 6-bit codes / 3-bit, 42 = 4-bit codes / 2-bit low-bit model (3/4 and 1/2 of the plane bytes)")
     ap.add_argument("--tokens", type=int, default=1,
                     help="decode: tokens per step that pass the layer together in one pair of launches (1 = the headline "
                          "single-batch workload; 2-16 = smoe_decode_layer_multi, reported per token)")
@@ -84,7 +84,7 @@ def main():
     if args.workload == "prefill":
         return prefill_bench(args)
     global PLANE_BITS
-    bh, bl = (8, 4) if args.nest == "84" else (4, 2)
+    bh, bl = {"84": (8, 4), "63": (6, 3), "42": (4, 2)}[args.nest]
     PLANE_BITS = bl
     wl = synth.DSV2_LAYER
     if args.shape == "qwen":
@@ -230,7 +230,7 @@ def main():
         "metric": "decode MoE-layer us/token (+ achieved HBM GB/s as a fraction of MI355X peak)",
         "value": ms_per_step * 1e3 / TT, "unit": "us/token", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u4+u4 bit-sliced weights, bf16 activations rewritten per 32-chunk as 3 balanced hex digits, signed 4-bit dot products, int32/fp32 accumulate",
+        "dtype": "u%d+u%d bit-sliced weights, bf16 activations rewritten per 32-chunk as 3 balanced hex digits, signed 4-bit dot products, int32/fp32 accumulate" % (bl, bl),
         "data": "synthetic",
         "config": {"workload": ("DeepSeek-V2-Lite-shaped MoE layer decode, %d token%s/step (BASELINE configs[1])" if args.shape == "dsv2" else
                                 "Qwen1.5-MoE-shaped MoE layer decode, %d token%s/step (one layer of BASELINE configs[2])") % (TT, "" if TT == 1 else "s"),

@@ -3,7 +3,7 @@
  *
  * The calls follow the paper's statement of the problem (SliceMoE, arXiv 2512.12990):
  *   quantize/slice   AMAT: group-wise asymmetric b_high-bit codes whose upper b_low bits are the
- *                    low-bit model (Section 4.2 and its equation, Table 1 note 1); 8/4 and 4/2
+ *                    low-bit model (Section 4.2 and its equation, Table 1 note 1); 8/4, 6/3, 4/2
  *   route            cache-aware top-k: resident experts get a score boost (Section 2.1)
  *   expert_ffn(mask) per selected expert a SwiGLU FFN run from the MSB slice alone or from
  *                    MSB+LSB, decided by slice residency (Section 4.1)
@@ -40,7 +40,7 @@ typedef enum {
   SMOE_EALIGN = -3,   /* device pointer not 16-byte aligned */
   SMOE_ESIZE = -4,    /* a caller buffer or the ctx workspace is too small */
   SMOE_EHIP = -5,     /* a HIP call failed; see smoe_last_hip_error */
-  SMOE_ENOTIMPL = -6  /* valid request this build does not implement (e.g. 6/3-bit nests) */
+  SMOE_ENOTIMPL = -6  /* valid request this build does not implement (e.g. a 5/2-bit nest) */
 } smoe_status;
 
 enum { SMOE_F32 = 0, SMOE_BF16 = 1 };
@@ -51,9 +51,10 @@ typedef struct smoe_cache smoe_cache; /* host-only slice LRU */
 
 /* One set of equally shaped SwiGLU experts: gate, up are [d_ff, d_model], down is [d_model, d_ff].
  * d_model, d_ff and group must be multiples of 32 (a K that is not a multiple of `group` gets a
- * short last group).  b_high/b_low: 8/4 (8-bit codes, two nibble planes) and 4/2 (4-bit codes, two
- * 2-bit planes: half the bytes) are implemented; the low-bit model is always the upper b_low bits
- * with the zero-point shifted by the same amount.  6/3 returns SMOE_ENOTIMPL. */
+ * short last group).  b_high/b_low: the three nests of Table 1 are implemented -- 8/4 (8-bit codes,
+ * two nibble planes), 6/3 (6-bit codes, two 3-bit planes: 3/4 of the plane bytes) and 4/2 (4-bit
+ * codes, two 2-bit planes: half of them); the low-bit model is always the upper b_low bits with the
+ * zero-point shifted by the same amount.  Any other pair returns SMOE_ENOTIMPL. */
 typedef struct {
   int32_t n_experts, d_model, d_ff, group;
   int32_t b_high, b_low;

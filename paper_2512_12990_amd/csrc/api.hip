@@ -86,7 +86,8 @@ static int check_desc(const smoe_bank_desc* d) {
   if ((d->w_dtype != SMOE_F32 && d->w_dtype != SMOE_BF16) || (d->scale_dtype != SMOE_F32 && d->scale_dtype != SMOE_BF16))
     return SMOE_EINVAL;
   if (d->b_high <= d->b_low || d->b_low < 1 || d->b_high > 8) return SMOE_ESHAPE;
-  if (!((d->b_high == 8 && d->b_low == 4) || (d->b_high == 4 && d->b_low == 2))) return SMOE_ENOTIMPL;   // 6/3: 3-bit planes
+  if (!((d->b_high == 8 && d->b_low == 4) || (d->b_high == 6 && d->b_low == 3) || (d->b_high == 4 && d->b_low == 2)))
+    return SMOE_ENOTIMPL;
   return SMOE_OK;
 }
 
@@ -188,6 +189,14 @@ extern "C" int smoe_export_codes(smoe_ctx* ctx, const smoe_bank* bank, int exper
       if (bits == 4) {
         const uint8_t bm = pm[sr * row_b + kk / 2] ^ 0x88, bl = pl[sr * row_b + kk / 2] ^ 0x88;   // stored as n ^ 8
         mv = (kk & 1) ? (bm >> 4) : (bm & 15); lv = (kk & 1) ? (bl >> 4) : (bl & 15);
+      } else if (bits == 3) {                                   // 12-byte chunks of 32 columns (see quantize.hip)
+        const int t = (kk & 31) >> 3, j = kk & 7;
+        auto code3 = [&](const std::vector<uint8_t>& pl8) {
+          uint32_t w[3];
+          memcpy(w, &pl8[sr * row_b + (size_t)(kk >> 5) * 12], 12);
+          return (uint8_t)(((w[t >> 1] >> (4 * j + 2 * (t & 1))) & 3u) | (((w[2] >> (4 * j + t)) & 1u) << 2));
+        };
+        mv = code3(pm); lv = code3(pl);
       } else {                                                  // four 2-bit codes per byte, column 4j in bits 0-1
         mv = (pm[sr * row_b + kk / 4] >> (2 * (kk & 3))) & 3; lv = (pl[sr * row_b + kk / 4] >> (2 * (kk & 3))) & 3;
       }

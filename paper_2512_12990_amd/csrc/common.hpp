@@ -14,14 +14,15 @@
 // ---- host objects -------------------------------------------------------------------------
 // Device view of one quantised matrix family inside a bank ("gu": gate and up rows interleaved,
 // row 2r = gate r, row 2r+1 = up r, shape [2*d_ff, d_model]; "dn": down, [d_model, d_ff]).
-// Per expert e the data starts at base + e * stride.  Planes hold two 4-bit values per byte,
-// row-major, low nibble = even column, each value n stored as n ^ 8 (= n - 8 in 4-bit two's
-// complement).  Metadata: zp uint8 [N, ng], scale [N, sng] (the first ng of a row are used).
+// Per expert e the data starts at base + e * stride.  Planes of the 8/4 nest hold two 4-bit values
+// per byte, row-major, low nibble = even column, each value n stored as n ^ 8 (= n - 8 in 4-bit two's
+// complement); the 4/2 nest keeps four 2-bit values per byte (column 4j in bits 0-1) and the 6/3 nest
+// 32 three-bit values per 12 bytes (layout in quantize.hip), both as plain unsigned values.  Metadata: zp uint8 [N, ng], scale [N, sng] (the first ng of a row are used).
 struct MatDev {
   const uint8_t* msb; const uint8_t* lsb; const uint8_t* zp; const uint8_t* sc;
   unsigned long long plane_stride, zp_stride, sc_stride;   // bytes per expert
   int N, K, ng, cpg;                                       // cpg = 32-column chunks per group
-  int bits;                                                // bits per code in a plane: 4 (8/4 nest) or 2 (4/2 nest)
+  int bits;                                                // bits per code in a plane: 4 (8/4 nest), 3 (6/3) or 2 (4/2)
   int sng;                                                 // scales per row as stored: ng rounded up to even, so that
                                                            // every row of scales starts on a 4-byte boundary
   unsigned ps32, zs32, ss32, fits32;                       // the strides as 32-bit numbers; fits32 = every
@@ -31,7 +32,7 @@ struct MatDev {
 struct BankDev {
   MatDev gu, dn;
   int n_experts, d_model, d_ff, group, sc_bf16;
-  int bits;             // plane bits per code (4: 8-bit codes of nibble planes; 2: 4-bit codes of 2-bit planes)
+  int bits;             // plane bits per code (4: 8-bit codes of nibble planes; 3: 6-bit codes; 2: 4-bit codes)
 };
 
 struct smoe_ctx {

@@ -173,12 +173,19 @@ __device__ __forceinline__ uint2 bload64(__amdgpu_buffer_rsrc_t r, unsigned voff
   return make_uint2(v.x, v.y);
 }
 // A lane's 32 codes of one plane as loaded.  FMT 0: 8/4 nest, nibble planes (16 bytes, every nibble n
-// stored as n ^ 8); FMT 1: 4/2 nest, 2-bit planes (8 bytes, column c of a word in bits 2c, 2c+1).
+// stored as n ^ 8); FMT 1: 4/2 nest, 2-bit planes (8 bytes, column c of a word in bits 2c, 2c+1);
+// FMT 2: 6/3 nest, 3-bit planes (12 bytes: two words of 2-bit fields and one word of third bits).
 template <int FMT> struct PlaneT { typedef uint4 t; enum { BYTES = 16 }; };
 template <> struct PlaneT<1> { typedef uint2 t; enum { BYTES = 8 }; };
+template <> struct PlaneT<2> { typedef uint3 t; enum { BYTES = 12 }; };
 template <int FMT> __device__ __forceinline__ typename PlaneT<FMT>::t pload(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff);
 template <> __device__ __forceinline__ uint4 pload<0>(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) { return bload128(r, voff, soff); }
 template <> __device__ __forceinline__ uint2 pload<1>(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) { return bload64(r, voff, soff); }
+template <> __device__ __forceinline__ uint3 pload<2>(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+  typedef unsigned int u32x3_t __attribute__((ext_vector_type(3)));
+  const u32x3_t v = __builtin_amdgcn_raw_buffer_load_b96(r, (int)voff, (int)soff, 0);
+  return make_uint3(v.x, v.y, v.z);
+}
 __device__ __forceinline__ uint32_t bload32(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
   return __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0);
 }
@@ -285,6 +292,30 @@ __device__ __forceinline__ float lane_value(const XR<SMOE_F32>& x, const uint2& 
   return (4.0f * s) * fmaf(-(float)(zp >> 2), x.xs, a0 + a1);
 }
 
+// 3-bit planes: word t of the result holds the values of columns 8t .. 8t+7, one per nibble (0..7).
+// Column 8t + j keeps its two low bits in word t >> 1 of the plane at bits 4j + 2(t & 1) and its
+// third bit in word 2 at bit 4j + t, so every nibble word is two shifts, two masks and an or.
+__device__ __forceinline__ uint4 nibbles_of(const uint3& p) {
+  return make_uint4((p.x & 0x33333333u) | ((p.z & 0x11111111u) << 2), ((p.x >> 2) & 0x33333333u) | ((p.z & 0x22222222u) << 1),
+                    (p.y & 0x33333333u) | (p.z & 0x44444444u), ((p.y >> 2) & 0x33333333u) | ((p.z & 0x88888888u) >> 1));
+}
+// 6/3 nest, codes as plain nibbles 0..7 (no offset):
+//   HIGH: s (8 m + l - zp) x = s sx (8 m.q + l.q - zp sum q)
+//   LOW : 8 s (m - (zp >> 3)) x = 8 s sx (m.q - (zp >> 3) sum q)
+__device__ __forceinline__ float lane_value(const XR<SMOE_BF16>& x, const uint3& m3, const uint3& l3, int high, int zp,
+                                            float s) {
+  int m0 = 0, m1 = 0, mm2 = 0;
+  dot_plane_i4(nibbles_of(m3), x, m0, m1, mm2);
+  const int tm = (((mm2 << 4) + m1) << 4) + m0;
+  if (high) {
+    int l0 = 0, l1 = 0, ll2 = 0;
+    dot_plane_i4(nibbles_of(l3), x, l0, l1, ll2);
+    const int tl = (((ll2 << 4) + l1) << 4) + l0;
+    return (s * x.sx) * (float)(8 * tm + tl - __mul24(zp, x.xs));
+  }
+  return (8.0f * s * x.sx) * (float)(tm - __mul24(zp >> 3, x.xs));
+}
+
 __device__ __forceinline__ float dot_bytes(uint32_t e, uint32_t o, const float* x, float acc0, float& acc1) {
   acc0 = fmaf((float)(e & 0xFF), x[0], acc0);
   acc1 = fmaf((float)(o & 0xFF), x[1], acc1);
@@ -314,6 +345,25 @@ __device__ __forceinline__ float lane_value(const XR<SMOE_F32>& x, const uint4& 
 #pragma unroll
   for (int j = 0; j < 4; j++) a0 = dot_bytes(wm[j] & 0x0F0F0F0Fu, (wm[j] >> 4) & 0x0F0F0F0Fu, x.v + 8 * j, a0, a1);
   return (16.0f * s) * fmaf(-(float)(zp >> 4), x.xs, a0 + a1);
+}
+
+__device__ __forceinline__ float lane_value(const XR<SMOE_F32>& x, const uint3& m3, const uint3& l3, int high, int zp,
+                                            float s) {
+  const uint4 nm = nibbles_of(m3), nl = nibbles_of(l3);
+  const uint32_t wm[4] = {nm.x, nm.y, nm.z, nm.w}, wl[4] = {nl.x, nl.y, nl.z, nl.w};
+  float a0 = 0.0f, a1 = 0.0f;
+  if (high) {
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const uint32_t qe = ((wm[j] & 0x0F0F0F0Fu) << 3) | (wl[j] & 0x0F0F0F0Fu);              // codes of even columns
+      const uint32_t qo = (((wm[j] >> 4) & 0x0F0F0F0Fu) << 3) | ((wl[j] >> 4) & 0x0F0F0F0Fu);   // codes of odd columns
+      a0 = dot_bytes(qe, qo, x.v + 8 * j, a0, a1);
+    }
+    return s * fmaf(-(float)zp, x.xs, a0 + a1);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; j++) a0 = dot_bytes(wm[j] & 0x0F0F0F0Fu, (wm[j] >> 4) & 0x0F0F0F0Fu, x.v + 8 * j, a0, a1);
+  return (8.0f * s) * fmaf(-(float)(zp >> 3), x.xs, a0 + a1);
 }
 
 // ---------------------------------------------------------------------------------- LDS staging
@@ -1068,6 +1118,10 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   if (bits == 2) {
     if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1, 1>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_F32, 0, 1>(ctx, in, a, n_wg, T);
     return scb ? launch_decode_t<SMOE_BF16, 1, 1>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_BF16, 0, 1>(ctx, in, a, n_wg, T);
+  }
+  if (bits == 3) {
+    if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1, 2>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_F32, 0, 2>(ctx, in, a, n_wg, T);
+    return scb ? launch_decode_t<SMOE_BF16, 1, 2>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_BF16, 0, 2>(ctx, in, a, n_wg, T);
   }
   if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1, 0>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_F32, 0, 0>(ctx, in, a, n_wg, T);
   return scb ? launch_decode_t<SMOE_BF16, 1, 0>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_BF16, 0, 0>(ctx, in, a, n_wg, T);

@@ -18,6 +18,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
 struct __attribute__((packed)) U32x2Unaligned { uint32_t x, y; };
+struct __attribute__((packed, aligned(4))) U32x3Words { uint32_t x, y, z; };      // twelve bytes on a 4-byte boundary
 
 #define PF_BM 192          // token rows per work-group tile
 #define PF_BN 256          // weight rows per work-group tile
@@ -122,7 +123,7 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // One work-group of eight waves (two per SIMD) per CU: the tile is 192 token rows x 256 weight rows,
 // a wave owns 96 x 64 of it (3 x 2 MFMA fragments), and LDS holds two copies of the K slice so that
 // one barrier per K step is enough.
-template <int MODE, int SCB, int FMT>      // FMT 0: 8/4 nest, nibble planes; 1: 4/2 nest, 2-bit planes
+template <int MODE, int SCB, int FMT>      // FMT 0: 8/4 nest, nibble planes; 1: 4/2 nest, 2-bit planes; 2: 6/3 nest, 3-bit planes
 __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
   // (separate arrays, so that the compiler knows a write into one buffer cannot alias a read of the other)
   __shared__ __align__(16) uint16_t As0[PF_BM * PF_LDK], As1[PF_BM * PF_LDK];
@@ -182,8 +183,8 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
   const uint8_t* pl = a.w.lsb + (size_t)e * a.w.plane_stride;
   const uint8_t* ps = a.w.sc + (size_t)e * a.w.sc_stride;
   const uint8_t* pz = a.w.zp + (size_t)e * a.w.zp_stride;       // 4-byte aligned: zp_stride is a multiple of 4
-  constexpr int PSH = FMT ? 2 : 1;                      // columns per plane byte = 1 << PSH
-  const uint32_t poff = (uint32_t)grow * (uint32_t)(K >> PSH) + hb * (32 >> PSH);
+  constexpr int PB32 = FMT == 0 ? 16 : FMT == 1 ? 8 : 12;      // plane bytes of 32 columns
+  const uint32_t poff = (uint32_t)grow * (uint32_t)((K >> 5) * PB32) + hb * PB32;
   const uint32_t srow = (uint32_t)grow * (uint32_t)a.w.sng;
   const uint32_t zrow = (uint32_t)grow * (uint32_t)a.w.ng;
   const int b_dst = b * PF_LDK + hb * 32;
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
   // computed.  The registers hold what the loads return, untouched: arithmetic on them at this
   // point would make the wave wait for the loads.
   struct PreA { u32x4 ra[3]; };
-  typedef typename std::conditional<FMT != 0, u32x2, u32x4>::type PlaneV;      // a thread's 32 codes of one plane
+  typedef typename std::conditional<FMT == 1, u32x2, u32x4>::type PlaneV;      // a thread's 32 codes of one plane (FMT 2: three words used)
   struct Pre { PlaneV rm, rl; };
   // Scales and zero-points of eight consecutive groups of the thread's row (the chunk that holds the
   // groups of a K step), kept in registers and reloaded only when a step enters a new chunk: loading
@@ -219,8 +220,15 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
     for (int q = 0; q < 3; q++) *(u32x4*)(As + a_dst0 + q * 64 * PF_LDK) = p.ra[q];
   };
   auto gload = [&](int k0, Pre& p) __attribute__((always_inline)) {
-    p.rm = *(const PlaneV*)(pm + (poff + (uint32_t)(k0 >> PSH)));
-    p.rl = *(const PlaneV*)(pl + (poff + (uint32_t)(k0 >> PSH)));
+    const uint32_t o = poff + (uint32_t)((k0 >> 5) * PB32);
+    if constexpr (FMT == 2) {
+      const U32x3Words vm = *(const U32x3Words*)(pm + o), vl = *(const U32x3Words*)(pl + o);
+      p.rm = u32x4{vm.x, vm.y, vm.z, 0u};
+      p.rl = u32x4{vl.x, vl.y, vl.z, 0u};
+    } else {
+      p.rm = *(const PlaneV*)(pm + o);
+      p.rl = *(const PlaneV*)(pl + o);
+    }
   };
   auto lstore = [&](int k0, const Pre& p, const Meta& m, uint16_t* Bs) __attribute__((always_inline)) {
     const uint32_t g = (uint32_t)(k0 + 32 * hb) >> a.group_shift, gi = g & 7u;
@@ -239,11 +247,22 @@ __global__ __launch_bounds__(PF_NT) void grouped_gemm_kernel(GemmArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; j++) {
       uint32_t qe, qo;                          // codes of the even / odd columns of columns 8j .. 8j+7, one per byte
-      if (FMT == 0) {
+      if constexpr (FMT == 0) {
         // the planes hold n ^ 8 per nibble
         const uint32_t wm = p.rm[j], wl = p.rl[j];
         qe = (((wm & 0x0F0F0F0Fu) << 4) | (wl & 0x0F0F0F0Fu)) ^ 0x88888888u;
         qo = ((wm & 0xF0F0F0F0u) | ((wl >> 4) & 0x0F0F0F0Fu)) ^ 0x88888888u;
+      } else if constexpr (FMT == 2) {
+        // column 8j + i: two low bits in word j >> 1 at bits 4i + 2(j & 1), third bit in word 2 at bit
+        // 4i + j; one value per nibble first, then code = 8 msb + lsb, one per byte
+        auto nib = [&](const PlaneV& w) {
+          const uint32_t lo = (w[j >> 1] >> (2 * (j & 1))) & 0x33333333u;
+          const uint32_t hi = w[2] & (0x11111111u << j);
+          return lo | (j < 2 ? hi << (2 - j) : hi >> (j - 2));
+        };
+        const uint32_t nm = nib(p.rm), nl = nib(p.rl);
+        qe = ((nm & 0x0F0F0F0Fu) << 3) | (nl & 0x0F0F0F0Fu);
+        qo = (((nm >> 4) & 0x0F0F0F0Fu) << 3) | ((nl >> 4) & 0x0F0F0F0Fu);
       } else {
         // sixteen 2-bit codes per plane word, column c in bits 2c, 2c+1: spread half a word to one
         // code per nibble, then code = 4 msb + lsb
@@ -435,12 +454,15 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* o, const int3
 // ------------------------------------------------------------------------------- host entry
 static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// bits = plane bits per code of the bank (4: 8/4 nest, 2: 4/2 nest)
+// bits = plane bits per code of the bank (4: 8/4 nest, 3: 6/3 nest, 2: 4/2 nest)
 template <int MODE>
 static void launch_gemm(const GemmArgs& g, int bits, int grid, hipStream_t st) {
   if (bits == 2) {
     if (g.sc_bf16) grouped_gemm_kernel<MODE, 1, 1><<<grid, PF_NT, 0, st>>>(g);
     else grouped_gemm_kernel<MODE, 0, 1><<<grid, PF_NT, 0, st>>>(g);
+  } else if (bits == 3) {
+    if (g.sc_bf16) grouped_gemm_kernel<MODE, 1, 2><<<grid, PF_NT, 0, st>>>(g);
+    else grouped_gemm_kernel<MODE, 0, 2><<<grid, PF_NT, 0, st>>>(g);
   } else {
     if (g.sc_bf16) grouped_gemm_kernel<MODE, 1, 0><<<grid, PF_NT, 0, st>>>(g);
     else grouped_gemm_kernel<MODE, 0, 0><<<grid, PF_NT, 0, st>>>(g);

@@ -39,8 +39,8 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restri
   }
   const size_t sbase = src_row * (size_t)K;
   const size_t e = (size_t)(e0 + el);
-  const int bits = m.bits;                             // 4: 8-bit codes, nibble planes; 2: 4-bit codes, 2-bit planes
-  const float qmax = bits == 4 ? 255.0f : 15.0f;
+  const int bits = m.bits;                             // 4: 8-bit codes, nibble planes; 3: 6-bit codes; 2: 4-bit codes, 2-bit planes
+  const float qmax = bits == 4 ? 255.0f : bits == 3 ? 63.0f : 15.0f;
   uint8_t* pm = const_cast<uint8_t*>(m.msb) + e * m.plane_stride + (size_t)row * (K * bits / 8);
   uint8_t* pl = const_cast<uint8_t*>(m.lsb) + e * m.plane_stride + (size_t)row * (K * bits / 8);
   uint8_t* pz = const_cast<uint8_t*>(m.zp) + e * m.zp_stride + (size_t)row * ng;
@@ -62,7 +62,42 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restri
     if (sc_bf16) s = bf16_bits_to_f32(f32_to_bf16_bits(s));
     if (!(s > 0.0f)) s = 1.0f;
     const int zp = (int)fminf(fmaxf(rintf((-lo) / s), 0.0f), qmax);
-    if (bits == 2) {
+    if (bits == 3) {
+      // 6-bit codes: upper three bits = the low-bit code.  A plane keeps the 32 three-bit values of a
+      // chunk of 32 columns in 12 bytes, laid out so that a nibble word (one value per nibble, columns
+      // 8t .. 8t+7 in word t) comes out of it with a shift and a mask: column 8t + j has its two low
+      // bits in word t >> 1 at bits 4j + 2(t & 1), 4j + 2(t & 1) + 1 and its third bit in word 2 at
+      // bit 4j + t.  Eight lanes build a chunk: lane j of them takes the columns 8t + j.
+      const int nchunk = gsz >> 5, j = lane & 7;
+      for (int cb = 0; cb < nchunk; cb += 8) {
+        const int c = cb + (lane >> 3);
+        uint32_t wm[3] = {0, 0, 0}, wl[3] = {0, 0, 0};
+        if (c < nchunk) {
+#pragma unroll
+          for (int t = 0; t < 4; t++) {
+            const float a = load_w<WDT>(src, sbase + k0 + 32 * c + 8 * t + j);
+            const int q = min(max((int)rintf(a / s) + zp, 0), 63);
+            const uint32_t mv = (uint32_t)q >> 3, lv = (uint32_t)q & 7u;
+            wm[t >> 1] |= (mv & 3u) << (4 * j + 2 * (t & 1));
+            wl[t >> 1] |= (lv & 3u) << (4 * j + 2 * (t & 1));
+            wm[2] |= (mv >> 2) << (4 * j + t);
+            wl[2] |= (lv >> 2) << (4 * j + t);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 3; i++)
+          for (int x = 1; x < 8; x <<= 1) {
+            wm[i] |= (uint32_t)__shfl_xor((int)wm[i], x);
+            wl[i] |= (uint32_t)__shfl_xor((int)wl[i], x);
+          }
+        if (c < nchunk && j == 0) {
+          uint32_t* dm = (uint32_t*)(pm + (size_t)((k0 >> 5) + c) * 12);
+          uint32_t* dl = (uint32_t*)(pl + (size_t)((k0 >> 5) + c) * 12);
+#pragma unroll
+          for (int i = 0; i < 3; i++) { dm[i] = wm[i]; dl[i] = wl[i]; }
+        }
+      }
+    } else if (bits == 2) {
       // 4-bit codes: upper two bits = the low-bit code; four codes per plane byte, column 4j in bits 0-1
       for (int p = lane; p < (gsz >> 2); p += 64) {
         int bm = 0, bl = 0;

@@ -56,18 +56,22 @@ def test_quantize_slice_bit_exact(ctx, d, f, G, dt):
             assert np.array_equal(got["scale"].view(np.uint32), qm.scale.view(np.uint32))
 
 
+@pytest.mark.parametrize("nest", [(4, 2), (6, 3)])
 @pytest.mark.parametrize("d,f,G,dt", [(256, 160, 64, "bf16"), (96, 64, 32, "f32"), (2048, 1408, 32, "bf16")])
-def test_quantize_slice_4_2_nest_bit_exact(ctx, d, f, G, dt):
-    # the 4/2 nest: 4-bit codes whose upper two bits are the low-bit model, 2-bit planes
-    say("quantize 4/2", d, f, G, dt)
-    shape = synth.LayerShape(d, 2, f, 1, G, act=dt, b_high=4, b_low=2)
+def test_quantize_slice_lower_nests_bit_exact(ctx, d, f, G, dt, nest):
+    # the 4/2 nest: 4-bit codes whose upper two bits are the low-bit model, 2-bit planes;
+    # the 6/3 nest: 6-bit codes, upper three bits, 3-bit planes of twelve bytes per 32 columns
+    bh, bl = nest
+    say("quantize", nest, d, f, G, dt)
+    shape = synth.LayerShape(d, 2, f, 1, G, act=dt, b_high=bh, b_low=bl)
     pair = LayerPair(ctx, shape, seed=3)
-    assert pair.routed.nbytes < 0.6 * B.smoe_bank_bytes(B.BankDesc(2, d, f, G, 8, 4, B._DT[dt], B._DT[dt]))
+    full = B.smoe_bank_bytes(B.BankDesc(2, d, f, G, 8, 4, B._DT[dt], B._DT[dt]))
+    assert pair.routed.nbytes < (0.6 if bl == 2 else 0.85) * full
     for e in range(2):
         ex = pair.oracle_expert(e)
         for mi, qm in enumerate((ex.gate, ex.up, ex.down)):
             got = B.smoe_export_codes(ctx, pair.routed, e, mi)
-            assert int(got["q"].max()) <= 15
+            assert int(got["q"].max()) <= (1 << bh) - 1 and int(got["msb"].max()) <= (1 << bl) - 1
             assert np.array_equal(got["q"], qm.q)
             assert np.array_equal(got["msb"], qm.msb()) and np.array_equal(got["lsb"], qm.lsb())
             assert np.array_equal(got["zp"], qm.zp)
@@ -272,12 +276,15 @@ def test_multi_token_layer(ctx, T, dt):
                                        C.c_void_p(y.data_ptr()), None, None, None) == -1
 
 
+@pytest.mark.parametrize("nest", [(4, 2), (6, 3)])
 @pytest.mark.parametrize("dt,G", [("bf16", 128), ("bf16", 32), ("f32", 64)])
-def test_4_2_nest_layer(ctx, dt, G):
+def test_lower_nest_layer(ctx, dt, G, nest):
     # the 4/2 nest (4-bit codes, 2-bit planes): LOW = upper two bits with the zero-point shifted by
-    # two, HIGH = both planes; ragged chunk counts, a shared expert, masks of every kind
-    say("4/2 nest layer", dt, G)
-    shp = synth.LayerShape(512, 10, 416, 3, G, n_shared=1, shared_d_ff=224, act=dt, b_high=4, b_low=2)
+    # two, HIGH = both planes; the 6/3 nest likewise with three bits; ragged chunk counts, a shared
+    # expert, masks of every kind
+    bh, bl = nest
+    say("lower nest layer", nest, dt, G)
+    shp = synth.LayerShape(512, 10, 416, 3, G, n_shared=1, shared_d_ff=224, act=dt, b_high=bh, b_low=bl)
     wl = synth.Workload("mat42", shp, steps=5, seed=37)
     pair = LayerPair(ctx, shp, seed=wl.seed)
     x_all = synth.activations(wl.seed, wl.steps, shp.d_model, shp.act)
@@ -289,7 +296,7 @@ def test_4_2_nest_layer(ctx, dt, G):
         worst = _run_layer_steps(ctx, wl, pair, range(wl.steps), masks, None, logits, x_all, fused, add_residual=fused)
         say("  fused", fused, "worst max-abs-rel", worst)
     # HIGH and LOW differ, and a full-size layer shape runs too (one step, against the oracle)
-    shp2 = synth.LayerShape(2048, 8, 1408, 2, 128, n_shared=1, shared_d_ff=1408, act=dt, b_high=4, b_low=2)
+    shp2 = synth.LayerShape(2048, 8, 1408, 2, 128, n_shared=1, shared_d_ff=1408, act=dt, b_high=bh, b_low=bl)
     if dt == "bf16" and G == 128:
         wl2 = synth.Workload("mat42-full", shp2, steps=1, seed=38)
         pair2 = LayerPair(ctx, shp2, seed=wl2.seed)

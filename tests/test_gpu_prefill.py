@@ -90,12 +90,15 @@ def test_prefill_with_shared_experts(ctx, n_shared, f_s, gate):
     assert O.max_abs_rel(t2np(yd), t2np(y[t])) <= TOL
 
 
+@pytest.mark.parametrize("nest", [(4, 2), (6, 3)])
 @pytest.mark.parametrize("G,sdt", [(64, "bf16"), (32, "bf16")])
-def test_prefill_4_2_nest(ctx, G, sdt):
-    # the 4/2 nest (4-bit codes in 2-bit planes) through the prefill path, with a gated shared expert
+def test_prefill_lower_nests(ctx, G, sdt, nest):
+    # the 4/2 nest (4-bit codes in 2-bit planes) and the 6/3 nest (6-bit codes in 3-bit planes) through
+    # the prefill path, with a gated shared expert
     T, E, k, d, f = 230, 6, 2, 256, 192
-    say("prefill 4/2 nest", G)
-    shp = synth.LayerShape(d, E, f, k, G, n_shared=1, shared_d_ff=128, shared_gate=True, act=sdt, b_high=4, b_low=2)
+    say("prefill lower nest", nest, G)
+    shp = synth.LayerShape(d, E, f, k, G, n_shared=1, shared_d_ff=128, shared_gate=True, act=sdt, b_high=nest[0],
+                           b_low=nest[1])
     pair = LayerPair(ctx, shp, seed=41)
     x = synth.activations(41, T, d, "bf16").cuda()
     wr = synth.router_weight(41, 0, E, d, std=0.05).cuda()
