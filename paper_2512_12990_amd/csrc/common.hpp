@@ -44,6 +44,7 @@ struct smoe_ctx {
   // measurement aid (smoe_ctx_timing): events around the two decode launches of every call
   int timing;
   void* timing_events;   // std::vector<hipEvent_t>*, four events per decode call
+  size_t down_lds_granted[12];   // dynamic LDS already granted to each down_kernel instantiation on this device
 };
 
 struct smoe_bank {
@@ -93,10 +94,6 @@ template <int ACT> __device__ __forceinline__ float load_act(const void* p, size
 template <int ACT> __device__ __forceinline__ void store_act(void* p, size_t i, float v) {
   if (ACT == SMOE_F32) ((float*)p)[i] = v;
   else ((uint16_t*)p)[i] = (uint16_t)f32_to_bf16_bits(v);
-}
-
-__device__ __forceinline__ float load_scale(const uint8_t* sc, int sc_bf16, size_t i) {
-  return sc_bf16 ? bf16_bits_to_f32(((const uint16_t*)sc)[i]) : ((const float*)sc)[i];
 }
 
 template <int CTRL> __device__ __forceinline__ float dpp_f32(float v) {

@@ -32,10 +32,7 @@
 #define DEC_NT 1024                 // threads per work-group
 #define DEC_NW (DEC_NT / 64)
 #define DEC_MAXP 3                  // row pairs per batch and wave (gate/up kernel)
-#define DEC_MAXU 5                  // units per batch and wave (down kernel)
 #define DEC_RPW 8                   // output rows per work-group (down kernel)
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 // One expert matrix family as the kernels see it (56 bytes).
 struct MatK {
@@ -114,12 +111,6 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
-template <typename T> __device__ __forceinline__ const T* uni_ptr(const T* p) {
-  const unsigned long long v = (unsigned long long)p;
-  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)v);
-  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v >> 32));
-  return (const T*)(((unsigned long long)hi << 32) | lo);
-}
 
 template <int CTRL, int ROWM, int BANKM> __device__ __forceinline__ float dpp_add(float v) {
   return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROWM, BANKM, true));
@@ -193,20 +184,7 @@ __device__ __forceinline__ uint32_t bload8(__amdgpu_buffer_rsrc_t r, unsigned vo
   return __builtin_amdgcn_raw_buffer_load_b8(r, (int)voff, (int)soff, 0);
 }
 
-// Scale of element `elem + g` of an expert's scale block (block_off = its byte offset in the
-// section), fetched as the aligned dword that contains it; `odd` tells which half holds a 16-bit
-// scale.  live = false -> nothing is read and the scale is 0.
-template <int SCB>
-__device__ __forceinline__ uint32_t load_scale_raw(__amdgpu_buffer_rsrc_t sc, unsigned block_off, unsigned elem, int g,
-                                                   bool live, int& odd) {
-  if (SCB) {
-    const int t = (int)(elem & 1u) + g;
-    odd = t & 1;
-    return bload32(sc, live ? (unsigned)((t >> 1) << 2) : DEC_OOB, block_off + (elem >> 1) * 4u);
-  }
-  odd = 0;
-  return bload32(sc, live ? (unsigned)(g << 2) : DEC_OOB, block_off + elem * 4u);
-}
+// Value of a scale fetched as the aligned dword that contains it; `odd` tells which half holds a 16-bit scale.
 template <int SCB> __device__ __forceinline__ float scale_val(uint32_t raw, int odd) {
   return SCB ? __uint_as_float(odd ? (raw & 0xFFFF0000u) : (raw << 16)) : __uint_as_float(raw);
 }
@@ -1026,7 +1004,8 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
   const size_t lds = (size_t)DEC_NW * (StageTraits<ACT>::COMBO_BYTES + 64 * 8) + (size_t)n_combo * DEC_RPW * 4;
   if (lds > 160u * 1024u) return SMOE_ESIZE;
   if (lds > 64u * 1024u) {       // beyond the default per-work-group limit: ask for the larger carve-out
-    static size_t granted = 0;
+    // (kept per context, that is per device: the attribute belongs to the function on the current device)
+    size_t& granted = ctx->down_lds_granted[(ACT * 2 + SCB) * 3 + FMT];
     if (lds > granted) {
       if (hipFuncSetAttribute((const void*)down_kernel<ACT, SCB, FMT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
