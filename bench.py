@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=40)
-    ap.add_argument("--workload", choices=["decode", "prefill"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "prefill", "stack-qwen", "stack-dsv2"], default="decode",
                     help="decode (default, the headline metric) or the prefill grouped GEMM of one Qwen-shaped layer")
     ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64, 128],
                     help="decode: quantisation group of the expert weights (default: the workload's 128; 32 is the "
@@ -83,6 +83,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU fallback)"
     if args.workload == "prefill":
         return prefill_bench(args)
+    if args.workload in ("stack-qwen", "stack-dsv2"):
+        return stack_bench(args)
     global PLANE_BITS
     bh, bl = {"84": (8, 4), "63": (6, 3), "42": (4, 2)}[args.nest]
     PLANE_BITS = bl
@@ -319,6 +321,139 @@ def prefill_bench(args):
                      "frac": flops / (ms * 1e-3) / 1e12 / 2500.0, "flops_per_step": flops,
                      "weight_bytes_per_step": wbytes, "weight_gbps": wbytes / (ms * 1e-3) / 1e9, "traffic": None,
                      "kernel": "whole layer pass (route_batch, group, grouped_gemm<0>, grouped_gemm<1>, combine)"}}))
+
+
+def stack_bench(args):
+    """Whole decode steps of the multi-layer workloads (BASELINE configs[2] and configs[3]): a step sends
+    one token through every layer.  The MoE layers' outputs feed the next layer directly (add_residual);
+    the attention / normalisation blocks between MoE layers are outside the path and left out, so the
+    numbers are the MoE layers alone.  stack-dsv2 keeps its per-step host work inside the window: masks
+    and routing bias come from the slice LRU (25 % of the slices), which is fed the step's selections."""
+    import ctypes as C
+    import numpy as np
+    import torch
+    from paper_2512_12990_amd import binding as B, synth
+    qwen = args.workload == "stack-qwen"
+    wl = synth.QWEN_STACK if qwen else synth.DSV2_STACK
+    shp = wl.layer
+    dev = "cuda:0"
+    d, E, k = shp.d_model, shp.n_experts, shp.top_k
+    LM = wl.n_layers if qwen else wl.n_layers - 1
+    ctx = B.Ctx(0)
+
+    def bank(n, f, l, tag0):
+        b = B.Bank(ctx, n, d, f, shp.group, "bf16", "bf16")
+        for e in range(n):
+            wg, wu, wd = synth.expert_weights(wl.seed, l, tag0 + e, d, f, "bf16", dev)
+            B.smoe_quantize_slice(ctx, b, e, wg[None], wu[None], wd[None])
+        return b
+
+    routed = [bank(E, shp.d_ff, l, 0) for l in range(LM)]
+    shared = [bank(shp.n_shared, shp.shared_d_ff, l, 1000) for l in range(LM)]
+    dense = None if qwen else bank(1, wl.dense_first_d_ff, 2000, 1000)
+    steps = min(args.steps, wl.steps)
+    warm = min(args.warmup, 10)
+    n_in = steps + warm
+    x0 = synth.activations(wl.seed, n_in, d, "bf16").to(dev)
+    vp = lambda t: C.c_void_p(t.data_ptr())
+    xs = torch.empty((wl.n_layers + 1, d), dtype=torch.bfloat16, device=dev)       # layer inputs of the current step
+    idx_o = torch.zeros((LM, 16), dtype=torch.int32, device=dev)            # (rows padded to 64 bytes)
+    prec_o = torch.zeros((LM, 16), dtype=torch.uint8, device=dev)             # 16-byte rows keep every pointer aligned
+    lib = B.lib()
+    if qwen:
+        wr = [synth.router_weight(wl.seed, l, E, d).to(dev) for l in range(LM)]
+        wsg = [synth.shared_gate_weight(wl.seed, l, d, "bf16").to(dev) for l in range(LM)]
+        masks = torch.zeros((LM, E), dtype=torch.uint8, device=dev)
+        calls = [(ctx.h, routed[l].h, shared[l].h, vp(xs[l]), C.c_int(B.BF16), C.c_int(k), None, vp(wr[l]), None, C.c_int(0),
+                  C.c_float(1.0), vp(masks[l]), C.c_float(0.0), vp(wsg[l]), C.c_int(1), vp(xs[l + 1]), vp(idx_o[l]), None,
+                  vp(prec_o[l])) for l in range(LM)]
+    else:
+        z = [synth.zipf_logits(wl.seed, l + 1, n_in, E).to(dev) for l in range(LM)]
+        masks = torch.zeros((LM, E), dtype=torch.uint8, device=dev)
+        bias = torch.zeros((LM, E), dtype=torch.float32, device=dev)
+        cache = B.Cache(LM, E, (2 * LM * E) // 4)
+        dense_call = (ctx.h, None, dense.h, vp(xs[0]), C.c_int(B.BF16), C.c_int(0), None, None, None, C.c_float(0.0), None,
+                      C.c_int(1), vp(xs[1]), None)
+        host_masks = torch.zeros((LM, E), dtype=torch.uint8).pin_memory()
+        host_bias = torch.zeros((LM, E), dtype=torch.float32).pin_memory()
+        host_idx = torch.zeros((LM, 16), dtype=torch.int32).pin_memory()
+        want = np.ones((LM, k), np.uint8)
+        hm_np, hb_np, hi_np = host_masks.numpy(), host_bias.numpy(), host_idx.numpy()
+
+    def step(t):
+        xs[0].copy_(x0[t])
+        if qwen:
+            if t % 32 == 0:
+                masks.copy_(torch.from_numpy(synth.fraction_masks(wl.seed, LM, t // 32, E, 0.3)))
+            for l in range(LM):
+                rc = lib.smoe_decode_layer(*calls[l])
+                if rc:
+                    raise B.SmoeError("decode call failed: %d" % rc)
+        else:
+            cache.snapshot_all(1.0, hm_np, hb_np)      # straight into the pinned staging buffers
+            masks.copy_(host_masks, non_blocking=True)
+            bias.copy_(host_bias, non_blocking=True)
+            rc = lib.smoe_expert_ffn(*dense_call)
+            for l in range(LM):
+                rc = rc or lib.smoe_decode_layer(ctx.h, routed[l].h, shared[l].h, vp(xs[l + 1]), C.c_int(B.BF16), C.c_int(k),
+                                                 vp(z[l][t]), None, vp(bias[l]), C.c_int(0), C.c_float(1.0), vp(masks[l]),
+                                                 C.c_float(0.0), None, C.c_int(1), vp(xs[l + 2]), vp(idx_o[l]), None,
+                                                 vp(prec_o[l]))
+            if rc:
+                raise B.SmoeError("decode call failed: %d" % rc)
+            host_idx.copy_(idx_o)                       # synchronises: the LRU needs this step's selections
+            if t % 16 == 0:                             # HIGH slots of a sampled step: selected experts with both slices resident
+                high_sum[0] += int((hm_np[lrange, hi_np[:, :k]] == 3).sum())
+                high_sum[1] += 1
+            cache.access_all(hi_np, k, want)
+
+    high_sum = [0, 0]
+    lrange = np.arange(LM)[:, None]
+    for t in range(warm):
+        step(t)
+    torch.cuda.synchronize()
+    high_sum[0] = high_sum[1] = 0
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for t in range(warm, warm + steps):
+        step(t)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms = ev0.elapsed_time(ev1) / steps
+    assert bool(torch.isfinite(xs.float()).all())
+    # algorithmic bytes of the last step (the precision flags of its layers), as a sample of the mix
+    pr = prec_o.cpu().numpy()[:, :k]
+    hi_b = sum(slot_bytes(d, shp.d_ff, shp.group, 1)); lo_b = sum(slot_bytes(d, shp.d_ff, shp.group, 0))
+    sh_b = shp.n_shared * sum(slot_bytes(d, shp.shared_d_ff, shp.group, 1))
+    step_bytes = float(sum(sh_b + int(p.sum()) * hi_b + int(k - p.sum()) * lo_b for p in pr))
+    if not qwen:
+        step_bytes += sum(slot_bytes(d, wl.dense_first_d_ff, shp.group, 1))
+    out = {
+        "metric": "decode us/token per MoE layer over the whole %d-layer stack" % wl.n_layers,
+        "value": ms * 1e3 / wl.n_layers, "unit": "us/token-layer", "n_gpus": 1, "steps": steps, "warmup": warm,
+        "ms_per_step": ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u4+u4 bit-sliced weights, bf16 activations, signed 4-bit dot products, int32/fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": ("Qwen1.5-MoE-shaped 24-layer decode stack (BASELINE configs[2]): router mat-vec, one gated wide "
+                                "shared expert, masks redrawn every 32 steps" if qwen else
+                                "DeepSeek-V2-Lite-shaped 26-layer decode stack (BASELINE configs[3]): dense first layer, Zipf-skewed "
+                                "logits, masks and bias from the host slice LRU (25 % of the slices) inside the timed window"),
+                   "layers": wl.n_layers, "d_model": d, "n_experts": E, "d_ff": shp.d_ff, "top_k": k,
+                   "n_shared": shp.n_shared, "shared_d_ff": shp.shared_d_ff, "group": shp.group,
+                   "mean_high_slots_last_step": float(pr.sum() / LM),
+                   "mean_high_slots_sampled_steps": (high_sum[0] / (high_sum[1] * LM)) if high_sum[1] else None},
+        "us_per_step": ms * 1e3, "host_wall_ms_per_step": wall_ms / steps,
+        "bytes_last_step": step_bytes, "hbm_gbps": step_bytes / (ms * 1e-3) / 1e9,
+        "hbm_frac": step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "whole step (all layers: router mat-vec where used, gate/up, down)",
+                     "achieved": step_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None},
+    }
+    if not qwen:
+        out["lru_stats"] = cache.stats()
+    print(json.dumps(out))
 
 
 def cpu_baseline(wl, n_steps, idx_np, prec_np):

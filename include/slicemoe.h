@@ -194,6 +194,14 @@ int smoe_cache_snapshot(const smoe_cache* c, int layer, float beta, uint8_t* sli
  * next eviction victim.  A fetch into a full cache first evicts the least recent slice. */
 int smoe_cache_access(smoe_cache* c, int layer, int k, const int32_t* idx_host,
                       const uint8_t* want_high_host);
+/* The same for one token's pass through all L layers, in layer order: the snapshot fills
+ * slice_mask_host[L*E] (and bias_host[L*E] unless NULL); the access takes the selections of layer l
+ * at idx_host[l*idx_stride .. l*idx_stride + k) (idx_stride >= k, so rows padded for alignment can be
+ * passed as they are) and want_high_host[l*k .. ) (NULL = no LSB requests).  Either all layers are
+ * applied or, on an invalid index, none. */
+int smoe_cache_snapshot_all(const smoe_cache* c, float beta, uint8_t* slice_mask_host, float* bias_host);
+int smoe_cache_access_all(smoe_cache* c, int k, const int32_t* idx_host, int idx_stride,
+                          const uint8_t* want_high_host);
 int smoe_cache_stats_get(const smoe_cache* c, smoe_cache_stats* out);
 /* Copies the resident slice ids, most recent first; returns their number in *n_out. */
 int smoe_cache_order(const smoe_cache* c, uint32_t* slice_ids_host, int max_n, int* n_out);

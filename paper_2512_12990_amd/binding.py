@@ -51,7 +51,7 @@ EXPORTS = [
     "smoe_route", "smoe_expert_ffn", "smoe_decode_layer", "smoe_decode_layer_multi",
     "smoe_prefill_bytes", "smoe_prefill_histogram", "smoe_topn_slices",
     "smoe_cache_create", "smoe_cache_destroy", "smoe_cache_init_order", "smoe_cache_snapshot",
-    "smoe_cache_access", "smoe_cache_stats_get", "smoe_cache_order",
+    "smoe_cache_access", "smoe_cache_snapshot_all", "smoe_cache_access_all", "smoe_cache_stats_get", "smoe_cache_order",
     "smoe_system_spec_paper", "smoe_cost_model",
 ]
 
@@ -307,6 +307,27 @@ class Cache:
         wh = np.ascontiguousarray(want_high, dtype=np.uint8)
         _chk(lib().smoe_cache_access(self.h, C.c_int(layer), C.c_int(i.size), i.ctypes.data_as(C.c_void_p),
                                      wh.ctypes.data_as(C.c_void_p)), "smoe_cache_access")
+
+    def snapshot_all(self, beta: float, mask_out: np.ndarray, bias_out: Optional[np.ndarray] = None):
+        """Masks (uint8 [L, E]) and routing bias (float32 [L, E]) of all layers into the caller's arrays."""
+        assert mask_out.dtype == np.uint8 and mask_out.flags.c_contiguous and mask_out.size == self.L * self.E
+        bp = None
+        if bias_out is not None:
+            assert bias_out.dtype == np.float32 and bias_out.flags.c_contiguous and bias_out.size == self.L * self.E
+            bp = bias_out.ctypes.data_as(C.c_void_p)
+        _chk(lib().smoe_cache_snapshot_all(self.h, C.c_float(beta), mask_out.ctypes.data_as(C.c_void_p), bp),
+             "smoe_cache_snapshot_all")
+
+    def access_all(self, idx: np.ndarray, k: int, want_high: Optional[np.ndarray] = None):
+        """One token's selections in all layers: idx int32 [L, stride >= k] (C-contiguous), want_high uint8 [L, k]."""
+        assert idx.dtype == np.int32 and idx.flags.c_contiguous and idx.shape[0] == self.L and idx.shape[1] >= k
+        wp = None
+        if want_high is not None:
+            wh = np.ascontiguousarray(want_high, dtype=np.uint8)
+            assert wh.size == self.L * k
+            wp = wh.ctypes.data_as(C.c_void_p)
+        _chk(lib().smoe_cache_access_all(self.h, C.c_int(k), idx.ctypes.data_as(C.c_void_p), C.c_int(idx.shape[1]), wp),
+             "smoe_cache_access_all")
 
     def stats(self) -> dict:
         s = CacheStats()

@@ -97,6 +97,29 @@ extern "C" int smoe_cache_access(smoe_cache* c, int layer, int k, const int32_t*
   return SMOE_OK;
 }
 
+extern "C" int smoe_cache_snapshot_all(const smoe_cache* c, float beta, uint8_t* slice_mask_host, float* bias_host) {
+  if (!c || !slice_mask_host) return SMOE_EINVAL;
+  for (int l = 0; l < c->L; l++) {
+    const int rc = smoe_cache_snapshot(c, l, beta, slice_mask_host + (size_t)l * c->E, bias_host ? bias_host + (size_t)l * c->E : nullptr);
+    if (rc) return rc;
+  }
+  return SMOE_OK;
+}
+
+extern "C" int smoe_cache_access_all(smoe_cache* c, int k, const int32_t* idx_host, int idx_stride, const uint8_t* want_high_host) {
+  if (!c || !idx_host || k < 0 || idx_stride < k) return SMOE_EINVAL;
+  for (int l = 0; l < c->L; l++)                      // nothing is applied unless every index is valid
+    for (int j = 0; j < k; j++) {
+      const int32_t e = idx_host[(size_t)l * idx_stride + j];
+      if (e < 0 || e >= c->E) return SMOE_ESHAPE;
+    }
+  for (int l = 0; l < c->L; l++) {
+    const int rc = smoe_cache_access(c, l, k, idx_host + (size_t)l * idx_stride, want_high_host ? want_high_host + (size_t)l * k : nullptr);
+    if (rc) return rc;
+  }
+  return SMOE_OK;
+}
+
 extern "C" int smoe_cache_stats_get(const smoe_cache* c, smoe_cache_stats* out) {
   if (!c || !out) return SMOE_EINVAL;
   *out = c->st;

@@ -100,3 +100,35 @@ def test_product_path_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".cpp", ".h")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src.replace("the CPU oracle's tests", ""), f
+
+
+def test_cache_all_layer_calls_match_per_layer_calls():
+    """smoe_cache_snapshot_all / smoe_cache_access_all = the per-layer calls in layer order (and the oracle's LRU)."""
+    rng = np.random.default_rng(3)
+    L, E, cap, k = 5, 12, 30, 3
+    a, b, o = B.Cache(L, E, cap), B.Cache(L, E, cap), O.SliceLRU(L, E, cap)
+    masks, bias = np.empty((L, E), np.uint8), np.empty((L, E), np.float32)
+    for t in range(60):
+        idx = np.zeros((L, 16), np.int32)                         # padded rows, as a device buffer would have
+        for l in range(L):
+            idx[l, :k] = rng.choice(E, size=k, replace=False)
+        want = (rng.random((L, k)) < 0.6).astype(np.uint8)
+        a.snapshot_all(0.75, masks, bias)
+        for l in range(L):
+            m, bb = b.snapshot(l, 0.75)
+            om, ob = o.snapshot(l, 0.75)
+            assert np.array_equal(masks[l], m) and np.array_equal(bias[l], bb)
+            assert np.array_equal(m, om) and np.array_equal(bb, ob)
+        a.access_all(idx, k, want)
+        for l in range(L):
+            b.access(l, idx[l, :k], want[l])
+            o.access(l, idx[l, :k], want[l])
+        assert a.order() == b.order() == o.order and a.stats() == b.stats() == o.stats
+    # an invalid index anywhere leaves the cache untouched
+    bad = np.zeros((L, 16), np.int32)
+    bad[L - 1, 1] = E
+    before = a.order()
+    with pytest.raises(B.SmoeError):
+        a.access_all(bad, k, None)
+    assert a.order() == before
+
