@@ -2,7 +2,8 @@
 // slices of an expert are resident, MSB-only otherwise; Section 4.2: the MSB nibble with the
 // truncated zero-point IS the low-bit model; Section 2.1: cache-aware top-k in the prologue).
 //
-// Two launches per token-layer, both HBM-streaming kernels of 1024-thread work-groups:
+// Two launches per token-layer, both HBM-streaming kernels of 512-thread (8-wave) work-groups, two of
+// which share a CU:
 //   gateup  h = silu(Wg x) * (Wu x) for every slot.  Work-group b takes the row pairs
 //           r = b' + n_wg*q of EVERY slot (b' rotated per slot), so all work-groups move the same
 //           bytes whatever the precision mix, and nothing about the split depends on routing:
@@ -29,7 +30,7 @@
 #include <hip/hip_ext.h>
 #include <vector>
 
-#define DEC_NT 1024                 // threads per work-group
+#define DEC_NT 512                  // threads per work-group
 #define DEC_NW (DEC_NT / 64)
 #define DEC_MAXP 3                  // row pairs per batch and wave (gate/up kernel)
 #define DEC_RPW 8                   // output rows per work-group (down kernel)
@@ -631,7 +632,7 @@ __device__ __forceinline__ float route_weights(const RouteIn& in, const DecodeAr
 // ---------------------------------------------------------------------------------- gate/up kernel
 // Work-group b < n_wg takes the row pairs r = b' + n_wg*q (q < cap) of every slot, b' = (b +
 // slot*rot) mod n_wg, so all work-groups move the same bytes whatever the precision mix.  These
-// (slot, q) entries, shared experts first, are dealt to the 16 waves in runs of L; a run is worked
+// (slot, q) entries, shared experts first, are dealt to the 8 waves in runs of L; a run is worked
 // through as pieces = its entries of one slot, so expert, precision and base addresses are set up
 // once per piece and the rows of a piece differ by constant offsets.  Entries of shared experts
 // have their loads in flight before the routing decision exists; the last wave routes (selection
@@ -845,8 +846,8 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
 // ---------------------------------------------------------------------------------- down kernel
 // A work-group owns DEC_RPW = 8 output rows.  Its work is cut into pieces = (combo, part): a combo
 // is one (slot, 64-chunk k-slice) pair -- shared experts first, then the routed slots -- and a
-// combo's 8 rows are split into P parts of 8/P rows (P = the largest power of two that gives the 16
-// waves at most one piece each; the host picks it).  Wave w takes pieces w, w+16, ...  Everything a
+// combo's 8 rows are split into P parts of 8/P rows (P = the largest power of two that gives the 8
+// waves at most one piece each; the host picks it).  Wave w takes pieces w, w+8, ...  Everything a
 // piece needs beyond its rows -- expert, precision, weight, the h chunk in digit form -- belongs to
 // its combo, so a wave works it out once, and no wave depends on another before the final sum:
 // every wave puts the h chunks of its own combo into a private LDS area (the digit transposition
@@ -873,7 +874,7 @@ template <int ACT, int SCB, int FMT>
 __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const float* h, int n_combo_s, int n_pieces, int psh, int f_s,
                                                       int f_r, int ks_s, int ks_r, int inv_ks_s, int inv_ks_r, int nsf,
                                                       DecodeArgs a) {
-  extern __shared__ __align__(16) uint8_t dyn[];     // [16 waves: h digits of one combo, chunk figures][partials][gamma]
+  extern __shared__ __align__(16) uint8_t dyn[];     // [per wave: h digits of one combo, chunk figures][partials]
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   constexpr int XB = StageTraits<ACT>::COMBO_BYTES, WS = XB + 64 * 8;
   constexpr int DEC_RB = ACT == SMOE_BF16 ? 4 : 2;      // rows per batch (the fp32 path keeps 32 activations per lane in registers)
@@ -1077,7 +1078,11 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   a.d_model = d_model;
   // gate/up split: n_wg work-groups, each takes ceil(f / n_wg) row pairs of every slot
   int n_wg = (total_f + DEC_NW - 1) / DEC_NW;              // at least one row pair per wave
-  n_wg = n_wg < 1 ? 1 : (n_wg > ctx->n_cu ? ctx->n_cu : n_wg);
+  // Two 8-wave work-groups fit a CU: one token gets two per CU (measured best: 15.0 us per step against
+  // 15.9 with one 16-wave work-group per CU and 16.3 - 17.5 with three, five, six or eight halves);
+  // several tokens get one per CU each, and the work-groups of different tokens share the CUs.
+  const int wg_cap = (T == 1 ? 2 : 1) * ctx->n_cu;
+  n_wg = n_wg < 1 ? 1 : (n_wg > wg_cap ? wg_cap : n_wg);
   if (T > 1) n_wg = n_wg < 8 ? 8 : (n_wg & ~7);            // the multi-token grid is (8, T, n_wg / 8)
   a.cap_r = a.f_r ? (a.f_r + n_wg - 1) / n_wg : 1;
   a.cap_s = a.f_s ? (a.f_s + n_wg - 1) / n_wg : 1;
