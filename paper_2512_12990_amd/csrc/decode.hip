@@ -1088,7 +1088,9 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   a.cap_s = a.f_s ? (a.f_s + n_wg - 1) / n_wg : 1;
   a.inv_cap_r = (65536 + a.cap_r - 1) / a.cap_r;
   a.inv_cap_s = (65536 + a.cap_s - 1) / a.cap_s;
-  a.rot = n_wg / (k + ns);
+  // (several tokens: no rotation, so that tokens which hold an expert in different slots still read the
+  // same rows of it in the same work-group index, i.e. on the same XCD, and share them in its L2)
+  a.rot = T > 1 ? 0 : n_wg / (k + ns);
   if (ns * a.cap_s >= 8192 || k * a.cap_r >= 8192) return SMOE_ESIZE;
   a.gu_L = (ns * a.cap_s + k * a.cap_r + DEC_NW - 1) / DEC_NW;
   // down split
