@@ -46,45 +46,78 @@ __global__ __launch_bounds__(GR_THREADS) void group_kernel(const int32_t* idx, i
   __syncthreads();
   const int c = (n + GR_THREADS - 1) / GR_THREADS;          // every thread owns a contiguous run of c pairs
   const int i0 = min(n, tid * c), i1 = min(n, i0 + c);
+  // a run of up to GR_RUN pairs is fetched into registers before the first is used (all loads in
+  // flight at once) and serves both passes; longer runs are read pair by pair
+  constexpr int GR_RUN = 8;
+  int v8[GR_RUN];
+  const bool in_regs = c <= GR_RUN;
+  if (in_regs) {
+#pragma unroll
+    for (int u = 0; u < GR_RUN; u++) v8[u] = i0 + u < i1 ? idx[i0 + u] : -1;
+  }
   int mine = 0;
-  for (int i = i0; i < i1; i++) {
-    const int v = idx[i];
-    if ((unsigned)v < (unsigned)E) atomicAdd(&cnt[v], 1);
-    mine += v == e;
+  if (in_regs) {
+#pragma unroll
+    for (int u = 0; u < GR_RUN; u++) {
+      if ((unsigned)v8[u] < (unsigned)E) atomicAdd(&cnt[v8[u]], 1);
+      mine += v8[u] == e;
+    }
+  } else {
+    for (int i = i0; i < i1; i++) {
+      const int v = idx[i];
+      if ((unsigned)v < (unsigned)E) atomicAdd(&cnt[v], 1);
+      mine += v == e;
+    }
   }
   int incl = mine;
   for (int s = 1; s < 64; s <<= 1) { const int o = __shfl_up(incl, s); if (lane >= s) incl += o; }
   if (lane == 63) wtot[wave] = incl;
   __syncthreads();
+  // Wave 0 turns the counts into what the work-group needs (lane x takes experts x, x + 64, ...): rows
+  // and tiles of the experts before e, all full tiles, and the ragged tiles that precede e's ragged one
+  // (more rows first; equal sizes by expert).
+  __shared__ int summary[4];      // rows before e, full tiles before e, full tiles in all, ragged tiles before e's
+  const int ne = cnt[e];
+  const int rem = ne % PF_BM;
+  if (wave == 0) {
+    int s_off = 0, s_fb = 0, s_fa = 0, s_rb = 0, s_ra = 0;
+    for (int x = lane; x < E; x += 64) {
+      const int cx = cnt[x], fx = cx / PF_BM, rx = cx - fx * PF_BM;
+      s_fa += fx;
+      s_ra += rx > 0;
+      if (x < e) { s_off += cx; s_fb += fx; }
+      s_rb += rx > rem || (rx == rem && x < e);
+    }
+    for (int m = 32; m >= 1; m >>= 1) {
+      s_off += __shfl_xor(s_off, m); s_fb += __shfl_xor(s_fb, m); s_fa += __shfl_xor(s_fa, m);
+      s_rb += __shfl_xor(s_rb, m); s_ra += __shfl_xor(s_ra, m);
+    }
+    if (lane == 0) { summary[0] = s_off; summary[1] = s_fb; summary[2] = s_fa; summary[3] = s_rb; }
+    if (lane == 0 && e == E - 1) { offsets[E] = s_off + ne; tiles[0] = s_fa + s_ra; }
+  }
+  __syncthreads();
   int p = incl - mine;
   for (int w = 0; w < wave; w++) p += wtot[w];
-  int off = 0, nt = 0;
-  for (int j = 0; j < e; j++) { off += cnt[j]; nt += (cnt[j] + PF_BM - 1) / PF_BM; }
+  const int off = summary[0];
   p += off;
-  for (int i = i0; i < i1; i++)
-    if (idx[i] == e) { rows[p] = i; pos[i] = p; p++; }
-  const int ne = cnt[e];
+  if (in_regs) {
+#pragma unroll
+    for (int u = 0; u < GR_RUN; u++)
+      if (v8[u] == e) { rows[p] = i0 + u; pos[i0 + u] = p; p++; }
+  } else {
+    for (int i = i0; i < i1; i++)
+      if (idx[i] == e) { rows[p] = i; pos[i] = p; p++; }
+  }
   if (tid == 0) {
     hist[e] = (uint32_t)ne;
     offsets[e] = off;
-    if (e == E - 1) { offsets[E] = off + ne; tiles[0] = nt + (ne + PF_BM - 1) / PF_BM; }
   }
   // Position of each of this expert's tiles in the list = number of tiles that precede it: every
   // full tile precedes a ragged one; full tiles among themselves and ragged tiles of equal size go
   // by expert (an expert has at most one ragged tile, its last).
-  const int n_full = ne / PF_BM, rem = ne - n_full * PF_BM;
+  const int n_full = ne / PF_BM;
   for (int j = tid; j < n_full + (rem > 0); j += GR_THREADS) {
-    int rank;
-    if (j < n_full) {
-      rank = j;
-      for (int x = 0; x < e; x++) rank += cnt[x] / PF_BM;
-    } else {
-      rank = 0;
-      for (int x = 0; x < E; x++) {
-        const int fx = cnt[x] / PF_BM, rx = cnt[x] - fx * PF_BM;
-        rank += fx + (rx > rem || (rx == rem && x < e));
-      }
-    }
+    const int rank = j < n_full ? summary[1] + j : summary[2] + summary[3];
     int4 rec;
     rec.x = e; rec.y = j * PF_BM; rec.z = off + j * PF_BM; rec.w = min(PF_BM, ne - j * PF_BM);
     *(int4*)(tiles + 4 + 4 * rank) = rec;
