@@ -44,7 +44,7 @@ struct smoe_ctx {
   // measurement aid (smoe_ctx_timing): events around the two decode launches of every call
   int timing;
   void* timing_events;   // std::vector<hipEvent_t>*, four events per decode call
-  size_t down_lds_granted[12];   // dynamic LDS already granted to each down_kernel instantiation on this device
+  size_t down_lds_granted[48];   // dynamic LDS already granted to each down_kernel instantiation on this device
 };
 
 struct smoe_bank {

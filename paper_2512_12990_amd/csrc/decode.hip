@@ -870,7 +870,7 @@ __device__ __forceinline__ float wave_sum4_to_last(float v0, float v1, float v2,
 
 #define DEC_HQ 4      // h words of 8 values per lane that cover one combo (64 chunks)
 
-template <int ACT, int SCB, int FMT>
+template <int ACT, int SCB, int FMT, int RPW>      // RPW output rows per work-group
 __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const float* h, int n_combo_s, int n_pieces, int psh, int f_s,
                                                       int f_r, int ks_s, int ks_r, int inv_ks_s, int inv_ks_r, int nsf,
                                                       DecodeArgs a) {
@@ -882,7 +882,7 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
   float2* xcs = (float2*)(xbuf + XB);
   float* part = (float*)(dyn + DEC_NW * WS);         // [combo][row]
   const int tok = blockIdx.y;                          // see gateup_kernel
-  const int n0 = ((int)blockIdx.x + 8 * (int)blockIdx.z) * DEC_RPW;
+  const int n0 = ((int)blockIdx.x + 8 * (int)blockIdx.z) * RPW;
   if (tok) {
     rec += tok * (int)(sizeof(RouteRec) / 4);
     h += (size_t)tok * DEC_H_STRIDE(nsf, f_r);
@@ -891,7 +891,7 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
 
   for (int p = wave; p < n_pieces; p += DEC_NW) {
     // ---- which piece (leading parameters only)
-    const int combo = p >> psh, row0 = (p & ((1 << psh) - 1)) * (DEC_RPW >> psh), n_rows = DEC_RPW >> psh;
+    const int combo = p >> psh, row0 = (p & ((1 << psh) - 1)) * (RPW >> psh), n_rows = RPW >> psh;
     const bool is_sh = combo < n_combo_s;
     const int c2 = is_sh ? combo : combo - n_combo_s;
     const int ksn = is_sh ? ks_s : ks_r, inv_ks = is_sh ? inv_ks_s : inv_ks_r, f = is_sh ? f_s : f_r;
@@ -973,15 +973,15 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
 #pragma unroll
       for (int r = 0; r < DEC_RB; r++) v[r] = lane_value(x, wm[r], wl[r], prec, (int)zz[r], scale_val<SCB>(ss[r], odd));
       const float tot = wave_sum4_to_last(v[0], v[1], v[2], v[3], lane);
-      if (lane >= 60 && lane - 60 < nr) part[combo * DEC_RPW + row0 + b0 + lane - 60] = wt * tot;
+      if (lane >= 60 && lane - 60 < nr) part[combo * RPW + row0 + b0 + lane - 60] = wt * tot;
     }
   }
   __syncthreads();
-  if (tid < DEC_RPW) {
+  if (tid < RPW) {
     const int n_combo = n_pieces >> psh;
     float acc = 0.0f;
-    for (int c = n_combo_s; c < n_combo; c++) acc += part[c * DEC_RPW + tid];      // routed slots in slot order
-    for (int c = 0; c < n_combo_s; c++) acc += part[c * DEC_RPW + tid];            // then the shared experts
+    for (int c = n_combo_s; c < n_combo; c++) acc += part[c * RPW + tid];      // routed slots in slot order
+    for (int c = 0; c < n_combo_s; c++) acc += part[c * RPW + tid];            // then the shared experts
     const size_t n = (size_t)tok * a.d_model + n0 + tid;
     if (a.add_residual) acc += load_act<ACT>(a.x, n);
     store_act<ACT>(a.y, n, acc);
@@ -995,20 +995,20 @@ static int ilog2_exact(int v) {
   return (1 << s) == v ? s : -1;
 }
 
-template <int ACT, int SCB, int FMT>
+template <int ACT, int SCB, int FMT, int RPW>
 static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int n_wg, int T) {
   // down kernel: pieces = combos x parts
   const int n_combo_s = a.n_shared * a.ks_s, n_combo = n_combo_s + a.k * a.ks_r;
-  int psh = 3;
+  int psh = RPW == 64 ? 6 : RPW == 32 ? 5 : RPW == 16 ? 4 : 3;      // at most RPW parts of one row each
   while (psh > 0 && (n_combo << psh) > DEC_NW) psh--;
   const int n_pieces = n_combo << psh;
-  const size_t lds = (size_t)DEC_NW * (StageTraits<ACT>::COMBO_BYTES + 64 * 8) + (size_t)n_combo * DEC_RPW * 4;
+  const size_t lds = (size_t)DEC_NW * (StageTraits<ACT>::COMBO_BYTES + 64 * 8) + (size_t)n_combo * RPW * 4;
   if (lds > 160u * 1024u) return SMOE_ESIZE;
   if (lds > 64u * 1024u) {       // beyond the default per-work-group limit: ask for the larger carve-out
     // (kept per context, that is per device: the attribute belongs to the function on the current device)
-    size_t& granted = ctx->down_lds_granted[(ACT * 2 + SCB) * 3 + FMT];
+    size_t& granted = ctx->down_lds_granted[((ACT * 2 + SCB) * 3 + FMT) * 4 + (RPW == 16) + 2 * (RPW == 32) + 3 * (RPW == 64)];
     if (lds > granted) {
-      if (hipFuncSetAttribute((const void*)down_kernel<ACT, SCB, FMT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+      if (hipFuncSetAttribute((const void*)down_kernel<ACT, SCB, FMT, RPW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
         return SMOE_ESIZE;
       }
@@ -1016,7 +1016,7 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
     }
   }
   std::vector<hipEvent_t>* evs = (ctx->timing && ctx->timing_events) ? (std::vector<hipEvent_t>*)ctx->timing_events : nullptr;
-  const int n_dn = a.d_model / DEC_RPW;
+  const int n_dn = a.d_model / RPW;
   if (T > 1 && ((n_wg & 7) || (n_dn & 7))) return SMOE_ESHAPE;      // the multi-token grid is (8, T, n / 8)
   const dim3 g1 = T > 1 ? dim3(8, T, n_wg / 8) : dim3(n_wg), g2 = T > 1 ? dim3(8, T, n_dn / 8) : dim3(n_dn), blk(DEC_NT);
   const int n_se = a.n_shared * a.cap_s;
@@ -1028,12 +1028,12 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
     for (int i = 0; i < 4; i++) { HIPCHK(ctx, hipEventCreate(&ev[i])); evs->push_back(ev[i]); }
     hipExtLaunchKernelGGL((gateup_kernel<ACT, SCB, FMT>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
                           in.E, in.k, in.do_route, a.d_model, n_wg, n_se, a);
-    hipExtLaunchKernelGGL((down_kernel<ACT, SCB, FMT>), g2, blk, (unsigned)lds, ctx->stream, ev[2], ev[3], 0, recw, (const float*)a.h,
+    hipExtLaunchKernelGGL((down_kernel<ACT, SCB, FMT, RPW>), g2, blk, (unsigned)lds, ctx->stream, ev[2], ev[3], 0, recw, (const float*)a.h,
                           n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s, a.ks_r, a.inv_ks_s, a.inv_ks_r, nsf, a);
   } else {
     gateup_kernel<ACT, SCB, FMT><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, n_wg, n_se,
                                                          a);
-    down_kernel<ACT, SCB, FMT><<<g2, blk, lds, ctx->stream>>>(recw, (const float*)a.h, n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s,
+    down_kernel<ACT, SCB, FMT, RPW><<<g2, blk, lds, ctx->stream>>>(recw, (const float*)a.h, n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s,
                                                          a.ks_r, a.inv_ks_s, a.inv_ks_r, nsf, a);
   }
   HIPCHK(ctx, hipGetLastError());
@@ -1080,8 +1080,12 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   int n_wg = (total_f + DEC_NW - 1) / DEC_NW;              // at least one row pair per wave
   // Two 8-wave work-groups fit a CU: one token gets two per CU (measured best: 15.0 us per step against
   // 15.9 with one 16-wave work-group per CU and 16.3 - 17.5 with three, five, six or eight halves);
-  // several tokens get one per CU each, and the work-groups of different tokens share the CUs.
-  const int wg_cap = (T == 1 ? 2 : 1) * ctx->n_cu;
+  // several tokens share them, and the work-groups of different tokens run side by side on a CU.
+  int wg_cap = 2 * ctx->n_cu;
+  if (T > 1) {      // about two per CU over all tokens (measured at 2 .. 16 tokens: better than four or eight per CU)
+    wg_cap = ctx->n_cu;
+    while (wg_cap > 8 && wg_cap * T > 2 * ctx->n_cu) wg_cap >>= 1;
+  }
   n_wg = n_wg < 1 ? 1 : (n_wg > wg_cap ? wg_cap : n_wg);
   if (T > 1) n_wg = n_wg < 8 ? 8 : (n_wg & ~7);            // the multi-token grid is (8, T, n_wg / 8)
   a.cap_r = a.f_r ? (a.f_r + n_wg - 1) / n_wg : 1;
@@ -1101,17 +1105,24 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   const int scb = routed ? routed->dev.sc_bf16 : shared->dev.sc_bf16;
   if (routed && shared && routed->dev.sc_bf16 != shared->dev.sc_bf16) return SMOE_ENOTIMPL;   // one scale dtype per layer
   const int bits = routed ? routed->dev.bits : shared->dev.bits;
+  // Several tokens per launch: a down work-group owns 8 * 2^n output rows, so that again about two
+  // work-groups per CU cover all tokens (8 rows up to 2 tokens, 16 up to 4, 32 up to 8, 64 beyond): with
+  // more, smaller work-groups each one pays its own start-up and rewrites h as digits for fewer rows.
+  const bool rows16 = T >= 3 && d_model % 128 == 0, rows32 = T >= 6 && d_model % 256 == 0, rows64 = T >= 12 && d_model % 512 == 0;
+#define DEC_LAUNCH(A, S, F) (rows64 ? launch_decode_t<A, S, F, 64>(ctx, in, a, n_wg, T) : rows32 ? launch_decode_t<A, S, F, 32>(ctx, in, a, n_wg, T) : rows16 ? launch_decode_t<A, S, F, 16>(ctx, in, a, n_wg, T) : launch_decode_t<A, S, F, DEC_RPW>(ctx, in, a, n_wg, T))
   if (bits == 2) {
-    if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1, 1>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_F32, 0, 1>(ctx, in, a, n_wg, T);
-    return scb ? launch_decode_t<SMOE_BF16, 1, 1>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_BF16, 0, 1>(ctx, in, a, n_wg, T);
+    if (act_dtype == SMOE_F32) return scb ? DEC_LAUNCH(SMOE_F32, 1, 1) : DEC_LAUNCH(SMOE_F32, 0, 1);
+    return scb ? DEC_LAUNCH(SMOE_BF16, 1, 1) : DEC_LAUNCH(SMOE_BF16, 0, 1);
   }
   if (bits == 3) {
-    if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1, 2>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_F32, 0, 2>(ctx, in, a, n_wg, T);
-    return scb ? launch_decode_t<SMOE_BF16, 1, 2>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_BF16, 0, 2>(ctx, in, a, n_wg, T);
+    if (act_dtype == SMOE_F32) return scb ? DEC_LAUNCH(SMOE_F32, 1, 2) : DEC_LAUNCH(SMOE_F32, 0, 2);
+    return scb ? DEC_LAUNCH(SMOE_BF16, 1, 2) : DEC_LAUNCH(SMOE_BF16, 0, 2);
   }
-  if (act_dtype == SMOE_F32) return scb ? launch_decode_t<SMOE_F32, 1, 0>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_F32, 0, 0>(ctx, in, a, n_wg, T);
-  return scb ? launch_decode_t<SMOE_BF16, 1, 0>(ctx, in, a, n_wg, T) : launch_decode_t<SMOE_BF16, 0, 0>(ctx, in, a, n_wg, T);
+  if (act_dtype == SMOE_F32) return scb ? DEC_LAUNCH(SMOE_F32, 1, 0) : DEC_LAUNCH(SMOE_F32, 0, 0);
+  return scb ? DEC_LAUNCH(SMOE_BF16, 1, 0) : DEC_LAUNCH(SMOE_BF16, 0, 0);
 }
+
+#undef DEC_LAUNCH
 
 extern "C" int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
                                int act_dtype, int k, const int32_t* idx_dev, const float* w_dev,
