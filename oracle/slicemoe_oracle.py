@@ -114,8 +114,25 @@ class QMat:
         return (s * float(1 << self.shift)) * (code - self._expand(self.zp_low().astype(np.int64)))
 
 
-def _quant_groups(Wg: np.ndarray, qmax: int, scale_dtype: str):
+def _quant_groups_symmetric(Wg: np.ndarray, qmax: int, scale_dtype: str):
+    """Symmetric variant (Section 5 set-up: the non-expert weights are symmetric INT8): the
+    signed code c = rint(w / s) with s = max|w| / (2^(b-1) - 1), kept in the same unsigned
+    store as c + 2^(b-1), i.e. with the zero-point fixed at mid-range."""
+    Wg = Wg.astype(np.float32)
+    half = (qmax + 1) // 2
+    amax = np.abs(Wg).max(axis=2).astype(np.float32)
+    s = _round_scale((amax / F32(half - 1)).astype(np.float32), scale_dtype)
+    s = np.where(s > F32(0.0), s, F32(1.0)).astype(np.float32)
+    r = np.rint(Wg / s[:, :, None]).astype(np.float32)
+    q = np.clip(r.astype(np.int64) + half, 0, qmax)
+    zp = np.full(s.shape, half, dtype=np.uint8)
+    return q.astype(np.uint8), zp, s
+
+
+def _quant_groups(Wg: np.ndarray, qmax: int, scale_dtype: str, symmetric: bool = False):
     """Quantise W[N, g, Gsz]: every [n, j, :] is one group.  fp32 throughout."""
+    if symmetric:
+        return _quant_groups_symmetric(Wg, qmax, scale_dtype)
     Wg = Wg.astype(np.float32)
     lo = np.minimum(Wg.min(axis=2), F32(0.0)).astype(np.float32)
     hi = np.maximum(Wg.max(axis=2), F32(0.0)).astype(np.float32)
@@ -128,7 +145,8 @@ def _quant_groups(Wg: np.ndarray, qmax: int, scale_dtype: str):
     return q.astype(np.uint8), zp.astype(np.uint8), s
 
 
-def quantize(W, group: int, b_high: int = 8, b_low: int = 4, scale_dtype: str = "f32") -> QMat:
+def quantize(W, group: int, b_high: int = 8, b_low: int = 4, scale_dtype: str = "f32",
+             symmetric: bool = False) -> QMat:
     """Group-wise asymmetric min-max quantisation of W[N, K] to b_high-bit codes.
 
     The paper names the format (Table 1 note 1; Section 4.2 needs an integer
@@ -137,6 +155,8 @@ def quantize(W, group: int, b_high: int = 8, b_low: int = 4, scale_dtype: str = 
     fp32, then rounded to the storage dtype and used in that rounded form;
     zp = clamp(rint(-lo / s)); q = clamp(rint(w / s) + zp).  A last group
     shorter than `group` (K not a multiple) has its own range.
+    symmetric=True selects the mid-range zero-point variant instead (see
+    _quant_groups_symmetric); slicing and both dequantisation rules are unchanged.
     """
     W = np.asarray(W, dtype=np.float32)
     N, K = W.shape
@@ -146,10 +166,10 @@ def quantize(W, group: int, b_high: int = 8, b_low: int = 4, scale_dtype: str = 
     nfull = K // group
     qs, zps, ss = [], [], []
     if nfull:
-        q, zp, s = _quant_groups(W[:, : nfull * group].reshape(N, nfull, group), qmax, scale_dtype)
+        q, zp, s = _quant_groups(W[:, : nfull * group].reshape(N, nfull, group), qmax, scale_dtype, symmetric)
         qs.append(q.reshape(N, nfull * group)); zps.append(zp); ss.append(s)
     if K % group:
-        q, zp, s = _quant_groups(W[:, nfull * group:].reshape(N, 1, K - nfull * group), qmax, scale_dtype)
+        q, zp, s = _quant_groups(W[:, nfull * group:].reshape(N, 1, K - nfull * group), qmax, scale_dtype, symmetric)
         qs.append(q.reshape(N, -1)); zps.append(zp); ss.append(s)
     return QMat(np.concatenate(qs, axis=1), np.concatenate(zps, axis=1),
                 np.concatenate(ss, axis=1), group, b_high, b_low)
@@ -163,10 +183,10 @@ class QExpert:
     down: QMat
 
 
-def quantize_expert(w_gate, w_up, w_down, group, b_high=8, b_low=4, scale_dtype="f32") -> QExpert:
-    return QExpert(quantize(w_gate, group, b_high, b_low, scale_dtype),
-                   quantize(w_up, group, b_high, b_low, scale_dtype),
-                   quantize(w_down, group, b_high, b_low, scale_dtype))
+def quantize_expert(w_gate, w_up, w_down, group, b_high=8, b_low=4, scale_dtype="f32", symmetric=False) -> QExpert:
+    return QExpert(quantize(w_gate, group, b_high, b_low, scale_dtype, symmetric),
+                   quantize(w_up, group, b_high, b_low, scale_dtype, symmetric),
+                   quantize(w_down, group, b_high, b_low, scale_dtype, symmetric))
 
 
 # --------------------------------------------------------------------------

@@ -155,3 +155,39 @@ def test_lower_bit_nests():
         d = (m.dequant(O.LOW) - m.dequant(O.HIGH)) / 0.25
         for z, c in itertools.product(range(n), range(n)):
             assert d[z, c] == (z % (1 << shift)) - (c % (1 << shift))
+
+
+@pytest.mark.parametrize("b_high,b_low", [(8, 4), (6, 3), (4, 2)])
+def test_symmetric_variant_pins(b_high, b_low):
+    # Symmetric integer quantisation (Section 5 set-up) in the unsigned store: what must hold whatever
+    # the implementation -- the zero-point sits at mid-range, the largest magnitude of a group lands on
+    # the last signed level, negating the weights mirrors every code about the zero-point, an exact
+    # signed grid is recovered, and the error is at most half a step.
+    rng = np.random.default_rng(5)
+    half, G = 1 << (b_high - 1), 32
+    W = rng.standard_normal((6, 96)).astype(np.float32)
+    W[0, :32] = 0.0                                        # flat group
+    m = O.quantize(W, G, b_high, b_low, symmetric=True)
+    n = O.quantize(-W, G, b_high, b_low, symmetric=True)
+    assert np.all(m.zp == half) and np.all(n.zp == half)
+    assert np.array_equal(m.scale, n.scale)
+    assert np.array_equal(m.q.astype(int) - half, -(n.q.astype(int) - half))
+    assert m.q.min() >= 1                                  # level -2^(b-1) is never used
+    assert np.all(m.q[0, :32] == half) and m.scale[0, 0] == 1.0
+    Wg, qg = W.reshape(6, 3, G), m.q.reshape(6, 3, G).astype(int) - half
+    j = np.abs(Wg).argmax(axis=2)
+    top = np.take_along_axis(qg, j[:, :, None], axis=2)[:, :, 0]
+    assert np.all(np.abs(top)[1:] == half - 1)
+    assert np.array_equal(np.sign(top), np.sign(np.take_along_axis(Wg, j[:, :, None], axis=2)[:, :, 0]))
+    err = np.abs(m.dequant(O.HIGH) - W.astype(np.float64)).reshape(6, 3, G)
+    assert np.all(err <= 0.5 * m.scale[:, :, None].astype(np.float64) * (1 + 1e-6))
+    # an exact grid: signed integers times a power-of-two step come back unchanged
+    c = rng.integers(-(half - 1), half, size=(4, 64))
+    c[:, 0] = half - 1
+    c[:, 32] = -(half - 1)
+    g = O.quantize((c * 0.25).astype(np.float32), G, b_high, b_low, symmetric=True)
+    assert np.array_equal(g.q.astype(int) - half, c) and np.all(g.scale == 0.25)
+    assert np.array_equal(g.dequant(O.HIGH), c * 0.25)
+    # the low-bit model of the symmetric store is the truncated code against the truncated mid-point
+    shift = b_high - b_low
+    assert np.array_equal(g.dequant(O.LOW), 0.25 * (1 << shift) * ((g.q.astype(int) >> shift) - (half >> shift)))
