@@ -60,6 +60,10 @@ typedef struct {
   int32_t b_high, b_low;
   int32_t w_dtype;      /* dtype of the source weights handed to smoe_quantize_slice */
   int32_t scale_dtype;  /* dtype the per-group scales are stored in (and rounded to) */
+  int32_t symmetric;    /* 0: asymmetric min-max quantiser (the experts, Table 1 note 1).  1: symmetric
+                         * quantiser (Section 5: the non-expert weights are symmetric INT8) in the same
+                         * store: zero-point fixed at 2^(b_high-1); see smoe_quantize_slice.  Other
+                         * values: SMOE_EINVAL. */
 } smoe_bank_desc;
 
 typedef struct {
@@ -94,7 +98,10 @@ int smoe_bank_destroy(smoe_bank* bank);
  * bank: per group lo = min(0, min w), hi = max(0, max w), s = round_to_scale_dtype((hi-lo)/255)
  * (1 if that is not positive), zp = clamp(rint(-lo/s)), q = clamp(rint(w/s) + zp), all fp32
  * round-to-nearest-even; then the code is split into its upper nibble (MSB slice, = the 4-bit
- * model's code floor(q/16)) and lower nibble (LSB slice), stored in separate planes. */
+ * model's code floor(q/16)) and lower nibble (LSB slice), stored in separate planes.
+ * With desc.symmetric the first three steps are instead s = round_to_scale_dtype(max|w| /
+ * (2^(b_high-1) - 1)) (1 if not positive), zp = 2^(b_high-1), q = clamp(rint(w/s) + zp); every
+ * consumer reads such a bank like any other. */
 int smoe_quantize_slice(smoe_ctx* ctx, smoe_bank* bank, int e0, int n, const void* w_gate_dev,
                         const void* w_up_dev, const void* w_down_dev);
 /* Copies one matrix of one expert back in canonical form (matrix: 0 gate, 1 up, 2 down; N x K its

@@ -26,7 +26,7 @@ class SmoeError(RuntimeError):
 
 class BankDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
-                ("n_experts", "d_model", "d_ff", "group", "b_high", "b_low", "w_dtype", "scale_dtype")]
+                ("n_experts", "d_model", "d_ff", "group", "b_high", "b_low", "w_dtype", "scale_dtype", "symmetric")]
 
 
 class CacheStats(C.Structure):
@@ -123,9 +123,10 @@ def smoe_bank_bytes(desc: BankDesc) -> int:
 class Bank:
     """A sliced expert store; the torch tensor `store` owns the device memory."""
 
-    def __init__(self, ctx: Ctx, n_experts, d_model, d_ff, group, w_dtype="f32", scale_dtype="f32", b_high=8, b_low=4):
+    def __init__(self, ctx: Ctx, n_experts, d_model, d_ff, group, w_dtype="f32", scale_dtype="f32", b_high=8, b_low=4,
+                 symmetric=False):
         self.ctx = ctx
-        self.desc = BankDesc(n_experts, d_model, d_ff, group, b_high, b_low, _DT[w_dtype], _DT[scale_dtype])
+        self.desc = BankDesc(n_experts, d_model, d_ff, group, b_high, b_low, _DT[w_dtype], _DT[scale_dtype], int(symmetric))
         self.nbytes = smoe_bank_bytes(self.desc)
         self.store = torch.empty(self.nbytes + 256, dtype=torch.uint8, device="cuda:%d" % ctx.device)
         off = (-self.store.data_ptr()) % 256

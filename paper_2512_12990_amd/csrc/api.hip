@@ -86,6 +86,7 @@ static int check_desc(const smoe_bank_desc* d) {
   if (d->d_model % 32 || d->d_ff % 32 || d->group % 32) return SMOE_ESHAPE;
   if ((d->w_dtype != SMOE_F32 && d->w_dtype != SMOE_BF16) || (d->scale_dtype != SMOE_F32 && d->scale_dtype != SMOE_BF16))
     return SMOE_EINVAL;
+  if (d->symmetric != 0 && d->symmetric != 1) return SMOE_EINVAL;
   if (d->b_high <= d->b_low || d->b_low < 1 || d->b_high > 8) return SMOE_ESHAPE;
   if (!((d->b_high == 8 && d->b_low == 4) || (d->b_high == 6 && d->b_low == 3) || (d->b_high == 4 && d->b_low == 2)))
     return SMOE_ENOTIMPL;

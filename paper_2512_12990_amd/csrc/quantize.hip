@@ -25,7 +25,7 @@ __device__ __forceinline__ float wave_max(float v) {
 // else w0 is [n, N, K]).  Destination family `m` already points at expert 0 of the bank.
 template <int WDT>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restrict__ w0, const void* __restrict__ w1,
-                                                            MatDev m, int e0, int group, int sc_bf16, int interleave) {
+                                                            MatDev m, int e0, int group, int sc_bf16, int interleave, int symmetric) {
   const int row = blockIdx.x, el = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int K = m.K, ng = m.ng;
   const void* src;
@@ -58,10 +58,13 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restri
     }
     lo = wave_min(lo);
     hi = wave_max(hi);
-    float s = (hi - lo) / qmax;
+    // symmetric variant (Section 5: symmetric integer weights): step from the largest magnitude, the
+    // zero-point fixed at mid-range of the unsigned store
+    const float half = 0.5f * (qmax + 1.0f);
+    float s = symmetric ? fmaxf(hi, -lo) / (half - 1.0f) : (hi - lo) / qmax;
     if (sc_bf16) s = bf16_bits_to_f32(f32_to_bf16_bits(s));
     if (!(s > 0.0f)) s = 1.0f;
-    const int zp = (int)fminf(fmaxf(rintf((-lo) / s), 0.0f), qmax);
+    const int zp = symmetric ? (int)half : (int)fminf(fmaxf(rintf((-lo) / s), 0.0f), qmax);
     if (bits == 3) {
       // 6-bit codes: upper three bits = the low-bit code.  A plane keeps the 32 three-bit values of a
       // chunk of 32 columns in 12 bytes, laid out so that a nibble word (one value per nibble, columns
@@ -135,11 +138,11 @@ int smoe_launch_quantize(smoe_ctx* ctx, smoe_bank* bank, int e0, int n, const vo
   HIPCHK(ctx, hipSetDevice(ctx->device));
   dim3 blk(256);
   if (bank->desc.w_dtype == SMOE_F32) {
-    quantize_rows_kernel<SMOE_F32><<<dim3(b.gu.N, n), blk, 0, ctx->stream>>>(wg, wu, b.gu, e0, b.group, b.sc_bf16, 1);
-    quantize_rows_kernel<SMOE_F32><<<dim3(b.dn.N, n), blk, 0, ctx->stream>>>(wd, nullptr, b.dn, e0, b.group, b.sc_bf16, 0);
+    quantize_rows_kernel<SMOE_F32><<<dim3(b.gu.N, n), blk, 0, ctx->stream>>>(wg, wu, b.gu, e0, b.group, b.sc_bf16, 1, bank->desc.symmetric);
+    quantize_rows_kernel<SMOE_F32><<<dim3(b.dn.N, n), blk, 0, ctx->stream>>>(wd, nullptr, b.dn, e0, b.group, b.sc_bf16, 0, bank->desc.symmetric);
   } else {
-    quantize_rows_kernel<SMOE_BF16><<<dim3(b.gu.N, n), blk, 0, ctx->stream>>>(wg, wu, b.gu, e0, b.group, b.sc_bf16, 1);
-    quantize_rows_kernel<SMOE_BF16><<<dim3(b.dn.N, n), blk, 0, ctx->stream>>>(wd, nullptr, b.dn, e0, b.group, b.sc_bf16, 0);
+    quantize_rows_kernel<SMOE_BF16><<<dim3(b.gu.N, n), blk, 0, ctx->stream>>>(wg, wu, b.gu, e0, b.group, b.sc_bf16, 1, bank->desc.symmetric);
+    quantize_rows_kernel<SMOE_BF16><<<dim3(b.dn.N, n), blk, 0, ctx->stream>>>(wd, nullptr, b.dn, e0, b.group, b.sc_bf16, 0, bank->desc.symmetric);
   }
   HIPCHK(ctx, hipGetLastError());
   return SMOE_OK;

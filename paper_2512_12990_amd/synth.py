@@ -33,6 +33,7 @@ class LayerShape:
     act: str = "bf16"                  # activation / scale dtype: "f32" or "bf16"
     b_high: int = 8                    # bits of the full code and of its upper (low-bit) part: 8/4 or 4/2
     b_low: int = 4
+    symmetric: bool = False            # symmetric quantiser (zero-point at mid-range) instead of min-max
 
 
 @dataclass(frozen=True)

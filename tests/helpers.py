@@ -28,13 +28,13 @@ class LayerPair:
         self.routed = self.shared = None
         if routed and shape.n_experts > 0:
             self.routed = B.Bank(ctx, shape.n_experts, shape.d_model, shape.d_ff, shape.group, self.dt, self.dt,
-                                 shape.b_high, shape.b_low)
+                                 shape.b_high, shape.b_low, shape.symmetric)
             for e in range(shape.n_experts):
                 self._quantise_into(self.routed, e, e, shape.d_ff)
         if shape.n_shared > 0:
             sf = shape.shared_d_ff
             self.shared = B.Bank(ctx, shape.n_shared, shape.d_model, sf, shape.group, self.dt, self.dt, shape.b_high,
-                                 shape.b_low)
+                                 shape.b_low, shape.symmetric)
             for i in range(shape.n_shared):
                 self._quantise_into(self.shared, i, 1000 + i, sf)
         torch.cuda.synchronize()
@@ -60,7 +60,7 @@ class LayerPair:
             d_ff = self.shape.shared_d_ff if tag >= 1000 else self.shape.d_ff
             wg, wu, wd = (t2np(w) for w in self.dense(tag, d_ff))
             self._oracle_cache[tag] = O.quantize_expert(wg, wu, wd, self.shape.group, self.shape.b_high, self.shape.b_low,
-                                                        scale_dtype=self.dt)
+                                                        scale_dtype=self.dt, symmetric=self.shape.symmetric)
         return self._oracle_cache[tag]
 
     def oracle_routed(self):

@@ -78,6 +78,24 @@ def test_quantize_slice_lower_nests_bit_exact(ctx, d, f, G, dt, nest):
             assert np.array_equal(got["scale"].view(np.uint32), qm.scale.view(np.uint32))
 
 
+@pytest.mark.parametrize("nest", [(8, 4), (6, 3), (4, 2)])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_quantize_symmetric_bit_exact(ctx, dt, nest):
+    # the symmetric quantiser of the non-expert weights (Section 5 set-up) in the same store
+    bh, bl = nest
+    say("quantize symmetric", nest, dt)
+    shape = synth.LayerShape(256, 2, 96, 1, 128, act=dt, b_high=bh, b_low=bl, symmetric=True)
+    pair = LayerPair(ctx, shape, seed=11)
+    for e in range(2):
+        ex = pair.oracle_expert(e)
+        for mi, qm in enumerate((ex.gate, ex.up, ex.down)):
+            got = B.smoe_export_codes(ctx, pair.routed, e, mi)
+            assert np.all(got["zp"] == 1 << (bh - 1)) and int(got["q"].min()) >= 1
+            assert np.array_equal(got["q"], qm.q)
+            assert np.array_equal(got["msb"], qm.msb()) and np.array_equal(got["lsb"], qm.lsb())
+            assert np.array_equal(got["scale"].view(np.uint32), qm.scale.view(np.uint32))
+
+
 def test_quantize_special_groups_bit_exact(ctx):
     # flat groups, one-sided groups, exact zeros, a huge and a tiny group next to each other
     say("quantize special")
@@ -317,6 +335,28 @@ def test_dense_ffn_through_shared_bank(ctx):
         y = B.smoe_expert_ffn(ctx, None, pair.shared, dev(x[t]), None, None, None)
         yref = O.moe_layer(t2np(x[t]).astype(np.float64), [], [], [], [], pair.oracle_shared())
         assert O.max_abs_rel(t2np(y), yref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_symmetric_store_layer(ctx, dt):
+    # a layer whose banks were filled by the symmetric quantiser: the dense FFN through the shared bank
+    # (how the symmetric INT8 non-expert weights of the paper's set-up run) and a routed mix of HIGH / LOW
+    say("symmetric store", dt)
+    shp = synth.LayerShape(256, 4, 128, 2, 128, n_shared=1, shared_d_ff=416, act=dt, symmetric=True)
+    pair = LayerPair(ctx, shp, seed=6)
+    x = synth.activations(6, 2, 256, dt)
+    for t in range(2):
+        y = B.smoe_expert_ffn(ctx, None, pair.shared, dev(x[t]), None, None, None)
+        yref = O.moe_layer(t2np(x[t]).astype(np.float64), [], [], [], [], pair.oracle_shared())
+        assert O.max_abs_rel(t2np(y), yref) <= TOL[dt]
+    idx = np.array([2, 0], np.int32)
+    w = np.array([0.7, 0.3], np.float32)
+    mask = np.array([3, 1, 1, 3], np.uint8)
+    prec = torch.zeros(2, dtype=torch.uint8, device="cuda:0")
+    y = B.smoe_expert_ffn(ctx, pair.routed, pair.shared, dev(x[0]), dev(idx), dev(w), dev(mask), prec_out=prec)
+    assert t2np(prec).tolist() == [0, 1]
+    yref = O.moe_layer(t2np(x[0]).astype(np.float64), pair.oracle_routed(), idx, w, [0, 1], pair.oracle_shared())
+    assert O.max_abs_rel(t2np(y), yref) <= TOL[dt]
 
 
 def test_determinism_and_high_low_differ(ctx):

@@ -39,7 +39,8 @@ def test_strerror_and_bank_bytes_validation():
     nbytes = C.c_size_t()
     for bad, rc in [(B.BankDesc(0, 2048, 1408, 128, 8, 4, 0, 0), -2), (B.BankDesc(4, 2040, 1408, 128, 8, 4, 0, 0), -2),
                     (B.BankDesc(4, 2048, 1408, 100, 8, 4, 0, 0), -2), (B.BankDesc(4, 2048, 1408, 128, 8, 2, 0, 0), -6),
-                    (B.BankDesc(4, 2048, 1408, 128, 4, 4, 0, 0), -2), (B.BankDesc(4, 2048, 1408, 128, 8, 4, 7, 0), -1)]:
+                    (B.BankDesc(4, 2048, 1408, 128, 4, 4, 0, 0), -2), (B.BankDesc(4, 2048, 1408, 128, 8, 4, 7, 0), -1),
+                    (B.BankDesc(4, 2048, 1408, 128, 8, 4, 0, 0, 2), -1)]:
         assert lib.smoe_bank_bytes(C.byref(bad), C.byref(nbytes)) == rc
     # the lower nests store b_low bits per plane value: 3/4 and 1/2 of the plane bytes of the 8/4 nest
     for bh, bl in [(6, 3), (4, 2)]:
