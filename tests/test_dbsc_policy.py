@@ -129,3 +129,31 @@ def test_criticality_threshold_trades_lsb_traffic():
     pair = (B.Cache(L, E, 2 * L * E), O.SliceLRU(L, E, 2 * L * E))
     st = _run(pair, idx, w, 0.0)
     assert st["lsb_hit"] + st["lsb_miss"] == st["msb_hit"] + st["msb_miss"] == 64 * L * k
+
+
+def test_warmup_beats_the_naive_initial_states():
+    """Section 4.3 names three naive cache states at the start of decode -- empty, only what the
+    layer-wise prefill touched last, a random retention -- and says each does poorly in early decode.
+    All four are just different retention orders handed to the same LRU: on a popularity-skewed trace
+    the frequency-ordered state misses least, and no filled state misses more than the empty one."""
+    L, E, k = 4, 32, 4
+    idx, w = _trace(17, L, E, k, 192, period=256)
+    pre, dec, wdec = idx[:128], idx[128:], w[128:]
+    hist = np.stack([O.histogram(pre[:, l].reshape(-1), E) for l in range(L)]).astype(np.uint32)
+    cap = (2 * L * E) // 4
+    sid = lambda l, e, lsb: ((l * E + e) << 1) | lsb
+    # prefill runs layer by layer at high precision and loads every expert: the cache ends up holding
+    # both slices of the layers processed last
+    last = [sid(l, e, b) for l in range(L - 1, -1, -1) for e in range(E) for b in (0, 1)][:cap]
+    rnd = np.random.default_rng(17).permutation(2 * L * E)[:cap].tolist()
+    states = {"empty": None, "last": last, "random": rnd, "pcw": B.smoe_topn_slices(hist, cap).tolist()}
+    miss = {}
+    for name, ids in states.items():
+        pair = (B.Cache(L, E, cap), O.SliceLRU(L, E, cap))
+        if ids is not None:
+            pair[0].init_order(np.asarray(ids, np.int32))
+            pair[1].init_order(np.asarray(ids, np.int32))
+        miss[name] = _run(pair, dec, wdec, 0.0, first=10)["msb_miss"]
+    assert miss["pcw"] < miss["last"] and miss["pcw"] < miss["random"] and miss["pcw"] < miss["empty"], miss
+    assert miss["last"] <= miss["empty"] and miss["random"] <= miss["empty"], miss
+    assert 2 * miss["pcw"] < min(miss["last"], miss["random"]), miss
