@@ -46,10 +46,11 @@ def main():
     ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64, 128],
                     help="decode: quantisation group of the expert weights (default: the workload's 128; 32 is the "
                          "paper's expert format, with four times the scales and zero-points)")
-    ap.add_argument("--shape", choices=["dsv2", "qwen"], default="dsv2",
+    ap.add_argument("--shape", choices=["dsv2", "qwen", "wide"], default="dsv2",
                     help="decode: dsv2 = the headline DeepSeek-V2-Lite-shaped layer; qwen = one Qwen1.5-MoE-shaped layer "
                          "(60 experts top-4, one shared expert of d_ff 5632 behind a sigmoid gate, 18 experts HIGH, all "
-                         "MSB slices resident), reported as its own line")
+                         "MSB slices resident), reported as its own line; wide = d_model 4096 (16 experts of d_ff 2048, top-4, one "
+                         "shared expert: rows of two 64-chunk k-slices, the wide gate/up kernel)")
     ap.add_argument("--router-matvec", action="store_true",
                     help="decode (one token per step): logits from the router mat-vec W_r x (a third launch) instead of "
                          "supplied logits")
@@ -92,6 +93,8 @@ def main():
     if args.shape == "qwen":
         import dataclasses
         wl = dataclasses.replace(synth.QWEN_STACK, n_layers=1, steps=1024)
+    if args.shape == "wide":
+        wl = synth.Workload("wide-layer", synth.LayerShape(4096, 16, 2048, 4, 128, n_shared=1, shared_d_ff=2048), steps=256)
     if args.group:
         import dataclasses
         wl = dataclasses.replace(wl, layer=dataclasses.replace(wl.layer, group=args.group))
@@ -112,6 +115,8 @@ def main():
     if args.shape == "qwen":
         mask_np = synth.fraction_masks(wl.seed, 1, 0, shp.n_experts, 0.3)[0]
         bias_np = np.zeros(shp.n_experts, np.float32)
+    elif args.shape == "wide":
+        mask_np, bias_np = synth.cached_set_mask(wl.seed, shp.n_experts, 8, 4, 1.0)
     else:
         mask_np, bias_np = synth.cached_set_mask(wl.seed, shp.n_experts, 32, 16, 1.0)
     mask = torch.from_numpy(mask_np).to(dev)
@@ -235,6 +240,7 @@ def main():
         "dtype": "u%d+u%d bit-sliced weights, bf16 activations rewritten per 32-chunk as 3 balanced hex digits, signed 4-bit dot products, int32/fp32 accumulate" % (bl, bl),
         "data": "synthetic",
         "config": {"workload": ("DeepSeek-V2-Lite-shaped MoE layer decode, %d token%s/step (BASELINE configs[1])" if args.shape == "dsv2" else
+                                "d_model-4096 MoE layer decode, %d token%s/step (no BASELINE config: the wide-row kernel)" if args.shape == "wide" else
                                 "Qwen1.5-MoE-shaped MoE layer decode, %d token%s/step (one layer of BASELINE configs[2])") % (TT, "" if TT == 1 else "s"),
                    "d_model": shp.d_model, "n_experts": shp.n_experts, "d_ff": shp.d_ff, "top_k": shp.top_k,
                    "n_shared": shp.n_shared, "shared_d_ff": shp.shared_d_ff, "group": shp.group, "nest": "%d/%d" % (bh, bl),

@@ -130,7 +130,10 @@ int smoe_route(smoe_ctx* ctx, int T, int E, int k, int d_model, const float* log
  * plane.  gamma = 1, or sigmoid(shared_gate_w . x) when shared_gate_w_dev (act_dtype [d_model]) is
  * given.  `routed` may be NULL with k = 0 (dense FFN through `shared`); `shared` may be NULL.
  * x_dev, y_dev: act_dtype [d_model]; idx_dev int32 [k]; w_dev fp32 [k]; slice_mask_dev uint8 [E];
- * prec_out_dev uint8 [k] or NULL.  y_dev may not alias x_dev. */
+ * prec_out_dev uint8 [k] or NULL.  y_dev may not alias x_dev.
+ * Limits of the decode entry points: d_model <= 8192 (SMOE_ENOTIMPL beyond) and a multiple of 8,
+ * group = 32 * 2^n, k <= 16, at most 8 shared experts, one scale dtype and one nest per layer, and
+ * k * d_ff + n_shared * shared_d_ff floats of intermediates within the ctx workspace (SMOE_ESIZE). */
 int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared,
                     const void* x_dev, int act_dtype, int k, const int32_t* idx_dev,
                     const float* w_dev, const uint8_t* slice_mask_dev, float tau_head,

@@ -24,6 +24,7 @@ extern "C" int smoe_ctx_create(int device, void* hip_stream, smoe_ctx** out) {
   if (!c) return SMOE_EINVAL;
   c->device = device; c->stream = (hipStream_t)hip_stream; c->ws = nullptr; c->last_hip = 0; c->n_cu = 256; c->timing = 0; c->timing_events = nullptr;
   for (size_t& g : c->down_lds_granted) g = 0;
+  for (size_t& g : c->route_lds_granted) g = 0;
   hipError_t e = hipSetDevice(device);
   if (e == hipSuccess) e = hipMalloc((void**)&c->ws, SMOE_WORKSPACE_BYTES);
   if (e == hipSuccess) {

@@ -45,6 +45,7 @@ struct smoe_ctx {
   int timing;
   void* timing_events;   // std::vector<hipEvent_t>*, four events per decode call
   size_t down_lds_granted[48];   // dynamic LDS already granted to each down_kernel instantiation on this device
+  size_t route_lds_granted[2];   // likewise for route_batch_kernel (bf16, fp32 activations)
 };
 
 struct smoe_bank {

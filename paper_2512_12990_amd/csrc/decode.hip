@@ -843,6 +843,143 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
   }
 }
 
+// ---------------------------------------------------------------------------------- gate/up kernel, wide rows
+// d_model above 2048 (up to DEC_WIDE_MAX_D): a row has more 32-column chunks than a wave has lanes, so a
+// lane takes one chunk of each of up to four 64-chunk k-slices and adds the partial values before the
+// wave sum.  Same split of the row pairs over work-groups and waves, same routing wave and record as
+// gateup_kernel; one row pair at a time per wave, all k-slices of the pair in flight together.
+#define DEC_WIDE_KS 4
+#define DEC_WIDE_MAX_D (DEC_WIDE_KS * 2048)
+template <int ACT> struct WideTraits;
+template <> struct WideTraits<SMOE_BF16> { enum { SLICE_BYTES = 4096 }; };      // the k-slice stride of stage_regs / load_xr
+template <> struct WideTraits<SMOE_F32> { enum { SLICE_BYTES = 8192 }; };
+
+template <int ACT, int SCB, int FMT>
+__global__ __launch_bounds__(DEC_NT) void gateup_wide_kernel(const float* logits, const float* bias, const uint8_t* mask, const void* x_in,
+                                                             int E, int k, int do_route, int d_model, int n_wg, int n_se,
+                                                             DecodeArgs a) {
+  __shared__ int sel_lds[SMOE_MAX_TOPK], prec_lds[SMOE_MAX_TOPK];
+  __shared__ __align__(16) uint8_t xvec[DEC_WIDE_KS * WideTraits<ACT>::SLICE_BYTES];
+  __shared__ float2 xcs[DEC_WIDE_KS * 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
+  const int tok = blockIdx.y, wg = (int)blockIdx.x + 8 * (int)blockIdx.z;
+  if (tok) {
+    logits += (size_t)tok * E;
+    x_in = (const uint8_t*)x_in + (size_t)tok * d_model * (ACT == SMOE_BF16 ? 2 : 4);
+    a.h += (size_t)tok * DEC_H_STRIDE(a.n_shared * a.f_s, a.f_r);
+    a.rec += tok;
+    if (a.idx_in) a.idx_in += tok * k;
+    if (a.w_in) a.w_in += tok * k;
+    if (a.idx_out) a.idx_out += tok * k;
+    if (a.w_out) a.w_out += tok * k;
+    if (a.prec_out) a.prec_out += tok * k;
+  }
+  const RouteIn in{logits, bias, mask, E, k, do_route};
+  const int d = d_model, C = d >> 5, KS = (C + 63) >> 6;
+  const bool router = k > 0 && wave == DEC_NW - 1;
+  RouteRegs rr = {};
+  route_load(in, lane, rr, router);
+  // ---- x into LDS in digit form: word i (8 values) of the vector belongs to chunk i / 4; a quad handles a chunk
+  for (int i = tid; i < 4 * C; i += DEC_NT) {
+    Raw8 xraw = {};
+    load8_raw<ACT>(x_in, (size_t)i * 8, xraw);
+    float xv[8];
+    unpack8<ACT>(xraw, xv);
+    stage_regs<ACT>(xv, C, i >> 2, i & 3, xvec, xcs);
+  }
+  int mysel = 0, myprec = 0;
+  float myw = 0.0f;
+  if (router) {
+    route_wave<true>(in, a, lane, rr, mysel, myprec, myw);
+    if (lane < k) { sel_lds[lane] = mysel; prec_lds[lane] = myprec; }
+  }
+  __syncthreads();
+  if (wg == 0) {
+    if (router && lane < k) {
+      a.rec->sel[lane] = mysel; a.rec->prec[lane] = myprec; a.rec->w[lane] = myw;
+      if (a.prec_out) a.prec_out[lane] = (uint8_t)myprec;
+      if (a.idx_out) a.idx_out[lane] = mysel;
+      if (a.w_out) a.w_out[lane] = myw;
+    }
+    if (wave == 0) {                                       // weight of the shared experts
+      float g = 1.0f;
+      if (a.shared_gate_w) {
+        float p = 0.0f;
+        for (int i0 = lane * 8; i0 < d; i0 += 512) {
+          Raw8 wr = {}, xr = {};
+          load8_raw<ACT>(a.shared_gate_w, (size_t)i0, wr);
+          load8_raw<ACT>(x_in, (size_t)i0, xr);
+          float wv[8], xv8[8];
+          unpack8<ACT>(wr, wv);
+          unpack8<ACT>(xr, xv8);
+#pragma unroll
+          for (int i = 0; i < 8; i++) p = fmaf(wv[i], xv8[i], p);
+        }
+        g = 1.0f / (1.0f + expf(-wave_sum(p)));
+      }
+      if (lane == 0) a.rec->gamma = g;
+    }
+  }
+
+  constexpr unsigned PB = PlaneT<FMT>::BYTES;
+  const unsigned rowb32 = (unsigned)C * PB;
+  const int nsf = a.n_shared * a.f_s;
+  const int N_e = n_se + k * a.cap_r;
+  const int e_lo = wave * a.gu_L, e_hi = uni(min(e_lo + a.gu_L, N_e));
+  for (int e_cur = e_lo; e_cur < e_hi; e_cur++) {
+    const bool is_sh = e_cur < n_se;
+    int s, q0, ex, prec, f, sh;
+    if (is_sh) {
+      s = (e_cur * a.inv_cap_s) >> 16; q0 = e_cur - s * a.cap_s; ex = s; prec = 1; f = a.f_s; sh = a.gu_sh_s;
+    } else {
+      const int er = e_cur - n_se, sr = (er * a.inv_cap_r) >> 16;
+      s = a.n_shared + sr; q0 = er - sr * a.cap_r; ex = uni(sel_lds[sr]); prec = uni(prec_lds[sr]); f = a.f_r; sh = a.gu_sh_r;
+    }
+    const MatK& md = is_sh ? a.sgu : a.rgu;
+    int bp = wg + s * a.rot;
+    bp = bp >= n_wg ? bp - n_wg : bp;
+    const int r0 = bp + n_wg * q0;
+    if (r0 >= f) continue;                                  // wave-uniform
+    const SecRsrc R = make_sec(md, is_sh ? a.n_shared : E);
+    const unsigned po = (unsigned)ex * md.ps32 + (unsigned)(2 * r0) * rowb32;
+    const unsigned zo = (unsigned)ex * md.zs32 + (unsigned)(2 * r0) * (unsigned)md.ng;
+    const unsigned sb = (unsigned)md.sng * (SCB ? 2u : 4u);
+    const unsigned so = (unsigned)ex * md.ss32 + (unsigned)(2 * r0) * sb;
+    typename PlaneT<FMT>::t gm[DEC_WIDE_KS], um[DEC_WIDE_KS], gl[DEC_WIDE_KS], ul[DEC_WIDE_KS];
+    uint32_t zg[DEC_WIDE_KS], zu[DEC_WIDE_KS], sg[DEC_WIDE_KS], su[DEC_WIDE_KS];
+#pragma unroll
+    for (int ks = 0; ks < DEC_WIDE_KS; ks++) {
+      const unsigned c = (unsigned)(ks * 64 + lane), gi = c >> sh;
+      const bool live = ks < KS && c < (unsigned)C;
+      const unsigned vz = live ? gi : DEC_OOB, vs = live ? (SCB ? (gi >> 1) << 2 : gi << 2) : DEC_OOB;
+      const unsigned vo = live ? c * PB : DEC_OOB, vl = (live && prec) ? c * PB : DEC_OOB;
+      zg[ks] = bload8(R.zp, vz, zo);
+      zu[ks] = bload8(R.zp, vz, zo + (unsigned)md.ng);
+      sg[ks] = bload32(R.sc, vs, so);
+      su[ks] = bload32(R.sc, vs, so + sb);
+      gm[ks] = pload<FMT>(R.msb, vo, po);
+      gl[ks] = pload<FMT>(R.lsb, vl, po);
+      um[ks] = pload<FMT>(R.msb, vo, po + rowb32);
+      ul[ks] = pload<FMT>(R.lsb, vl, po + rowb32);
+    }
+    float av = 0.0f, uv = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < DEC_WIDE_KS; ks++) {
+      if (ks < KS) {                                        // wave-uniform
+        const int cw = min(64, C - ks * 64);
+        const int odd = SCB ? (((ks * 64 + lane) >> sh) & 1) : 0;
+        XR<ACT> x = {};
+        if (lane < cw) load_xr<ACT>(x, xvec, xcs, ks, cw, lane);
+        av += lane_value(x, gm[ks], gl[ks], prec, (int)zg[ks], scale_val<SCB>(sg[ks], odd));
+        uv += lane_value(x, um[ks], ul[ks], prec, (int)zu[ks], scale_val<SCB>(su[ks], odd));
+      }
+    }
+    av = wave_sum_to63(av);
+    uv = wave_sum_to63(uv);
+    if (lane == 63) a.h[(is_sh ? s * a.f_s : nsf + (s - a.n_shared) * a.f_r) + r0] = av * __builtin_amdgcn_rcpf(1.0f + __expf(-av)) * uv;
+  }
+}
+
 // ---------------------------------------------------------------------------------- down kernel
 // A work-group owns DEC_RPW = 8 output rows.  Its work is cut into pieces = (combo, part): a combo
 // is one (slot, 64-chunk k-slice) pair -- shared experts first, then the routed slots -- and a
@@ -1020,19 +1157,28 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
   if (T > 1 && ((n_wg & 7) || (n_dn & 7))) return SMOE_ESHAPE;      // the multi-token grid is (8, T, n / 8)
   const dim3 g1 = T > 1 ? dim3(8, T, n_wg / 8) : dim3(n_wg), g2 = T > 1 ? dim3(8, T, n_dn / 8) : dim3(n_dn), blk(DEC_NT);
   const int n_se = a.n_shared * a.cap_s;
+  const bool wide = a.d_model > 2048;                 // rows of more than 64 chunks: the k-sliced gate/up kernel
   const int* recw = (const int*)a.rec;
   const int nsf = a.n_shared * a.f_s;
   if (evs) {
     // measurement aid: the dispatches themselves carry start/stop events (no extra marker packets)
     hipEvent_t ev[4];
     for (int i = 0; i < 4; i++) { HIPCHK(ctx, hipEventCreate(&ev[i])); evs->push_back(ev[i]); }
-    hipExtLaunchKernelGGL((gateup_kernel<ACT, SCB, FMT>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
-                          in.E, in.k, in.do_route, a.d_model, n_wg, n_se, a);
+    if (wide)
+      hipExtLaunchKernelGGL((gateup_wide_kernel<ACT, SCB, FMT>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
+                            in.E, in.k, in.do_route, a.d_model, n_wg, n_se, a);
+    else
+      hipExtLaunchKernelGGL((gateup_kernel<ACT, SCB, FMT>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
+                            in.E, in.k, in.do_route, a.d_model, n_wg, n_se, a);
     hipExtLaunchKernelGGL((down_kernel<ACT, SCB, FMT, RPW>), g2, blk, (unsigned)lds, ctx->stream, ev[2], ev[3], 0, recw, (const float*)a.h,
                           n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s, a.ks_r, a.inv_ks_s, a.inv_ks_r, nsf, a);
   } else {
-    gateup_kernel<ACT, SCB, FMT><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, n_wg, n_se,
-                                                         a);
+    if (wide)
+      gateup_wide_kernel<ACT, SCB, FMT><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, n_wg,
+                                                                n_se, a);
+    else
+      gateup_kernel<ACT, SCB, FMT><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, n_wg, n_se,
+                                                           a);
     down_kernel<ACT, SCB, FMT, RPW><<<g2, blk, lds, ctx->stream>>>(recw, (const float*)a.h, n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s,
                                                          a.ks_r, a.inv_ks_s, a.inv_ks_r, nsf, a);
   }
@@ -1053,7 +1199,7 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   const int ns = shared ? shared->desc.n_experts : 0;
   if (k + ns > SMOE_MAX_SLOTS) return SMOE_ESHAPE;
   const int d_model = routed ? routed->desc.d_model : shared->desc.d_model;
-  if (d_model > 2048) return SMOE_ENOTIMPL;       // gate/up keeps one 32-column chunk per lane
+  if (d_model > DEC_WIDE_MAX_D) return SMOE_ENOTIMPL;      // gate/up: at most four 64-chunk k-slices per row
   if (d_model % DEC_RPW) return SMOE_ESHAPE;
   a.f_r = routed ? routed->desc.d_ff : 0;
   a.f_s = shared ? shared->desc.d_ff : 0;

@@ -49,15 +49,32 @@ int smoe_launch_router_logits(smoe_ctx* ctx, int E, int d, const void* x, int ac
   return SMOE_OK;
 }
 
+// Dynamic LDS beyond the default 64 KB per work-group (wide activations) has to be granted to the
+// kernel once per device.
+template <typename K>
+static int route_lds_grant(smoe_ctx* ctx, K kernel, size_t lds, size_t& granted) {
+  if (lds > 160u * 1024u) return SMOE_ESIZE;
+  if (lds > 64u * 1024u && lds > granted) {
+    if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+      (void)hipGetLastError();
+      return SMOE_ESIZE;
+    }
+    granted = lds;
+  }
+  return SMOE_OK;
+}
+
 int smoe_launch_route(smoe_ctx* ctx, const RouteArgs& a, int T, int act_dtype) {
   const bool given = a.logits != nullptr;
   if (act_dtype == SMOE_BF16) {
     const size_t lds = RouteLds<SMOE_BF16, 8>::bytes(a.E, a.d_model, given);
-    if (lds > 64u * 1024u) return SMOE_ESIZE;
+    const int rc = route_lds_grant(ctx, route_batch_kernel<SMOE_BF16, 8>, lds, ctx->route_lds_granted[0]);
+    if (rc != SMOE_OK) return rc;
     route_batch_kernel<SMOE_BF16, 8><<<(T + 7) / 8, RT_THREADS, lds, ctx->stream>>>(a, T);
   } else {
     const size_t lds = RouteLds<SMOE_F32, 4>::bytes(a.E, a.d_model, given);
-    if (lds > 64u * 1024u) return SMOE_ESIZE;
+    const int rc = route_lds_grant(ctx, route_batch_kernel<SMOE_F32, 4>, lds, ctx->route_lds_granted[1]);
+    if (rc != SMOE_OK) return rc;
     route_batch_kernel<SMOE_F32, 4><<<(T + 3) / 4, RT_THREADS, lds, ctx->stream>>>(a, T);
   }
   HIPCHK(ctx, hipGetLastError());

@@ -324,6 +324,40 @@ def test_lower_nest_layer(ctx, dt, G, nest):
         _run_layer_steps(ctx, wl2, pair2, range(1), m2, None, z2, x2, True)
 
 
+@pytest.mark.parametrize("d,dt,G,nest", [(4096, "bf16", 128, (8, 4)), (2560, "bf16", 32, (8, 4)), (2112, "f32", 64, (8, 4)),
+                                         (8192, "bf16", 128, (8, 4)), (4096, "bf16", 128, (6, 3)), (2560, "f32", 128, (4, 2))])
+def test_wide_rows_layer(ctx, d, dt, G, nest):
+    # d_model above 2048: a row of the gate/up matrices spans several 64-chunk k-slices (2112 and 2560:
+    # a ragged last slice; 8192: four full ones); shared expert with its sigmoid gate, router mat-vec,
+    # residual, masks of every kind
+    bh, bl = nest
+    say("wide rows", d, dt, G, nest)
+    shp = synth.LayerShape(d, 6, 96, 2, G, n_shared=1, shared_d_ff=160, shared_gate=True, act=dt, b_high=bh, b_low=bl)
+    wl = synth.Workload("wide", shp, steps=3, seed=41)
+    pair = LayerPair(ctx, shp, seed=wl.seed)
+    x_all = synth.activations(wl.seed, wl.steps, d, dt)
+    masks = synth.bernoulli_masks(wl.seed, wl.steps, shp.n_experts)
+    masks[1, :] = 3
+    masks[2, :] = 1
+    logits = synth.normal_logits(wl.seed, wl.steps, shp.n_experts)
+    wsg = synth.shared_gate_weight(wl.seed, 0, d, dt)
+    wr = synth.router_weight(wl.seed, 0, shp.n_experts, d)
+    for fused in (False, True):
+        worst = _run_layer_steps(ctx, wl, pair, range(wl.steps), masks, None, logits, x_all, fused, wsg=wsg, add_residual=fused)
+        say("  fused", fused, "worst max-abs-rel", worst)
+    worst = _run_layer_steps(ctx, wl, pair, range(1), masks, None, None, x_all, True, wr=wr, wsg=wsg, tau=0.4)
+    say("  router mat-vec, tau 0.4: worst", worst)
+    # several tokens per step agree with the one-token entry point
+    T, k = 3, shp.top_k
+    x = dev(x_all[:T])
+    z = dev(logits[:T])
+    y = B.smoe_decode_layer_multi(ctx, pair.routed, pair.shared, x, k, z, slice_mask=dev(masks[0]), shared_gate_w=dev(wsg))
+    for t in range(T):
+        y1 = B.smoe_decode_layer(ctx, pair.routed, pair.shared, x[t].clone(), k, logits=z[t].clone(), slice_mask=dev(masks[0]),
+                                 shared_gate_w=dev(wsg))
+        assert torch.equal(y[t], y1), t
+
+
 def test_dense_ffn_through_shared_bank(ctx):
     # no routed bank at all: a dense SwiGLU run HIGH; K of the down projection is not a multiple
     # of the group (416 = 3*128 + 32)
