@@ -40,10 +40,12 @@ def _check_routing(ctx, x, wr, k, idx, w, hist, E):
     return ridx, rw
 
 
-@pytest.mark.parametrize("T,E,k,d,f,G", [(200, 6, 2, 256, 128, 64), (37, 5, 3, 128, 192, 32), (450, 3, 1, 128, 64, 64)])
+@pytest.mark.parametrize("T,E,k,d,f,G", [(200, 6, 2, 256, 128, 64), (37, 5, 3, 128, 192, 32), (450, 3, 1, 128, 64, 64),
+                                          (70, 4, 2, 4096, 128, 128)])
 def test_prefill_small_all_tokens(ctx, T, E, k, d, f, G):
     # 200 tokens over 6 experts: one expert tile is ragged; 37 tokens: a single partial fragment;
-    # 450 tokens over 3 experts top-1: some expert gets more than one 192-row tile
+    # 450 tokens over 3 experts top-1: some expert gets more than one 192-row tile; d_model 4096: the
+    # router's activations need more than 64 KB of LDS
     say("prefill small", T, E, k, d, f, G)
     shp = synth.LayerShape(d, E, f, k, G, act="bf16")
     pair = LayerPair(ctx, shp, seed=21)
