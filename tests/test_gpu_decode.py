@@ -428,6 +428,11 @@ def test_argument_errors_on_device(ctx):
     assert call(2, p(x), p(y), None) == -1
     assert lib.smoe_route(ctx.h, 1, 300, 2, 0, p(x), None, 0, None, None, 0, C.c_float(1), None, p(idx), p(w)) == -2
     assert lib.smoe_quantize_slice(ctx.h, pair.routed.h, 3, 2, p(x), p(x), p(x)) == -2
+    # a row of more than four 64-chunk k-slices: valid, not implemented by the decode kernels (no launch)
+    big = B.Bank(ctx, 2, 8192 + 32, 32, 32, "f32", "f32")
+    xb = torch.zeros(8192 + 32, dtype=torch.float32, device="cuda:0")
+    yb = torch.empty_like(xb)
+    assert lib.smoe_expert_ffn(ctx.h, big.h, None, p(xb), 0, 2, p(idx), p(w), None, C.c_float(0), None, 0, p(yb), None) == -6
 
 
 # ------------------------------------------------------------------------------ full-size layer
