@@ -494,6 +494,35 @@ def test_random_small_shapes(ctx):
                              add_residual=bool(case & 1), tau=tau)
 
 
+def test_random_wide_shapes(ctx):
+    # the same kind of sweep over rows of more than 64 chunks (two to four k-slices, the last one ragged
+    # or full), both nests' plane widths included
+    rng = np.random.default_rng(2025)
+    for case in range(8):
+        d = int(rng.choice([2080, 3072, 4128, 5120, 6176, 8192]))
+        G = int(rng.choice([32, 64, 128]))
+        f = int(rng.integers(1, 5)) * 32
+        E = int(rng.integers(2, 9))
+        k = int(rng.integers(1, min(E, 4) + 1))
+        n_sh = int(rng.integers(0, 3))
+        f_s = int(rng.integers(1, 4)) * 32 if n_sh else 0
+        dt = "bf16" if rng.random() < 0.6 else "f32"
+        gate = bool(n_sh and rng.random() < 0.5)
+        bh, bl = [(8, 4), (6, 3), (4, 2)][int(rng.integers(0, 3))]
+        say("random wide shape", case, dict(d=d, G=G, f=f, E=E, k=k, n_sh=n_sh, f_s=f_s, dt=dt, gate=gate, nest=(bh, bl)))
+        shp = synth.LayerShape(d, E, f, k, G, n_shared=n_sh, shared_d_ff=f_s, shared_gate=gate, act=dt, b_high=bh, b_low=bl)
+        wl = synth.Workload("randw%d" % case, shp, steps=2, seed=300 + case)
+        pair = LayerPair(ctx, shp, seed=wl.seed)
+        x_all = synth.activations(wl.seed, wl.steps, d, dt)
+        masks = synth.bernoulli_masks(wl.seed, wl.steps, E)
+        logits = synth.normal_logits(wl.seed, wl.steps, E)
+        wsg = synth.shared_gate_weight(wl.seed, 0, d, dt, std=0.05) if gate else None
+        tau = float(rng.choice([0.0, 0.25]))
+        for fused in (False, True):
+            _run_layer_steps(ctx, wl, pair, range(wl.steps), masks, None, logits, x_all, fused, wsg=wsg,
+                             add_residual=bool(case & 1), tau=tau)
+
+
 def test_decode_steps_replay_from_a_hip_graph():
     # a serving loop can record its decode calls once and replay them: every call only enqueues two
     # kernels on the context's stream.  Four steps are captured on a side stream, replayed three times
