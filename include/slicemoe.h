@@ -116,7 +116,9 @@ int smoe_export_codes(smoe_ctx* ctx, const smoe_bank* bank, int expert, int matr
  * accumulation); score = z + bias (bias_dev fp32 [E] or NULL = 0); idx_dev[t,0..k) = the k largest
  * scores from the highest down, equal scores to the lower index; w_dev[t,j] = softmax(z)[idx]
  * (unbiased logits), divided by their sum if norm_topk, times routed_scale.  logits_out_dev
- * (fp32 [T,E], may be NULL) receives z.  E <= 256, k <= 16. */
+ * (fp32 [T,E], may be NULL) receives z.  E <= 256, k <= 16.  With the mat-vec a work-group keeps the
+ * activations of eight (bf16) or four (fp32) tokens in LDS: SMOE_ESIZE if they exceed 160 KB (bf16
+ * d_model above about 9000, fp32 above about 8000). */
 int smoe_route(smoe_ctx* ctx, int T, int E, int k, int d_model, const float* logits_dev,
                const void* x_dev, int act_dtype, const float* w_router_dev, const float* bias_dev,
                int norm_topk, float routed_scale, float* logits_out_dev, int32_t* idx_dev,
