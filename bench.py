@@ -46,11 +46,12 @@ def main():
     ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64, 128],
                     help="decode: quantisation group of the expert weights (default: the workload's 128; 32 is the "
                          "paper's expert format, with four times the scales and zero-points)")
-    ap.add_argument("--shape", choices=["dsv2", "qwen", "wide"], default="dsv2",
+    ap.add_argument("--shape", choices=["dsv2", "qwen", "wide", "tiny"], default="dsv2",
                     help="decode: dsv2 = the headline DeepSeek-V2-Lite-shaped layer; qwen = one Qwen1.5-MoE-shaped layer "
                          "(60 experts top-4, one shared expert of d_ff 5632 behind a sigmoid gate, 18 experts HIGH, all "
                          "MSB slices resident), reported as its own line; wide = d_model 4096 (16 experts of d_ff 2048, top-4, one "
-                         "shared expert: rows of two 64-chunk k-slices, the wide gate/up kernel)")
+                         "shared expert: rows of two 64-chunk k-slices, the wide gate/up kernel); tiny = the fp32 correctness "
+                         "layer (BASELINE configs[0]: d_model 256, 8 experts of d_ff 128, top-2, group 64), launch-bound")
     ap.add_argument("--router-matvec", action="store_true",
                     help="decode (one token per step): logits from the router mat-vec W_r x (a third launch) instead of "
                          "supplied logits")
@@ -93,6 +94,8 @@ def main():
     if args.shape == "qwen":
         import dataclasses
         wl = dataclasses.replace(synth.QWEN_STACK, n_layers=1, steps=1024)
+    if args.shape == "tiny":
+        wl = synth.TINY
     if args.shape == "wide":
         wl = synth.Workload("wide-layer", synth.LayerShape(4096, 16, 2048, 4, 128, n_shared=1, shared_d_ff=2048), steps=256)
     if args.group:
@@ -101,28 +104,34 @@ def main():
     shp = wl.layer
     dev = "cuda:0"
     ctx = B.Ctx(0)
-    routed = B.Bank(ctx, shp.n_experts, shp.d_model, shp.d_ff, shp.group, "bf16", "bf16", bh, bl)
-    shared = B.Bank(ctx, shp.n_shared, shp.d_model, shp.shared_d_ff, shp.group, "bf16", "bf16", bh, bl)
+    adt = shp.act                                   # activation and scale dtype of the workload
+    ADT, asz = B._DT[adt], (4 if adt == "f32" else 2)
+    routed = B.Bank(ctx, shp.n_experts, shp.d_model, shp.d_ff, shp.group, adt, adt, bh, bl)
+    shared = B.Bank(ctx, shp.n_shared, shp.d_model, shp.shared_d_ff, shp.group, adt, adt, bh, bl) if shp.n_shared else None
+    shared_h = shared.h if shared is not None else None
     for e in range(shp.n_experts):
-        wg, wu, wd = synth.expert_weights(wl.seed, 0, e, shp.d_model, shp.d_ff, "bf16", dev)
+        wg, wu, wd = synth.expert_weights(wl.seed, 0, e, shp.d_model, shp.d_ff, adt, dev)
         B.smoe_quantize_slice(ctx, routed, e, wg[None], wu[None], wd[None])
     for i in range(shp.n_shared):
-        wg, wu, wd = synth.expert_weights(wl.seed, 0, 1000 + i, shp.d_model, shp.shared_d_ff, "bf16", dev)
+        wg, wu, wd = synth.expert_weights(wl.seed, 0, 1000 + i, shp.d_model, shp.shared_d_ff, adt, dev)
         B.smoe_quantize_slice(ctx, shared, i, wg[None], wu[None], wd[None])
     n_in = wl.steps
-    x_all = synth.activations(wl.seed, n_in, shp.d_model, "bf16").to(dev)
+    x_all = synth.activations(wl.seed, n_in, shp.d_model, adt).to(dev)
     z_all = synth.normal_logits(wl.seed, n_in, shp.n_experts).to(dev)
     if args.shape == "qwen":
         mask_np = synth.fraction_masks(wl.seed, 1, 0, shp.n_experts, 0.3)[0]
         bias_np = np.zeros(shp.n_experts, np.float32)
     elif args.shape == "wide":
         mask_np, bias_np = synth.cached_set_mask(wl.seed, shp.n_experts, 8, 4, 1.0)
+    elif args.shape == "tiny":
+        mask_np = synth.bernoulli_masks(wl.seed, 1, shp.n_experts)[0]
+        bias_np = np.zeros(shp.n_experts, np.float32)
     else:
         mask_np, bias_np = synth.cached_set_mask(wl.seed, shp.n_experts, 32, 16, 1.0)
     mask = torch.from_numpy(mask_np).to(dev)
     bias = torch.from_numpy(bias_np).to(dev)
-    wsg = synth.shared_gate_weight(wl.seed, 0, shp.d_model, "bf16").to(dev) if shp.shared_gate else None
-    y = torch.empty((n_in, shp.d_model), dtype=torch.bfloat16, device=dev)
+    wsg = synth.shared_gate_weight(wl.seed, 0, shp.d_model, adt).to(dev) if shp.shared_gate else None
+    y = torch.empty((n_in, shp.d_model), dtype=x_all.dtype, device=dev)
     prec = torch.zeros((n_in, shp.top_k), dtype=torch.uint8, device=dev)
     idx = torch.zeros((n_in, shp.top_k), dtype=torch.int32, device=dev)
     torch.cuda.synchronize()
@@ -134,7 +143,7 @@ def main():
     TT = args.tokens
     wr = synth.router_weight(wl.seed, 0, shp.n_experts, shp.d_model).to(dev) if args.router_matvec else None
     if TT == 1:
-        calls = [(ctx.h, routed.h, shared.h, vp(x_all[i]), C.c_int(B.BF16), C.c_int(shp.top_k),
+        calls = [(ctx.h, routed.h, shared_h, vp(x_all[i]), C.c_int(ADT), C.c_int(shp.top_k),
                   None if wr is not None else vp(z_all[i]), vp(wr) if wr is not None else None,
                   vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), vp(wsg) if wsg is not None else None,
                   C.c_int(0), vp(y[i]), vp(idx[i]), None, vp(prec[i])) for i in range(n_in)]
@@ -142,7 +151,7 @@ def main():
         # step t takes the TT consecutive tokens that start at row (t * TT) mod n_in
         assert 2 <= TT <= 16 and n_in % TT == 0
         fn = B.lib().smoe_decode_layer_multi
-        calls = [(ctx.h, routed.h, shared.h, C.c_int(TT), vp(x_all[i]), C.c_int(B.BF16), C.c_int(shp.top_k), vp(z_all[i]),
+        calls = [(ctx.h, routed.h, shared_h, C.c_int(TT), vp(x_all[i]), C.c_int(ADT), C.c_int(shp.top_k), vp(z_all[i]),
                   vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), vp(wsg) if wsg is not None else None,
                   C.c_int(0), vp(y[i]), vp(idx[i]), None, vp(prec[i])) for i in range(0, n_in, TT)]
     n_calls = len(calls)
@@ -204,9 +213,9 @@ def main():
 
     # algorithmic bytes of exactly the timed steps, from the precision flags the kernels reported
     prec_np = prec.cpu().numpy()
-    hi_gu, hi_dn = slot_bytes(shp.d_model, shp.d_ff, shp.group, 1)
-    lo_gu, lo_dn = slot_bytes(shp.d_model, shp.d_ff, shp.group, 0)
-    sh_gu, sh_dn = slot_bytes(shp.d_model, shp.shared_d_ff, shp.group, 1)
+    hi_gu, hi_dn = slot_bytes(shp.d_model, shp.d_ff, shp.group, 1, asz)
+    lo_gu, lo_dn = slot_bytes(shp.d_model, shp.d_ff, shp.group, 0, asz)
+    sh_gu, sh_dn = slot_bytes(shp.d_model, shp.shared_d_ff, shp.group, 1, asz) if shp.n_shared else (0, 0)
     sh_gu, sh_dn = sh_gu * shp.n_shared, sh_dn * shp.n_shared
     total_bytes = gu_bytes = 0
     idx_np = idx.cpu().numpy()
@@ -224,8 +233,8 @@ def main():
                     need[int(e)] = max(need.get(int(e), 0), int(p))
             nh = sum(need.values())
             nl = len(need) - nh
-        gu = sh_gu + nh * hi_gu + nl * lo_gu + TT * (shp.d_model * 2 + shp.n_experts * 9)
-        dn = sh_dn + nh * hi_dn + nl * lo_dn + TT * shp.d_model * 2
+        gu = sh_gu + nh * hi_gu + nl * lo_gu + TT * (shp.d_model * asz + shp.n_experts * 9)
+        dn = sh_dn + nh * hi_dn + nl * lo_dn + TT * shp.d_model * asz
         gu_bytes += gu
         total_bytes += gu + dn
     bytes_per_step = total_bytes / args.steps
@@ -237,10 +246,12 @@ def main():
         "metric": "decode MoE-layer us/token (+ achieved HBM GB/s as a fraction of MI355X peak)",
         "value": ms_per_step * 1e3 / TT, "unit": "us/token", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u%d+u%d bit-sliced weights, bf16 activations rewritten per 32-chunk as 3 balanced hex digits, signed 4-bit dot products, int32/fp32 accumulate" % (bl, bl),
+        "dtype": ("u%d+u%d bit-sliced weights, bf16 activations rewritten per 32-chunk as 3 balanced hex digits, signed 4-bit dot products, int32/fp32 accumulate" % (bl, bl)
+                  if adt == "bf16" else "u%d+u%d bit-sliced weights, fp32 activations and scales, fp32 multiply-add" % (bl, bl)),
         "data": "synthetic",
         "config": {"workload": ("DeepSeek-V2-Lite-shaped MoE layer decode, %d token%s/step (BASELINE configs[1])" if args.shape == "dsv2" else
                                 "d_model-4096 MoE layer decode, %d token%s/step (no BASELINE config: the wide-row kernel)" if args.shape == "wide" else
+                                "tiny fp32 MoE layer decode, %d token%s/step (BASELINE configs[0]; launch-bound)" if args.shape == "tiny" else
                                 "Qwen1.5-MoE-shaped MoE layer decode, %d token%s/step (one layer of BASELINE configs[2])") % (TT, "" if TT == 1 else "s"),
                    "d_model": shp.d_model, "n_experts": shp.n_experts, "d_ff": shp.d_ff, "top_k": shp.top_k,
                    "n_shared": shp.n_shared, "shared_d_ff": shp.shared_d_ff, "group": shp.group, "nest": "%d/%d" % (bh, bl),
@@ -251,10 +262,10 @@ def main():
         "host_wall_ms_per_step": wall_ms / args.steps,
         "repeat_windows_us_per_token": {"median": windows[2], "min": windows[0], "max": windows[-1], "n": 5},
         "copy_256mib_gbps": copy_gbps,
-        "roofline": {"bound": "hbm", "kernel": "gateup_kernel<bf16> (route + gate/up + SwiGLU of all 8 slots)",
+        "roofline": {"bound": "hbm", "kernel": "gateup_kernel<%s> (route + gate/up + SwiGLU of all %d slots)" % (adt, shp.top_k + shp.n_shared),
                      "achieved": gu_achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gu_achieved / HBM_PEAK_GBPS,
                      "bytes_per_launch": gu_bytes_per_launch, "avg_launch_us": gu_us,
-                     "other_kernel": {"kernel": "down_kernel<bf16>", "avg_launch_us": dn_us,
+                     "other_kernel": {"kernel": "down_kernel<%s>" % adt, "avg_launch_us": dn_us,
                                       "bytes_per_launch": bytes_per_step - gu_bytes_per_launch,
                                       "achieved": (bytes_per_step - gu_bytes_per_launch) / (dn_us * 1e-6) / 1e9},
                      "timing": "start/stop HIP events attached to every dispatch on the launch stream, second pass over the same steps",
