@@ -854,7 +854,7 @@ template <int ACT> struct WideTraits;
 template <> struct WideTraits<SMOE_BF16> { enum { SLICE_BYTES = 4096 }; };      // the k-slice stride of stage_regs / load_xr
 template <> struct WideTraits<SMOE_F32> { enum { SLICE_BYTES = 8192 }; };
 
-template <int ACT, int SCB, int FMT>
+template <int ACT, int SCB, int FMT, int NKS>      // NKS: k-slices a lane has registers for (2: d_model <= 4096, else 4)
 __global__ __launch_bounds__(DEC_NT) void gateup_wide_kernel(const float* logits, const float* bias, const uint8_t* mask, const void* x_in,
                                                              int E, int k, int do_route, int d_model, int n_wg, int n_se,
                                                              DecodeArgs a) {
@@ -945,10 +945,10 @@ __global__ __launch_bounds__(DEC_NT) void gateup_wide_kernel(const float* logits
     const unsigned zo = (unsigned)ex * md.zs32 + (unsigned)(2 * r0) * (unsigned)md.ng;
     const unsigned sb = (unsigned)md.sng * (SCB ? 2u : 4u);
     const unsigned so = (unsigned)ex * md.ss32 + (unsigned)(2 * r0) * sb;
-    typename PlaneT<FMT>::t gm[DEC_WIDE_KS], um[DEC_WIDE_KS], gl[DEC_WIDE_KS], ul[DEC_WIDE_KS];
-    uint32_t zg[DEC_WIDE_KS], zu[DEC_WIDE_KS], sg[DEC_WIDE_KS], su[DEC_WIDE_KS];
+    typename PlaneT<FMT>::t gm[NKS], um[NKS], gl[NKS], ul[NKS];
+    uint32_t zg[NKS], zu[NKS], sg[NKS], su[NKS];
 #pragma unroll
-    for (int ks = 0; ks < DEC_WIDE_KS; ks++) {
+    for (int ks = 0; ks < NKS; ks++) {
       const unsigned c = (unsigned)(ks * 64 + lane), gi = c >> sh;
       const bool live = ks < KS && c < (unsigned)C;
       const unsigned vz = live ? gi : DEC_OOB, vs = live ? (SCB ? (gi >> 1) << 2 : gi << 2) : DEC_OOB;
@@ -964,7 +964,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_wide_kernel(const float* logits
     }
     float av = 0.0f, uv = 0.0f;
 #pragma unroll
-    for (int ks = 0; ks < DEC_WIDE_KS; ks++) {
+    for (int ks = 0; ks < NKS; ks++) {
       if (ks < KS) {                                        // wave-uniform
         const int cw = min(64, C - ks * 64);
         const int odd = SCB ? (((ks * 64 + lane) >> sh) & 1) : 0;
@@ -1164,8 +1164,11 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
     // measurement aid: the dispatches themselves carry start/stop events (no extra marker packets)
     hipEvent_t ev[4];
     for (int i = 0; i < 4; i++) { HIPCHK(ctx, hipEventCreate(&ev[i])); evs->push_back(ev[i]); }
-    if (wide)
-      hipExtLaunchKernelGGL((gateup_wide_kernel<ACT, SCB, FMT>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
+    if (wide && a.d_model <= 4096)
+      hipExtLaunchKernelGGL((gateup_wide_kernel<ACT, SCB, FMT, 2>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
+                            in.E, in.k, in.do_route, a.d_model, n_wg, n_se, a);
+    else if (wide)
+      hipExtLaunchKernelGGL((gateup_wide_kernel<ACT, SCB, FMT, DEC_WIDE_KS>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
                             in.E, in.k, in.do_route, a.d_model, n_wg, n_se, a);
     else
       hipExtLaunchKernelGGL((gateup_kernel<ACT, SCB, FMT>), g1, blk, 0, ctx->stream, ev[0], ev[1], 0, in.logits, in.bias, in.mask, a.x,
@@ -1173,9 +1176,12 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
     hipExtLaunchKernelGGL((down_kernel<ACT, SCB, FMT, RPW>), g2, blk, (unsigned)lds, ctx->stream, ev[2], ev[3], 0, recw, (const float*)a.h,
                           n_combo_s, n_pieces, psh, a.f_s, a.f_r, a.ks_s, a.ks_r, a.inv_ks_s, a.inv_ks_r, nsf, a);
   } else {
-    if (wide)
-      gateup_wide_kernel<ACT, SCB, FMT><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, n_wg,
-                                                                n_se, a);
+    if (wide && a.d_model <= 4096)
+      gateup_wide_kernel<ACT, SCB, FMT, 2><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model,
+                                                                   n_wg, n_se, a);
+    else if (wide)
+      gateup_wide_kernel<ACT, SCB, FMT, DEC_WIDE_KS><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route,
+                                                                             a.d_model, n_wg, n_se, a);
     else
       gateup_kernel<ACT, SCB, FMT><<<g1, blk, 0, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model, n_wg, n_se,
                                                            a);
