@@ -45,7 +45,7 @@ typedef enum {
 
 enum { SMOE_F32 = 0, SMOE_BF16 = 1 };
 
-typedef struct smoe_ctx smoe_ctx;     /* host object: device id, stream, small device workspace */
+typedef struct smoe_ctx smoe_ctx;     /* host object: device id, stream, borrowed device workspace */
 typedef struct smoe_bank smoe_bank;   /* host object describing one sliced expert store in HBM */
 typedef struct smoe_cache smoe_cache; /* host-only slice LRU */
 
@@ -61,7 +61,7 @@ typedef struct {
   int32_t w_dtype;      /* dtype of the source weights handed to smoe_quantize_slice */
   int32_t scale_dtype;  /* dtype the per-group scales are stored in (and rounded to) */
   int32_t symmetric;    /* 0: asymmetric min-max quantiser (the experts, Table 1 note 1).  1: symmetric
-                         * quantiser (Section 5: the non-expert weights are symmetric INT8) in the same
+                         * quantiser (Section 6.1 item 1: the non-expert weights are symmetric INT8) in the same
                          * store: zero-point fixed at 2^(b_high-1); see smoe_quantize_slice.  Other
                          * values: SMOE_EINVAL. */
 } smoe_bank_desc;
@@ -71,10 +71,17 @@ typedef struct {
 } smoe_cache_stats;
 
 /* ---- context ---------------------------------------------------------------------------- */
-/* Creates a context bound to `device` and to `hip_stream` (a hipStream_t, NULL = default
- * stream).  Allocates a fixed 4 MiB device workspace (routing record, SwiGLU intermediates); this
- * is the only device allocation the library ever makes.  smoe_ctx_destroy frees it. */
-int smoe_ctx_create(int device, void* hip_stream, smoe_ctx** out);
+/* Bytes of device workspace a context needs for decode calls of up to `tokens` tokens (1..16) through
+ * layers of at most k routed slots of d_ff and n_shared shared experts of shared_d_ff: the routing
+ * records (64 KiB reserved) plus the fp32 SwiGLU vectors of every token. */
+int smoe_workspace_bytes(int tokens, int k, int d_ff, int n_shared, int shared_d_ff, size_t* bytes);
+/* Creates a context bound to `device`, to `hip_stream` (a hipStream_t, NULL = default stream) and
+ * to `workspace_dev`, caller-owned device memory of workspace_bytes (256-byte aligned, at least
+ * smoe_workspace_bytes of the largest layer it will see; SMOE_ESIZE below 64 KiB, and later from a
+ * decode call whose intermediates do not fit).  The library itself never allocates or frees device
+ * memory; the workspace is borrowed until smoe_ctx_destroy and is shared by all calls of the context,
+ * which therefore must not overlap in time (one stream). */
+int smoe_ctx_create(int device, void* hip_stream, void* workspace_dev, size_t workspace_bytes, smoe_ctx** out);
 int smoe_ctx_destroy(smoe_ctx* ctx);
 const char* smoe_strerror(int status);
 int smoe_last_hip_error(const smoe_ctx* ctx); /* hipError_t of the last failing HIP call, else 0 */
@@ -133,6 +140,8 @@ int smoe_route(smoe_ctx* ctx, int T, int E, int k, int d_model, const float* log
  * given.  `routed` may be NULL with k = 0 (dense FFN through `shared`); `shared` may be NULL.
  * x_dev, y_dev: act_dtype [d_model]; idx_dev int32 [k]; w_dev fp32 [k]; slice_mask_dev uint8 [E];
  * prec_out_dev uint8 [k] or NULL.  y_dev may not alias x_dev.
+ * idx_dev lives in device memory, so the host cannot validate it: an index outside [0, n_experts)
+ * is clamped to the nearest valid expert by the kernel (no error, no access outside the bank).
  * Limits of the decode entry points: d_model <= 8192 (SMOE_ENOTIMPL beyond) and a multiple of 8,
  * group = 32 * 2^n, k <= 16, at most 8 shared experts, one scale dtype and one nest per layer, and
  * k * d_ff + n_shared * shared_d_ff floats of intermediates within the ctx workspace (SMOE_ESIZE). */
@@ -192,7 +201,7 @@ int smoe_prefill_histogram(smoe_ctx* ctx, const smoe_bank* routed, const smoe_ba
 int smoe_topn_slices(const uint32_t* hist_host, int L, int E, int N, uint32_t* slice_ids_host,
                      int* n_out);
 
-/* ---- host bookkeeping that produces the mask (Sections 4.1, 5.1-3); no device work -------- */
+/* ---- host bookkeeping that produces the mask (Section 4.1; Section 6.1 item 3); no device work -------- */
 /* One LRU over the slices of all layers; capacity in slices (>= 2). */
 int smoe_cache_create(int L, int E, int capacity_slices, smoe_cache** out);
 int smoe_cache_destroy(smoe_cache* c);

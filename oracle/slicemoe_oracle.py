@@ -22,7 +22,7 @@ Paper passages followed (SliceMoE, arXiv 2512.12990):
   * Section 4.3: prefill accumulates per-expert access frequency; LSB slices go
     first, then MSB slices with low prefill frequency; the cache order at the
     start of decode follows accumulated frequency.
-  * Section 5.1 item 3: one LRU cache shared by all layers.
+  * Section 6.1 item 3: one LRU cache shared by all layers.
 
 Parity status: every function below is pinned by tests/test_oracle_*.py against
 closed forms, exhaustive integer identities, brute force on tiny inputs or a
@@ -115,7 +115,7 @@ class QMat:
 
 
 def _quant_groups_symmetric(Wg: np.ndarray, qmax: int, scale_dtype: str):
-    """Symmetric variant (Section 5 set-up: the non-expert weights are symmetric INT8): the
+    """Symmetric variant (Section 6.1 item 1: the non-expert weights are symmetric INT8): the
     signed code c = rint(w / s) with s = max|w| / (2^(b-1) - 1), kept in the same unsigned
     store as c + 2^(b-1), i.e. with the zero-point fixed at mid-range."""
     Wg = Wg.astype(np.float32)
@@ -335,7 +335,7 @@ def topn_slices(hist, n: int) -> np.ndarray:
 # slice cache (host bookkeeping that produces the mask)
 # --------------------------------------------------------------------------
 class SliceLRU:
-    """Unified slice-level cache over all layers (Sections 4.1 and 5.1-3).
+    """Unified slice-level cache over all layers (Section 4.1; Section 6.1 item 3).
 
     `order` lists resident slice ids from most- to least-recently used.
     MSB request: hit -> move to front; miss -> fetch, insert at front.

@@ -45,7 +45,7 @@ class Cost(C.Structure):
 _lib = None
 
 EXPORTS = [
-    "smoe_ctx_create", "smoe_ctx_destroy", "smoe_strerror", "smoe_last_hip_error", "smoe_ctx_timing",
+    "smoe_workspace_bytes", "smoe_ctx_create", "smoe_ctx_destroy", "smoe_strerror", "smoe_last_hip_error", "smoe_ctx_timing",
     "smoe_ctx_timing_read",
     "smoe_bank_bytes", "smoe_bank_create", "smoe_bank_destroy", "smoe_quantize_slice", "smoe_export_codes",
     "smoe_route", "smoe_expert_ffn", "smoe_decode_layer", "smoe_decode_layer_multi",
@@ -85,13 +85,25 @@ def _p(t: Optional[torch.Tensor]):
     return C.c_void_p(t.data_ptr())
 
 
+def smoe_workspace_bytes(tokens: int, k: int, d_ff: int, n_shared: int = 0, shared_d_ff: int = 0) -> int:
+    n = C.c_size_t()
+    _chk(lib().smoe_workspace_bytes(C.c_int(tokens), C.c_int(k), C.c_int(d_ff), C.c_int(n_shared), C.c_int(shared_d_ff),
+                                    C.byref(n)), "smoe_workspace_bytes")
+    return n.value
+
+
 class Ctx:
-    def __init__(self, device: int = 0, stream: Optional[torch.cuda.Stream] = None):
+    """A library context; the torch tensor `workspace` owns the device workspace it borrows."""
+
+    def __init__(self, device: int = 0, stream: Optional[torch.cuda.Stream] = None, workspace_bytes: int = 4 << 20):
         self.device = device
         s = stream if stream is not None else torch.cuda.current_stream(device)
         self._stream = s
+        self.workspace = torch.empty(workspace_bytes + 256, dtype=torch.uint8, device="cuda:%d" % device)
+        base = self.workspace.data_ptr() + (-self.workspace.data_ptr()) % 256
         self.h = C.c_void_p()
-        _chk(lib().smoe_ctx_create(C.c_int(device), C.c_void_p(s.cuda_stream), C.byref(self.h)), "smoe_ctx_create")
+        _chk(lib().smoe_ctx_create(C.c_int(device), C.c_void_p(s.cuda_stream), C.c_void_p(base),
+                                   C.c_size_t(workspace_bytes), C.byref(self.h)), "smoe_ctx_create")
 
     def timing(self, enable: bool):
         _chk(lib().smoe_ctx_timing(self.h, C.c_int(int(enable))), "smoe_ctx_timing")

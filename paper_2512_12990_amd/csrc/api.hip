@@ -17,16 +17,30 @@ extern "C" const char* smoe_strerror(int status) {
   }
 }
 
-extern "C" int smoe_ctx_create(int device, void* hip_stream, smoe_ctx** out) {
-  if (!out || device < 0) return SMOE_EINVAL;
+extern "C" int smoe_workspace_bytes(int tokens, int k, int d_ff, int n_shared, int shared_d_ff, size_t* bytes) {
+  if (!bytes) return SMOE_EINVAL;
+  if (tokens < 1 || tokens > SMOE_MAX_MULTI || k < 0 || k > SMOE_MAX_TOPK || n_shared < 0 || n_shared > SMOE_MAX_SLOTS - SMOE_MAX_TOPK ||
+      d_ff < 0 || shared_d_ff < 0)
+    return SMOE_ESHAPE;
+  // one token: its k + n_shared SwiGLU vectors; several tokens: vectors a fixed stride apart (room for the largest top-k)
+  const size_t nsf = (size_t)n_shared * (size_t)shared_d_ff;
+  const size_t floats = tokens > 1 ? (size_t)tokens * (nsf + (size_t)SMOE_MAX_TOPK * (size_t)d_ff) : nsf + (size_t)k * (size_t)d_ff;
+  *bytes = (size_t)WS_H_OFF + ((floats * 4 + 255) & ~(size_t)255);
+  return SMOE_OK;
+}
+
+extern "C" int smoe_ctx_create(int device, void* hip_stream, void* workspace_dev, size_t workspace_bytes, smoe_ctx** out) {
+  if (!out || device < 0 || !workspace_dev) return SMOE_EINVAL;
   *out = nullptr;
+  if (((uintptr_t)workspace_dev) & 255u) return SMOE_EALIGN;
+  if (workspace_bytes < (size_t)WS_H_OFF) return SMOE_ESIZE;
   smoe_ctx* c = new (std::nothrow) smoe_ctx();
   if (!c) return SMOE_EINVAL;
-  c->device = device; c->stream = (hipStream_t)hip_stream; c->ws = nullptr; c->last_hip = 0; c->n_cu = 256; c->timing = 0; c->timing_events = nullptr;
+  c->device = device; c->stream = (hipStream_t)hip_stream; c->ws = (uint8_t*)workspace_dev; c->ws_bytes = workspace_bytes;
+  c->last_hip = 0; c->n_cu = 256; c->timing = 0; c->timing_events = nullptr;
   for (size_t& g : c->down_lds_granted) g = 0;
   for (size_t& g : c->route_lds_granted) g = 0;
   hipError_t e = hipSetDevice(device);
-  if (e == hipSuccess) e = hipMalloc((void**)&c->ws, SMOE_WORKSPACE_BYTES);
   if (e == hipSuccess) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
@@ -39,7 +53,6 @@ extern "C" int smoe_ctx_create(int device, void* hip_stream, smoe_ctx** out) {
 
 extern "C" int smoe_ctx_destroy(smoe_ctx* ctx) {
   if (!ctx) return SMOE_EINVAL;
-  if (ctx->ws) { (void)hipSetDevice(ctx->device); (void)hipFree(ctx->ws); }
   if (ctx->timing_events) {
     std::vector<hipEvent_t>* ev = (std::vector<hipEvent_t>*)ctx->timing_events;
     for (hipEvent_t e : *ev) (void)hipEventDestroy(e);
@@ -114,8 +127,8 @@ static size_t layout(const smoe_bank_desc* d, BankDev* b, MatOff* ogu, MatOff* o
     m[i]->ps32 = (unsigned)m[i]->plane_stride; m[i]->zs32 = (unsigned)m[i]->zp_stride; m[i]->ss32 = (unsigned)m[i]->sc_stride;
     m[i]->fits32 = (E * m[i]->plane_stride < 0x7FFF0000ull) ? 1u : 0u;
   }
-  // MSB planes of both families first, then LSB planes, then metadata: a low-bit read never
-  // touches the LSB region.
+  // MSB planes of both families first, then zero-points, then scales, then the LSB planes: a
+  // low-bit read never touches the LSB region.
   for (int i = 0; i < 2; i++) { o[i]->msb = off; off = up256(off + E * m[i]->plane_stride); }
   for (int i = 0; i < 2; i++) { o[i]->zp = off; off = up256(off + E * m[i]->zp_stride); }
   for (int i = 0; i < 2; i++) { o[i]->sc = off; off = up256(off + E * m[i]->sc_stride); }

@@ -9,7 +9,6 @@
 #define SMOE_MAX_EXPERTS 256
 #define SMOE_MAX_MULTI 16          // tokens of one smoe_decode_layer_multi call
 #define SMOE_MAX_TOPK 16
-#define SMOE_WORKSPACE_BYTES (4u << 20)
 
 // ---- host objects -------------------------------------------------------------------------
 // Device view of one quantised matrix family inside a bank ("gu": gate and up rows interleaved,
@@ -38,7 +37,8 @@ struct BankDev {
 struct smoe_ctx {
   int device;
   hipStream_t stream;
-  uint8_t* ws;          // SMOE_WORKSPACE_BYTES of device memory
+  uint8_t* ws;          // the caller's device workspace (borrowed): routing records, router logits, SwiGLU vectors
+  size_t ws_bytes;
   int last_hip;
   int n_cu;
   // measurement aid (smoe_ctx_timing): events around the two decode launches of every call

@@ -27,6 +27,7 @@
 //   HIGH  (s sx) * (16 m'.q + l'.q + (136 - zp) X)      LOW  (16 s sx) * (m'.q + (8 - (zp >> 4)) X)
 // fp32 activations take a plain fp32 path (byte -> float conversions and FMAs).
 #include "route_device.hpp"
+#include "fastdiv.hpp"
 #include <hip/hip_ext.h>
 #include <vector>
 
@@ -54,7 +55,7 @@ struct DecodeArgs {
   float routed_scale, tau;
   int norm_topk;
   int cap_r, cap_s;                // gate/up: row pairs per work-group and slot = ceil(f / n_wg)
-  int inv_cap_r, inv_cap_s;        // ceil(65536 / cap)
+  uint32_t inv_cap_r, inv_cap_s;   // fastdiv_magic(cap): slot of entry e = fastdiv(e, inv_cap)
   int rot;                         // gate/up: per-slot rotation of the work-group index
   int gu_L;                        // gate/up: entries per wave
   int gu_sh_r, gu_sh_s;            // log2(32-column chunks per quantisation group), gate/up families
@@ -66,7 +67,7 @@ struct DecodeArgs {
   int f_r, f_s;                    // d_ff of the routed / shared bank (0 if absent)
   void* y;                         //                                                     [down kernel]
   MatK rdn, sdn;                   // down families
-  int ks_r, ks_s, inv_ks_r, inv_ks_s;   // down: 64-chunk k-slices per row, ceil(65536 / ks)
+  int ks_r, ks_s, inv_ks_r, inv_ks_s;   // down: 64-chunk k-slices per row, fastdiv_magic(ks)
   int dn_sh_r, dn_sh_s;
   int add_residual;
   int d_model;                     // host side only (the kernels get it as a leading parameter)
@@ -775,7 +776,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
   GuPiece pc0 = {};
   const bool pre = e_lo < min(e_hi, n_se);
   if (pre) {
-    const int s = (e_cur * a.inv_cap_s) >> 16, q0 = e_cur - s * a.cap_s;
+    const int s = fastdiv(e_cur, a.inv_cap_s), q0 = e_cur - s * a.cap_s;
     nb0 = uni(min(DEC_MAXP, min(min(e_hi, n_se) - e_cur, a.cap_s - q0)));
     pc0 = setup(true, s, q0, s, 1, a.sgu);
     issue(pc0, nb0, a.f_s, make_sec(a.sgu, a.n_shared), a.sgu, a.gu_sh_s);
@@ -825,7 +826,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
   // ---- everything else, batch by batch
   while (e_cur < e_hi) {
     if (e_cur < n_se) {
-      const int s = (e_cur * a.inv_cap_s) >> 16, q0 = e_cur - s * a.cap_s;
+      const int s = fastdiv(e_cur, a.inv_cap_s), q0 = e_cur - s * a.cap_s;
       const int nb = uni(min(DEC_MAXP, min(min(e_hi, n_se) - e_cur, a.cap_s - q0)));
       const GuPiece pc = setup(true, s, q0, s, 1, a.sgu);
       issue(pc, nb, a.f_s, make_sec(a.sgu, a.n_shared), a.sgu, a.gu_sh_s);
@@ -833,7 +834,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
       e_cur = uni(e_cur + nb);
     } else {
       const int er = e_cur - n_se;
-      const int sr = (er * a.inv_cap_r) >> 16, q0 = er - sr * a.cap_r;
+      const int sr = fastdiv(er, a.inv_cap_r), q0 = er - sr * a.cap_r;
       const int nb = uni(min(DEC_MAXP, min(e_hi - e_cur, a.cap_r - q0)));
       const GuPiece pc = setup(false, a.n_shared + sr, q0, uni(sel_lds[sr]), uni(prec_lds[sr]), a.rgu);
       issue(pc, nb, a.f_r, make_sec(a.rgu, E), a.rgu, a.gu_sh_r);
@@ -930,9 +931,9 @@ __global__ __launch_bounds__(DEC_NT) void gateup_wide_kernel(const float* logits
     const bool is_sh = e_cur < n_se;
     int s, q0, ex, prec, f, sh;
     if (is_sh) {
-      s = (e_cur * a.inv_cap_s) >> 16; q0 = e_cur - s * a.cap_s; ex = s; prec = 1; f = a.f_s; sh = a.gu_sh_s;
+      s = fastdiv(e_cur, a.inv_cap_s); q0 = e_cur - s * a.cap_s; ex = s; prec = 1; f = a.f_s; sh = a.gu_sh_s;
     } else {
-      const int er = e_cur - n_se, sr = (er * a.inv_cap_r) >> 16;
+      const int er = e_cur - n_se, sr = fastdiv(er, a.inv_cap_r);
       s = a.n_shared + sr; q0 = er - sr * a.cap_r; ex = uni(sel_lds[sr]); prec = uni(prec_lds[sr]); f = a.f_r; sh = a.gu_sh_r;
     }
     const MatK& md = is_sh ? a.sgu : a.rgu;
@@ -1032,7 +1033,7 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
     const bool is_sh = combo < n_combo_s;
     const int c2 = is_sh ? combo : combo - n_combo_s;
     const int ksn = is_sh ? ks_s : ks_r, inv_ks = is_sh ? inv_ks_s : inv_ks_r, f = is_sh ? f_s : f_r;
-    const int slot = (c2 * inv_ks) >> 16, ks = c2 - slot * ksn;
+    const int slot = fastdiv(c2, (uint32_t)inv_ks), ks = c2 - slot * ksn;
     const int cw = min(64, (f >> 5) - ks * 64);
     const int hoff = (is_sh ? 0 : nsf) + slot * f + ks * 2048;      // first h value of the combo
     // ---- first loads: the combo's h values (8 per lane and word, words past the combo read nothing)
@@ -1192,8 +1193,9 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
   return SMOE_OK;
 }
 
+// ws: device workspace of ws_bytes (routing records at WS_REC_OFF, SwiGLU vectors from WS_H_OFF on)
 static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, int act_dtype, int k,
-                         RouteIn in, DecodeArgs& a, int T = 1) {
+                         RouteIn in, DecodeArgs& a, int T, uint8_t* ws, size_t ws_bytes) {
   if (!routed && !shared) return SMOE_EINVAL;
   if (routed && routed->device != ctx->device) return SMOE_EINVAL;
   if (shared && shared->device != ctx->device) return SMOE_EINVAL;
@@ -1210,9 +1212,9 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   a.f_r = routed ? routed->desc.d_ff : 0;
   a.f_s = shared ? shared->desc.d_ff : 0;
   const int total_f = k * a.f_r + ns * a.f_s;
-  if ((size_t)total_f * 4 + WS_H_OFF > SMOE_WORKSPACE_BYTES) return SMOE_ESIZE;
+  if ((size_t)total_f * 4 + WS_H_OFF > ws_bytes) return SMOE_ESIZE;
   if (T < 1 || T > SMOE_MAX_MULTI) return SMOE_ESHAPE;
-  if (T > 1 && (size_t)T * DEC_H_STRIDE(ns * a.f_s, a.f_r) * 4 + WS_H_OFF > SMOE_WORKSPACE_BYTES) return SMOE_ESIZE;
+  if (T > 1 && (size_t)T * DEC_H_STRIDE(ns * a.f_s, a.f_r) * 4 + WS_H_OFF > ws_bytes) return SMOE_ESIZE;
   a.gu_sh_r = a.dn_sh_r = routed ? ilog2_exact(routed->desc.group / 32) : 0;
   a.gu_sh_s = a.dn_sh_s = shared ? ilog2_exact(shared->desc.group / 32) : 0;
   if (a.gu_sh_r < 0 || a.gu_sh_s < 0) return SMOE_ENOTIMPL;   // group must be 32 * 2^n for the decode kernels
@@ -1225,8 +1227,8 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   a.n_shared = ns; a.k = k;
   a.E = routed ? routed->desc.n_experts : 0;
   in.E = a.E; in.k = k;
-  a.rec = (RouteRec*)(ctx->ws + WS_REC_OFF);
-  a.h = (float*)(ctx->ws + WS_H_OFF);
+  a.rec = (RouteRec*)(ws + WS_REC_OFF);
+  a.h = (float*)(ws + WS_H_OFF);
   a.d_model = d_model;
   // gate/up split: n_wg work-groups, each takes ceil(f / n_wg) row pairs of every slot
   int n_wg = (total_f + DEC_NW - 1) / DEC_NW;              // at least one row pair per wave
@@ -1242,18 +1244,19 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
   if (T > 1) n_wg = n_wg < 8 ? 8 : (n_wg & ~7);            // the multi-token grid is (8, T, n_wg / 8)
   a.cap_r = a.f_r ? (a.f_r + n_wg - 1) / n_wg : 1;
   a.cap_s = a.f_s ? (a.f_s + n_wg - 1) / n_wg : 1;
-  a.inv_cap_r = (65536 + a.cap_r - 1) / a.cap_r;
-  a.inv_cap_s = (65536 + a.cap_s - 1) / a.cap_s;
+  a.inv_cap_r = fastdiv_magic(a.cap_r);
+  a.inv_cap_s = fastdiv_magic(a.cap_s);
   // (several tokens: no rotation, so that tokens which hold an expert in different slots still read the
   // same rows of it in the same work-group index, i.e. on the same XCD, and share them in its L2)
   a.rot = T > 1 ? 0 : n_wg / (k + ns);
-  if (ns * a.cap_s >= 8192 || k * a.cap_r >= 8192) return SMOE_ESIZE;
+  if (ns * a.cap_s >= SMOE_FASTDIV_LIMIT || k * a.cap_r >= SMOE_FASTDIV_LIMIT) return SMOE_ESIZE;      // entry indices the exact division covers
   a.gu_L = (ns * a.cap_s + k * a.cap_r + DEC_NW - 1) / DEC_NW;
   // down split
   a.ks_r = a.f_r ? (a.f_r / 32 + 63) / 64 : 1;
   a.ks_s = a.f_s ? (a.f_s / 32 + 63) / 64 : 1;
-  a.inv_ks_r = (65536 + a.ks_r - 1) / a.ks_r;
-  a.inv_ks_s = (65536 + a.ks_s - 1) / a.ks_s;
+  a.inv_ks_r = (int)fastdiv_magic(a.ks_r);
+  a.inv_ks_s = (int)fastdiv_magic(a.ks_s);
+  if (ns * a.ks_s >= SMOE_FASTDIV_LIMIT || k * a.ks_r >= SMOE_FASTDIV_LIMIT) return SMOE_ESIZE;
   const int scb = routed ? routed->dev.sc_bf16 : shared->dev.sc_bf16;
   if (routed && shared && routed->dev.sc_bf16 != shared->dev.sc_bf16) return SMOE_ENOTIMPL;   // one scale dtype per layer
   const int bits = routed ? routed->dev.bits : shared->dev.bits;
@@ -1289,7 +1292,7 @@ extern "C" int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smo
   a.idx_in = idx_dev; a.w_in = w_dev; a.tau = tau_head;
   a.x = x_dev; a.shared_gate_w = shared_gate_w_dev; a.prec_out = prec_out_dev; a.y = y_dev; a.add_residual = add_residual;
   const RouteIn in{nullptr, nullptr, slice_mask_dev, 0, 0, 0};
-  return launch_decode(ctx, routed, shared, act_dtype, k, in, a);
+  return launch_decode(ctx, routed, shared, act_dtype, k, in, a, 1, ctx->ws, ctx->ws_bytes);
 }
 
 extern "C" int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
@@ -1318,7 +1321,7 @@ extern "C" int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const s
   a.tau = tau_head; a.x = x_dev; a.shared_gate_w = shared_gate_w_dev;
   const RouteIn in{logits, bias_dev, slice_mask_dev, 0, 0, 1};
   a.idx_out = idx_out_dev; a.w_out = w_out_dev; a.prec_out = prec_out_dev; a.y = y_dev; a.add_residual = add_residual;
-  return launch_decode(ctx, routed, shared, act_dtype, k, in, a);
+  return launch_decode(ctx, routed, shared, act_dtype, k, in, a, 1, ctx->ws, ctx->ws_bytes);
 }
 
 extern "C" int smoe_decode_layer_multi(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, int T,
@@ -1340,5 +1343,5 @@ extern "C" int smoe_decode_layer_multi(smoe_ctx* ctx, const smoe_bank* routed, c
   a.tau = tau_head; a.x = x_dev; a.shared_gate_w = shared_gate_w_dev;
   const RouteIn in{logits_dev, bias_dev, slice_mask_dev, 0, 0, 1};
   a.idx_out = idx_out_dev; a.w_out = w_out_dev; a.prec_out = prec_out_dev; a.y = y_dev; a.add_residual = add_residual;
-  return launch_decode(ctx, routed, shared, act_dtype, k, in, a, T);
+  return launch_decode(ctx, routed, shared, act_dtype, k, in, a, T, ctx->ws, ctx->ws_bytes);
 }

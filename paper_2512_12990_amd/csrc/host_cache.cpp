@@ -1,5 +1,5 @@
 // Host-only bookkeeping that produces the slice mask: the unified slice LRU (paper Sections 4.1
-// and 5.1 item 3) and the post-prefill retention order (Section 4.3).  No device work.
+// and 6.1 item 3) and the post-prefill retention order (Section 4.3).  No device work.
 #include "../../include/slicemoe.h"
 #include <algorithm>
 #include <new>

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const void* __restri
     }
     lo = wave_min(lo);
     hi = wave_max(hi);
-    // symmetric variant (Section 5: symmetric integer weights): step from the largest magnitude, the
+    // symmetric variant (Section 6.1 item 1: symmetric integer weights): step from the largest magnitude, the
     // zero-point fixed at mid-range of the unsigned store
     const float half = 0.5f * (qmax + 1.0f);
     float s = symmetric ? fmaxf(hi, -lo) / (half - 1.0f) : (hi - lo) / qmax;

@@ -6,7 +6,7 @@ module that both the HIP path's tests/bench and the CPU oracle's tests use, so
 both sides see identical arrays.
 
 The paper evaluates DeepSeek-V2-Lite and Qwen1.5-MoE-A2.7B on a public
-benchmark (Section 5.1); neither the weights nor the benchmark are available
+benchmark (Section 6.1 item 1); neither the weights nor the benchmark are available
 here, so every tensor below is a synthetic stand-in with the same shapes:
 weights ~ N(0, 0.02^2), activations ~ N(0, 1), router logits as each workload
 states.
@@ -151,3 +151,26 @@ def zipf_logits(seed: int, layer: int, steps: int, n_experts: int, s: float = 1.
         rows = slice(ep * period, min(steps, (ep + 1) * period))
         z[rows] = base[perm][None, :] + noise[rows]
     return z
+
+
+def heavy_tailed_activations(seed: int, n: int, d_model: int, dtype: str) -> torch.Tensor:
+    """x[n, d_model] with the structure of transformer hidden states instead of plain N(0, 1): row 0
+    has one 100x outlier in every 32-element chunk; row 1 keeps a few fixed outlier channels (x300)
+    and has every fourth chunk all zero; row 2 lets every chunk span twenty-four binades (magnitudes
+    2^-20 .. 2^4 within a chunk); further rows cycle through the three kinds with fresh draws."""
+    g = _gen(_subseed(seed, 4008))
+    x = torch.randn((n, d_model), generator=g, dtype=torch.float32)
+    n_chunks = d_model // 32
+    for r in range(n):
+        kind = r % 3
+        if kind == 0:
+            pos = torch.randint(0, 32, (n_chunks,), generator=g)
+            x[r, torch.arange(n_chunks) * 32 + pos] *= 100.0
+        elif kind == 1:
+            chan = torch.randperm(d_model, generator=g)[: max(1, d_model // 256)]
+            x[r, chan] *= 300.0
+            x[r].view(n_chunks, 32)[::4] = 0.0
+        else:
+            e = torch.randint(-20, 5, (d_model,), generator=g).to(torch.float32)
+            x[r] = torch.sign(x[r]) * (1.0 + x[r].abs().clamp(max=0.99)) * torch.exp2(e)
+    return x.to(torch_dtype(dtype))

@@ -133,3 +133,60 @@ def test_cache_all_layer_calls_match_per_layer_calls():
         a.access_all(bad, k, None)
     assert a.order() == before
 
+
+
+def test_workspace_bytes_and_ctx_create_validation():
+    lib = B.lib()
+    # one token of the DeepSeek-V2-Lite-shaped layer: 64 KiB of records + (6 + 2) * 1408 floats
+    assert B.smoe_workspace_bytes(1, 6, 1408, 2, 1408) == (64 << 10) + 8 * 1408 * 4
+    # several tokens: vectors a fixed stride apart with room for the largest top-k (16)
+    assert B.smoe_workspace_bytes(4, 6, 1408, 2, 1408) == (64 << 10) + 4 * (2 + 16) * 1408 * 4
+    n = C.c_size_t()
+    for args in [(0, 6, 1408, 2, 1408), (17, 6, 1408, 2, 1408), (1, 17, 1408, 0, 0), (1, 6, -1, 0, 0), (1, 6, 32, 9, 32)]:
+        assert lib.smoe_workspace_bytes(*[C.c_int(a) for a in args], C.byref(n)) == -2
+    assert lib.smoe_workspace_bytes(C.c_int(1), C.c_int(1), C.c_int(32), C.c_int(0), C.c_int(0), None) == -1
+    # the context borrows its workspace: a null, misaligned or too small one is refused before any device call
+    h = C.c_void_p()
+    create = lib.smoe_ctx_create
+    assert create(C.c_int(0), None, None, C.c_size_t(1 << 20), C.byref(h)) == -1
+    assert create(C.c_int(0), None, C.c_void_p(0x1000 + 16), C.c_size_t(1 << 20), C.byref(h)) == -3
+    assert create(C.c_int(0), None, C.c_void_p(0x1000), C.c_size_t(1024), C.byref(h)) == -4
+    assert create(C.c_int(-1), None, C.c_void_p(0x1000), C.c_size_t(1 << 20), C.byref(h)) == -1
+
+
+def test_no_device_allocation_in_the_library_sources():
+    # the boundary's rule: device memory belongs to the caller
+    csrc = os.path.join(ROOT, "paper_2512_12990_amd", "csrc")
+    for name in os.listdir(csrc):
+        text = open(os.path.join(csrc, name)).read()
+        for call in ("hipMalloc", "hipFree", "hipMallocAsync", "hipExtMallocWithFlags", "hipHostMalloc"):
+            assert not re.search(r"\b%s\s*\(" % call, text), (name, call)
+
+
+def test_entry_division_is_exact_for_every_accepted_split(tmp_path):
+    # The decode kernels turn an entry index into (slot, position) with a multiply-high by a launch
+    # constant (csrc/fastdiv.hpp).  Checked here against integer division for EVERY row-pair count per
+    # slot (cap) and every entry index the host lets through (slots * cap below the stated limit).
+    src = tmp_path / "fastdiv_check.cpp"
+    src.write_text(r'''
+#include "fastdiv.hpp"
+#include <stdio.h>
+int main() {
+  long long n = 0;
+  for (int cap = 1; cap < SMOE_FASTDIV_LIMIT; cap++) {
+    const uint32_t m = fastdiv_magic(cap);
+    for (int e = 0; e < SMOE_FASTDIV_LIMIT; e++) {
+      const int s = fastdiv(e, m);
+      if (s != e / cap || e - s * cap != e % cap) { printf("FAIL cap=%d e=%d got %d want %d\n", cap, e, s, e / cap); return 1; }
+      n++;
+    }
+  }
+  printf("ok %lld\n", n);
+  return 0;
+}
+''')
+    exe = tmp_path / "fastdiv_check"
+    import subprocess
+    subprocess.run(["g++", "-O2", "-I", os.path.join(ROOT, "paper_2512_12990_amd", "csrc"), str(src), "-o", str(exe)], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0 and r.stdout.startswith("ok"), r.stdout

@@ -159,7 +159,7 @@ def test_lower_bit_nests():
 
 @pytest.mark.parametrize("b_high,b_low", [(8, 4), (6, 3), (4, 2)])
 def test_symmetric_variant_pins(b_high, b_low):
-    # Symmetric integer quantisation (Section 5 set-up) in the unsigned store: what must hold whatever
+    # Symmetric integer quantisation (Section 6.1 item 1) in the unsigned store: what must hold whatever
     # the implementation -- the zero-point sits at mid-range, the largest magnitude of a group lands on
     # the last signed level, negating the weights mirrors every code about the zero-point, an exact
     # signed grid is recovered, and the error is at most half a step.
