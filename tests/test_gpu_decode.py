@@ -189,8 +189,10 @@ def _run_layer_steps(ctx, wl: synth.Workload, pair: LayerPair, steps, masks, bia
                                   tau_head=tau, shared_gate_w=None if wsg is None else dev(wsg),
                                   add_residual=add_residual, prec_out=p_o)
             prec = p_o.cpu().numpy()
-        # the oracle uses the gate weights the GPU path was given / produced in fp32
-        w_used = rw[0].astype(np.float32).astype(np.float64)
+        # the oracle uses the gate weights the GPU path was given / produced in fp32: the threshold
+        # decision is taken on the very fp32 weight the kernel compares (checked against the oracle's
+        # weight above), so a weight that sits on the threshold cannot fall on different sides
+        w_used = (w if use_fused else rw[0]).astype(np.float32).astype(np.float64)
         rprec = O.precision_select(ridx[0], w_used, mask, tau)
         assert np.array_equal(prec, rprec), (t, prec, rprec)
         yref = O.moe_layer(t2np(x).astype(np.float64), pair.oracle_routed(), ridx[0], w_used, rprec,
