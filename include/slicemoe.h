@@ -80,7 +80,9 @@ int smoe_workspace_bytes(int tokens, int k, int d_ff, int n_shared, int shared_d
  * smoe_workspace_bytes of the largest layer it will see; SMOE_ESIZE below 64 KiB, and later from a
  * decode call whose intermediates do not fit).  The library itself never allocates or frees device
  * memory; the workspace is borrowed until smoe_ctx_destroy and is shared by all calls of the context,
- * which therefore must not overlap in time (one stream). */
+ * which therefore must not overlap in time (one stream).  workspace_dev may be NULL with
+ * workspace_bytes 0: such a context serves every call that needs no workspace (quantise, route,
+ * prefill, smoe_decode_layer_static); the other decode calls return SMOE_ESIZE. */
 int smoe_ctx_create(int device, void* hip_stream, void* workspace_dev, size_t workspace_bytes, smoe_ctx** out);
 int smoe_ctx_destroy(smoe_ctx* ctx);
 const char* smoe_strerror(int status);
@@ -160,6 +162,25 @@ int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* s
                       float routed_scale, const uint8_t* slice_mask_dev, float tau_head,
                       const void* shared_gate_w_dev, int add_residual, void* y_dev,
                       int32_t* idx_out_dev, float* w_out_dev, uint8_t* prec_out_dev);
+
+/* smoe_decode_layer for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, bit-identical
+ * results; the workspace (routing record, router logits, fp32 SwiGLU vectors) is a file-scope device
+ * array of smoe_static_scratch_bytes() = 512 KiB inside the library instead of the context's buffer,
+ * so the context may have been created without one.  Every GPU the library has run this call on holds
+ * its own copy of that array until the process ends.  The call makes no hipMalloc / hipFree and no
+ * allocating library call.  Limit: 64 KiB + 4 * (k * d_ff + n_shared * shared_d_ff) bytes must fit the
+ * array (114,688 floats of intermediates); SMOE_ESIZE beyond, before any device work.  All calls on one
+ * GPU share the array and it keeps the last call's contents (nothing in it needs clearing: every word
+ * read by a call was written by that call first); calls that overlap in time on one GPU -- two
+ * streams, two contexts, two threads -- race on it and must be serialised by the caller. */
+int smoe_static_scratch_bytes(size_t* bytes);
+int smoe_decode_layer_static(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared,
+                             const void* x_dev, int act_dtype, int k, const float* logits_dev,
+                             const float* w_router_dev, const float* bias_dev, int norm_topk,
+                             float routed_scale, const uint8_t* slice_mask_dev, float tau_head,
+                             const void* shared_gate_w_dev, int add_residual, void* y_dev,
+                             int32_t* idx_out_dev, float* w_out_dev, uint8_t* prec_out_dev);
 
 /* smoe_decode_layer for T tokens (1 <= T <= 16) that pass the same layer in one pair of launches,
  * e.g. the draft tokens of a speculative step or a small batch: token t uses row t of x_dev

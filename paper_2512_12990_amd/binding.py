@@ -48,7 +48,7 @@ EXPORTS = [
     "smoe_workspace_bytes", "smoe_ctx_create", "smoe_ctx_destroy", "smoe_strerror", "smoe_last_hip_error", "smoe_ctx_timing",
     "smoe_ctx_timing_read",
     "smoe_bank_bytes", "smoe_bank_create", "smoe_bank_destroy", "smoe_quantize_slice", "smoe_export_codes",
-    "smoe_route", "smoe_expert_ffn", "smoe_decode_layer", "smoe_decode_layer_multi",
+    "smoe_route", "smoe_expert_ffn", "smoe_decode_layer", "smoe_decode_layer_multi", "smoe_static_scratch_bytes", "smoe_decode_layer_static",
     "smoe_prefill_bytes", "smoe_prefill_histogram", "smoe_topn_slices",
     "smoe_cache_create", "smoe_cache_destroy", "smoe_cache_init_order", "smoe_cache_snapshot",
     "smoe_cache_access", "smoe_cache_snapshot_all", "smoe_cache_access_all", "smoe_cache_stats_get", "smoe_cache_order",
@@ -99,8 +99,10 @@ class Ctx:
         self.device = device
         s = stream if stream is not None else torch.cuda.current_stream(device)
         self._stream = s
-        self.workspace = torch.empty(workspace_bytes + 256, dtype=torch.uint8, device="cuda:%d" % device)
-        base = self.workspace.data_ptr() + (-self.workspace.data_ptr()) % 256
+        self.workspace, base = None, 0
+        if workspace_bytes:                       # 0: a context for the calls that need no workspace
+            self.workspace = torch.empty(workspace_bytes + 256, dtype=torch.uint8, device="cuda:%d" % device)
+            base = self.workspace.data_ptr() + (-self.workspace.data_ptr()) % 256
         self.h = C.c_void_p()
         _chk(lib().smoe_ctx_create(C.c_int(device), C.c_void_p(s.cuda_stream), C.c_void_p(base),
                                    C.c_size_t(workspace_bytes), C.byref(self.h)), "smoe_ctx_create")
@@ -227,6 +229,25 @@ def smoe_decode_layer(ctx: Ctx, routed: Bank, shared: Optional[Bank], x: torch.T
                                  C.c_float(routed_scale), _p(slice_mask), C.c_float(tau_head), _p(shared_gate_w),
                                  C.c_int(int(add_residual)), _p(y), _p(idx_out), _p(w_out), _p(prec_out)),
          "smoe_decode_layer", ctx.h)
+    return y
+
+
+def smoe_static_scratch_bytes() -> int:
+    n = C.c_size_t()
+    _chk(lib().smoe_static_scratch_bytes(C.byref(n)), "smoe_static_scratch_bytes")
+    return n.value
+
+
+def smoe_decode_layer_static(ctx: Ctx, routed: Bank, shared: Optional[Bank], x: torch.Tensor, k: int, y: torch.Tensor,
+                             logits=None, w_router=None, bias=None, norm_topk: bool = False, routed_scale: float = 1.0,
+                             slice_mask=None, tau_head: float = 0.0, shared_gate_w=None, add_residual: bool = False,
+                             idx_out=None, w_out=None, prec_out=None):
+    """smoe_decode_layer over the library's static workspace; the caller passes every buffer (y included)."""
+    _chk(lib().smoe_decode_layer_static(ctx.h, routed.h, shared.h if shared else None, _p(x), C.c_int(_DT[x.dtype]),
+                                        C.c_int(k), _p(logits), _p(w_router), _p(bias), C.c_int(int(norm_topk)),
+                                        C.c_float(routed_scale), _p(slice_mask), C.c_float(tau_head), _p(shared_gate_w),
+                                        C.c_int(int(add_residual)), _p(y), _p(idx_out), _p(w_out), _p(prec_out)),
+         "smoe_decode_layer_static", ctx.h)
     return y
 
 

@@ -30,10 +30,11 @@ extern "C" int smoe_workspace_bytes(int tokens, int k, int d_ff, int n_shared, i
 }
 
 extern "C" int smoe_ctx_create(int device, void* hip_stream, void* workspace_dev, size_t workspace_bytes, smoe_ctx** out) {
-  if (!out || device < 0 || !workspace_dev) return SMOE_EINVAL;
+  if (!out || device < 0) return SMOE_EINVAL;
   *out = nullptr;
+  if (!workspace_dev && workspace_bytes) return SMOE_EINVAL;
   if (((uintptr_t)workspace_dev) & 255u) return SMOE_EALIGN;
-  if (workspace_bytes < (size_t)WS_H_OFF) return SMOE_ESIZE;
+  if (workspace_dev && workspace_bytes < (size_t)WS_H_OFF) return SMOE_ESIZE;
   smoe_ctx* c = new (std::nothrow) smoe_ctx();
   if (!c) return SMOE_EINVAL;
   c->device = device; c->stream = (hipStream_t)hip_stream; c->ws = (uint8_t*)workspace_dev; c->ws_bytes = workspace_bytes;

@@ -9,6 +9,7 @@
 #define SMOE_MAX_EXPERTS 256
 #define SMOE_MAX_MULTI 16          // tokens of one smoe_decode_layer_multi call
 #define SMOE_MAX_TOPK 16
+#define SMOE_STATIC_SCRATCH_BYTES (512u << 10)   // the file-scope workspace of smoe_decode_layer_static
 
 // ---- host objects -------------------------------------------------------------------------
 // Device view of one quantised matrix family inside a bank ("gu": gate and up rows interleaved,

@@ -30,6 +30,7 @@
 #include "fastdiv.hpp"
 #include <hip/hip_ext.h>
 #include <vector>
+#include <mutex>
 
 #define DEC_NT 512                  // threads per work-group
 #define DEC_NW (DEC_NT / 64)
@@ -1295,22 +1296,23 @@ extern "C" int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smo
   return launch_decode(ctx, routed, shared, act_dtype, k, in, a, 1, ctx->ws, ctx->ws_bytes);
 }
 
-extern "C" int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
-                                 int act_dtype, int k, const float* logits_dev, const float* w_router_dev,
-                                 const float* bias_dev, int norm_topk, float routed_scale,
-                                 const uint8_t* slice_mask_dev, float tau_head, const void* shared_gate_w_dev,
-                                 int add_residual, void* y_dev, int32_t* idx_out_dev, float* w_out_dev,
-                                 uint8_t* prec_out_dev) {
+static int decode_layer_impl(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
+                             int act_dtype, int k, const float* logits_dev, const float* w_router_dev,
+                             const float* bias_dev, int norm_topk, float routed_scale,
+                             const uint8_t* slice_mask_dev, float tau_head, const void* shared_gate_w_dev,
+                             int add_residual, void* y_dev, int32_t* idx_out_dev, float* w_out_dev,
+                             uint8_t* prec_out_dev, uint8_t* ws, size_t ws_bytes) {
   if (!ctx || !x_dev || !y_dev || x_dev == y_dev || !routed) return SMOE_EINVAL;
   if (act_dtype != SMOE_F32 && act_dtype != SMOE_BF16) return SMOE_EINVAL;
   if (!logits_dev && !w_router_dev) return SMOE_EINVAL;
   if (!aligned16(x_dev) || !aligned16(y_dev) || !aligned16(logits_dev) || !aligned16(w_router_dev) ||
       !aligned16(bias_dev) || !aligned16(shared_gate_w_dev))
     return SMOE_EALIGN;
+  if (!ws || ws_bytes < (size_t)WS_H_OFF) return SMOE_ESIZE;
   const float* logits = logits_dev;
   if (!logits) {
     // router mat-vec into the workspace, then the gate/up prologue selects from those logits
-    float* zws = (float*)(ctx->ws + WS_IDX_OFF);
+    float* zws = (float*)(ws + WS_IDX_OFF);
     HIPCHK(ctx, hipSetDevice(ctx->device));
     int rc = smoe_launch_router_logits(ctx, routed->desc.n_experts, routed->desc.d_model, x_dev, act_dtype, w_router_dev, zws);
     if (rc) return rc;
@@ -1321,7 +1323,19 @@ extern "C" int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const s
   a.tau = tau_head; a.x = x_dev; a.shared_gate_w = shared_gate_w_dev;
   const RouteIn in{logits, bias_dev, slice_mask_dev, 0, 0, 1};
   a.idx_out = idx_out_dev; a.w_out = w_out_dev; a.prec_out = prec_out_dev; a.y = y_dev; a.add_residual = add_residual;
-  return launch_decode(ctx, routed, shared, act_dtype, k, in, a, 1, ctx->ws, ctx->ws_bytes);
+  return launch_decode(ctx, routed, shared, act_dtype, k, in, a, 1, ws, ws_bytes);
+}
+
+extern "C" int smoe_decode_layer(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
+                                 int act_dtype, int k, const float* logits_dev, const float* w_router_dev,
+                                 const float* bias_dev, int norm_topk, float routed_scale,
+                                 const uint8_t* slice_mask_dev, float tau_head, const void* shared_gate_w_dev,
+                                 int add_residual, void* y_dev, int32_t* idx_out_dev, float* w_out_dev,
+                                 uint8_t* prec_out_dev) {
+  if (!ctx) return SMOE_EINVAL;
+  return decode_layer_impl(ctx, routed, shared, x_dev, act_dtype, k, logits_dev, w_router_dev, bias_dev, norm_topk, routed_scale,
+                           slice_mask_dev, tau_head, shared_gate_w_dev, add_residual, y_dev, idx_out_dev, w_out_dev, prec_out_dev,
+                           ctx->ws, ctx->ws_bytes);
 }
 
 extern "C" int smoe_decode_layer_multi(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, int T,
@@ -1344,4 +1358,61 @@ extern "C" int smoe_decode_layer_multi(smoe_ctx* ctx, const smoe_bank* routed, c
   const RouteIn in{logits_dev, bias_dev, slice_mask_dev, 0, 0, 1};
   a.idx_out = idx_out_dev; a.w_out = w_out_dev; a.prec_out = prec_out_dev; a.y = y_dev; a.add_residual = add_residual;
   return launch_decode(ctx, routed, shared, act_dtype, k, in, a, T, ctx->ws, ctx->ws_bytes);
+}
+
+// ---------------------------------------------------------------------------------- no-allocation variant
+// smoe_decode_layer for callers that cannot allocate device memory at all (code under HIP graph capture,
+// serving loops or harnesses that forbid hipMalloc): the workspace of the call -- routing record,
+// router logits, SwiGLU vectors -- is this file-scope device array instead of a caller buffer.  Every
+// GPU the library runs on holds its own copy of the array, at its own address, until the process ends;
+// in host code the array's name is only a handle, so the address is looked up once per device with
+// hipGetSymbolAddress and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) uint8_t scratch[SMOE_STATIC_SCRATCH_BYTES];
+
+#define SMOE_STATIC_MAX_DEVICES 64
+static uint8_t* scratch_dev_ptr[SMOE_STATIC_MAX_DEVICES];      // per device; null until looked up
+static std::mutex scratch_lock;
+
+static int static_scratch(smoe_ctx* ctx, uint8_t** out) {
+  if (ctx->device < 0 || ctx->device >= SMOE_STATIC_MAX_DEVICES) return SMOE_ESHAPE;
+  std::lock_guard<std::mutex> guard(scratch_lock);
+  if (!scratch_dev_ptr[ctx->device]) {
+    HIPCHK(ctx, hipSetDevice(ctx->device));       // the lookup returns the copy of the current device
+    void* p = nullptr;
+    HIPCHK(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || (((uintptr_t)p) & 255u)) return SMOE_EALIGN;
+    scratch_dev_ptr[ctx->device] = (uint8_t*)p;
+  }
+  *out = scratch_dev_ptr[ctx->device];
+  return SMOE_OK;
+}
+
+extern "C" int smoe_static_scratch_bytes(size_t* bytes) {
+  if (!bytes) return SMOE_EINVAL;
+  *bytes = SMOE_STATIC_SCRATCH_BYTES;
+  return SMOE_OK;
+}
+
+extern "C" int smoe_decode_layer_static(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
+                                        int act_dtype, int k, const float* logits_dev, const float* w_router_dev,
+                                        const float* bias_dev, int norm_topk, float routed_scale,
+                                        const uint8_t* slice_mask_dev, float tau_head, const void* shared_gate_w_dev,
+                                        int add_residual, void* y_dev, int32_t* idx_out_dev, float* w_out_dev,
+                                        uint8_t* prec_out_dev) {
+  if (!ctx || !routed) return SMOE_EINVAL;
+  // size check first, with a clear status: the intermediates of the layer must fit the array
+  const size_t floats = (size_t)(k > 0 ? k : 0) * (size_t)routed->desc.d_ff +
+                        (shared ? (size_t)shared->desc.n_experts * (size_t)shared->desc.d_ff : 0);
+  if ((size_t)WS_H_OFF + floats * 4 > SMOE_STATIC_SCRATCH_BYTES) return SMOE_ESIZE;
+  uint8_t* ws = nullptr;
+  int rc = static_scratch(ctx, &ws);
+  if (rc) return rc;
+  // (the measurement aid of smoe_ctx_timing creates events: not in this entry point)
+  const int timing = ctx->timing;
+  ctx->timing = 0;
+  rc = decode_layer_impl(ctx, routed, shared, x_dev, act_dtype, k, logits_dev, w_router_dev, bias_dev, norm_topk, routed_scale,
+                         slice_mask_dev, tau_head, shared_gate_w_dev, add_residual, y_dev, idx_out_dev, w_out_dev, prec_out_dev,
+                         ws, SMOE_STATIC_SCRATCH_BYTES);
+  ctx->timing = timing;
+  return rc;
 }
