@@ -66,6 +66,11 @@ def main():
     ap.add_argument("--with-shared", action="store_true",
                     help="prefill: add the Qwen-shaped shared expert (d_ff 5632 behind a sigmoid gate) that every "
                          "token passes through; reported as its own line, not the headline")
+    ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
+                    help="decode: how the timed steps are launched: replayed from a captured HIP graph (default; the eager "
+                         "figure is reported beside it) or as eager calls only")
+    ap.add_argument("--replicas", type=int, default=4,
+                    help="decode: layer replicas of the cold-weights figure (0 or 1: skip it)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed passes, copy this many MiB device-to-device four times (a kernel of known "
                          "traffic, used to scale the HBM byte counters of a profiler run)")
@@ -103,18 +108,27 @@ def main():
         wl = dataclasses.replace(wl, layer=dataclasses.replace(wl.layer, group=args.group))
     shp = wl.layer
     dev = "cuda:0"
-    ctx = B.Ctx(0)
+    # everything runs on one side stream: the context launches on it, the events are recorded on it,
+    # and a HIP graph can be captured from it
+    side = torch.cuda.Stream()
+    torch.cuda.set_stream(side)
+    ctx = B.Ctx(0, stream=side)
     adt = shp.act                                   # activation and scale dtype of the workload
     ADT, asz = B._DT[adt], (4 if adt == "f32" else 2)
-    routed = B.Bank(ctx, shp.n_experts, shp.d_model, shp.d_ff, shp.group, adt, adt, bh, bl)
-    shared = B.Bank(ctx, shp.n_shared, shp.d_model, shp.shared_d_ff, shp.group, adt, adt, bh, bl) if shp.n_shared else None
-    shared_h = shared.h if shared is not None else None
-    for e in range(shp.n_experts):
-        wg, wu, wd = synth.expert_weights(wl.seed, 0, e, shp.d_model, shp.d_ff, adt, dev)
-        B.smoe_quantize_slice(ctx, routed, e, wg[None], wu[None], wd[None])
-    for i in range(shp.n_shared):
-        wg, wu, wd = synth.expert_weights(wl.seed, 0, 1000 + i, shp.d_model, shp.shared_d_ff, adt, dev)
-        B.smoe_quantize_slice(ctx, shared, i, wg[None], wu[None], wd[None])
+
+    def build_layer(replica):
+        """One layer's banks; replica r > 0 draws different weights of the same shape."""
+        routed = B.Bank(ctx, shp.n_experts, shp.d_model, shp.d_ff, shp.group, adt, adt, bh, bl)
+        shared = B.Bank(ctx, shp.n_shared, shp.d_model, shp.shared_d_ff, shp.group, adt, adt, bh, bl) if shp.n_shared else None
+        for e in range(shp.n_experts):
+            wg, wu, wd = synth.expert_weights(wl.seed, replica, e, shp.d_model, shp.d_ff, adt, dev)
+            B.smoe_quantize_slice(ctx, routed, e, wg[None], wu[None], wd[None])
+        for i in range(shp.n_shared):
+            wg, wu, wd = synth.expert_weights(wl.seed, replica, 1000 + i, shp.d_model, shp.shared_d_ff, adt, dev)
+            B.smoe_quantize_slice(ctx, shared, i, wg[None], wu[None], wd[None])
+        return routed, shared
+
+    routed, shared = build_layer(0)
     n_in = wl.steps
     x_all = synth.activations(wl.seed, n_in, shp.d_model, adt).to(dev)
     z_all = synth.normal_logits(wl.seed, n_in, shp.n_experts).to(dev)
@@ -138,70 +152,95 @@ def main():
 
     # argument lists are marshalled once; the timed loop only makes the C calls
     import ctypes as C
-    fn = B.lib().smoe_decode_layer
     vp = lambda t: C.c_void_p(t.data_ptr())
     TT = args.tokens
     wr = synth.router_weight(wl.seed, 0, shp.n_experts, shp.d_model).to(dev) if args.router_matvec else None
-    if TT == 1:
-        calls = [(ctx.h, routed.h, shared_h, vp(x_all[i]), C.c_int(ADT), C.c_int(shp.top_k),
-                  None if wr is not None else vp(z_all[i]), vp(wr) if wr is not None else None,
-                  vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), vp(wsg) if wsg is not None else None,
-                  C.c_int(0), vp(y[i]), vp(idx[i]), None, vp(prec[i])) for i in range(n_in)]
-    else:
+
+    def make_calls(routed, shared):
+        sh = shared.h if shared is not None else None
+        if TT == 1:
+            return B.lib().smoe_decode_layer, [
+                (ctx.h, routed.h, sh, vp(x_all[i]), C.c_int(ADT), C.c_int(shp.top_k),
+                 None if wr is not None else vp(z_all[i]), vp(wr) if wr is not None else None,
+                 vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), vp(wsg) if wsg is not None else None,
+                 C.c_int(0), vp(y[i]), vp(idx[i]), None, vp(prec[i])) for i in range(n_in)]
         # step t takes the TT consecutive tokens that start at row (t * TT) mod n_in
         assert 2 <= TT <= 16 and n_in % TT == 0
-        fn = B.lib().smoe_decode_layer_multi
-        calls = [(ctx.h, routed.h, shared_h, C.c_int(TT), vp(x_all[i]), C.c_int(ADT), C.c_int(shp.top_k), vp(z_all[i]),
-                  vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), vp(wsg) if wsg is not None else None,
-                  C.c_int(0), vp(y[i]), vp(idx[i]), None, vp(prec[i])) for i in range(0, n_in, TT)]
+        return B.lib().smoe_decode_layer_multi, [
+            (ctx.h, routed.h, sh, C.c_int(TT), vp(x_all[i]), C.c_int(ADT), C.c_int(shp.top_k), vp(z_all[i]),
+             vp(bias), C.c_int(0), C.c_float(1.0), vp(mask), C.c_float(0.0), vp(wsg) if wsg is not None else None,
+             C.c_int(0), vp(y[i]), vp(idx[i]), None, vp(prec[i])) for i in range(0, n_in, TT)]
+
+    fn, calls = make_calls(routed, shared)
     n_calls = len(calls)
 
-    def step(t):
-        rc = fn(*calls[t % n_calls])
-        if rc != 0:
-            raise B.SmoeError("decode call failed: %d" % rc)
+    def make_step(fn, call_lists):
+        """Step t makes call t of layer replica t mod R (R = 1: the one layer every step)."""
+        R = len(call_lists)
 
-    for t in range(args.warmup):
-        step(t)
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for t in range(args.warmup, args.warmup + args.steps):
-        step(t)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    gpu_ms = ev0.elapsed_time(ev1)
-    ms_per_step = gpu_ms / args.steps
+        def step(t):
+            rc = fn(*call_lists[t % R][t % n_calls])
+            if rc != 0:
+                raise B.SmoeError("decode call failed: %d" % rc)
+        return step
 
-    # Five more windows of the same K steps: their median and spread show how repeatable `value` is.
-    windows = []
-    for _ in range(5):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for t in range(args.warmup, args.warmup + args.steps):
-            step(t)
-        e1.record()
+    def timed(run):
+        """GPU time of run() between two events on the launch stream, and the host's wall time, in ms."""
         torch.cuda.synchronize()
-        windows.append(e0.elapsed_time(e1) / args.steps * 1e3)
-    windows = sorted(w / TT for w in windows)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(side)
+        run()
+        e1.record(side)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1), (time.perf_counter() - t0) * 1e3
+
+    def measure(step):
+        """ms per step of exactly args.steps steps after args.warmup warm-up steps: eager launches, and the
+        same steps replayed from a captured HIP graph (a serving loop records its decode calls once)."""
+        for t in range(args.warmup):
+            step(t)
+        eager_ms, eager_wall = timed(lambda: [step(t) for t in range(args.warmup, args.warmup + args.steps)])
+        res = {"eager_ms_per_step": eager_ms / args.steps, "eager_host_wall_ms_per_step": eager_wall / args.steps}
+        if args.launch == "graph":
+            G = min(args.steps, 256)
+            while args.steps % G:
+                G -= 1
+            graphs = []
+            for g0 in range(args.warmup, args.warmup + args.steps, G):      # the same steps, in the same order
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr, stream=side):
+                    for t in range(g0, g0 + G):
+                        step(t)
+                graphs.append(gr)
+            for gr in graphs[:1]:
+                gr.replay()                                                   # untimed first replay (upload)
+            graph_ms, graph_wall = timed(lambda: [gr.replay() for gr in graphs])
+            res.update({"graph_ms_per_step": graph_ms / args.steps, "graph_host_wall_ms_per_step": graph_wall / args.steps,
+                        "graph_steps_per_graph": G})
+            res["windows"] = sorted(timed(lambda: [gr.replay() for gr in graphs])[0] / args.steps for _ in range(5))
+            res["graphs"] = graphs
+        else:
+            res["windows"] = sorted(timed(lambda: [step(t) for t in range(args.warmup, args.warmup + args.steps)])[0] / args.steps
+                                    for _ in range(5))
+        res["ms_per_step"] = res["graph_ms_per_step"] if args.launch == "graph" else res["eager_ms_per_step"]
+        return res
+
+    step = make_step(fn, [calls])
+    m = measure(step)
+    ms_per_step = m["ms_per_step"]
+    windows = [w * 1e3 / TT for w in m["windows"]]
 
     # A plain device-to-device copy of 256 MiB, for scale: what this box's HBM delivers to a streaming
     # kernel (bytes read + bytes written per second).
     csrc = torch.full((256 << 20,), 7, dtype=torch.uint8, device=dev)
     cdst = torch.empty_like(csrc)
     cdst.copy_(csrc)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(4):
-        cdst.copy_(csrc)
-    e1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 4 * 2 * csrc.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    copy_ms, _ = timed(lambda: [cdst.copy_(csrc) for _ in range(4)])
+    copy_gbps = 4 * 2 * csrc.numel() / (copy_ms * 1e-3) / 1e9
     del csrc, cdst
 
-    # Dominant kernel (gate/up streams 2/3 of the bytes): a second pass over the SAME steps with HIP
+    # Dominant kernel (gate/up streams 2/3 of the bytes): a second pass over the SAME steps with
     # a start and a stop event attached by the library to each of the two dispatches of a call.
     ctx.timing(True)
     for t in range(args.warmup, args.warmup + args.steps):
@@ -213,20 +252,23 @@ def main():
 
     # algorithmic bytes of exactly the timed steps, from the precision flags the kernels reported
     prec_np = prec.cpu().numpy()
+    idx_np = idx.cpu().numpy()
     hi_gu, hi_dn = slot_bytes(shp.d_model, shp.d_ff, shp.group, 1, asz)
     lo_gu, lo_dn = slot_bytes(shp.d_model, shp.d_ff, shp.group, 0, asz)
     sh_gu, sh_dn = slot_bytes(shp.d_model, shp.shared_d_ff, shp.group, 1, asz) if shp.n_shared else (0, 0)
     sh_gu, sh_dn = sh_gu * shp.n_shared, sh_dn * shp.n_shared
     total_bytes = gu_bytes = 0
-    idx_np = idx.cpu().numpy()
+    high_slots = timed_rows = 0
     for t in range(args.warmup, args.warmup + args.steps):
+        r0 = (t % n_calls) * TT
+        high_slots += int(prec_np[r0:r0 + TT].sum())
+        timed_rows += TT
         if TT == 1:
-            nh = int(prec_np[t % n_in].sum())
+            nh = int(prec_np[r0].sum())
             nl = shp.top_k - nh
         else:
             # what the step must move: every expert some token of the step selected once, with its LSB
             # plane if some token runs it HIGH
-            r0 = (t % n_calls) * TT
             need = {}
             for tt in range(r0, r0 + TT):
                 for e, p in zip(idx_np[tt], prec_np[tt]):
@@ -242,6 +284,17 @@ def main():
     achieved = bytes_per_step / (ms_per_step * 1e-3) / 1e9
     gu_achieved = gu_bytes_per_launch / (gu_us * 1e-6) / 1e9
 
+    # HBM bytes per gate/up launch as the FETCH_SIZE / WRITE_SIZE counters read them: only for the one
+    # configuration the committed counter runs cover (profiles/...hbm_traffic.txt); any other run prints null
+    traffic = traffic_src = None
+    key = (args.shape, args.nest, shp.group, TT, bool(args.router_matvec))
+    if key in MEASURED_TRAFFIC:
+        traffic, traffic_src = MEASURED_TRAFFIC[key]
+
+    # hot set of the one-layer workload: the experts the mask marks resident (what the steps keep selecting)
+    hot_experts = int((mask_np & 1).sum()) or shp.n_experts
+    hot_bytes = sh_gu + sh_dn + int((mask_np == 3).sum()) * (hi_gu + hi_dn) + (hot_experts - int((mask_np == 3).sum())) * (lo_gu + lo_dn)
+
     out = {
         "metric": "decode MoE-layer us/token (+ achieved HBM GB/s as a fraction of MI355X peak)",
         "value": ms_per_step * 1e3 / TT, "unit": "us/token", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -256,10 +309,18 @@ def main():
                    "d_model": shp.d_model, "n_experts": shp.n_experts, "d_ff": shp.d_ff, "top_k": shp.top_k,
                    "n_shared": shp.n_shared, "shared_d_ff": shp.shared_d_ff, "group": shp.group, "nest": "%d/%d" % (bh, bl),
                    "cached": int((mask_np & 1).sum()), "cached_high": int((mask_np == 3).sum()),
-                   "mean_high_slots": float(prec_np.mean() * shp.top_k), "launches_per_step": 3 if wr is not None else 2,
-                   "tokens_per_step": TT},
+                   "mean_high_slots": high_slots / timed_rows, "launches_per_step": 3 if wr is not None else 2,
+                   "tokens_per_step": TT,
+                   "launch_mode": ("HIP graph replay (%d steps per graph, the same %d steps in order)" % (m["graph_steps_per_graph"], args.steps)
+                                   if args.launch == "graph" else "eager launches"),
+                   "weights_resident": "one layer of %.0f MB in HBM, re-read every step; the hot set the steps select from (%d resident "
+                                       "experts + %d shared) is about %.0f MB, which fits the 256 MB memory-side cache -- see "
+                                       "cold_weights for the same steps over rotating layer replicas" %
+                                       ((routed.nbytes + (shared.nbytes if shared else 0)) / 1e6, hot_experts, shp.n_shared, hot_bytes / 1e6)},
         "hbm_gbps": achieved, "hbm_frac": achieved / HBM_PEAK_GBPS, "bytes_per_token": bytes_per_step / TT,
-        "host_wall_ms_per_step": wall_ms / args.steps,
+        "eager_us_per_token": m["eager_ms_per_step"] * 1e3 / TT,
+        "host_wall_ms_per_step": m["graph_host_wall_ms_per_step"] if args.launch == "graph" else m["eager_host_wall_ms_per_step"],
+        "eager_host_wall_ms_per_step": m["eager_host_wall_ms_per_step"],
         "repeat_windows_us_per_token": {"median": windows[2], "min": windows[0], "max": windows[-1], "n": 5},
         "copy_256mib_gbps": copy_gbps,
         "roofline": {"bound": "hbm", "kernel": "gateup_kernel<%s> (route + gate/up + SwiGLU of all %d slots)" % (adt, shp.top_k + shp.n_shared),
@@ -268,11 +329,26 @@ def main():
                      "other_kernel": {"kernel": "down_kernel<%s>" % adt, "avg_launch_us": dn_us,
                                       "bytes_per_launch": bytes_per_step - gu_bytes_per_launch,
                                       "achieved": (bytes_per_step - gu_bytes_per_launch) / (dn_us * 1e-6) / 1e9},
-                     "timing": "start/stop HIP events attached to every dispatch on the launch stream, second pass over the same steps",
-                     # HBM bytes per gate/up launch from the FETCH_SIZE / WRITE_SIZE counter runs recorded in
-                     # profiles/decode_dsv2lite_gateup_down_hbm_traffic.txt (scaled by a 256 MiB copy)
-                     "traffic": 39.53e6 + 0.36e6, "traffic_over_algorithmic": (39.53e6 + 0.36e6) / 37.4e6},
+                     "timing": "start/stop HIP events attached to every dispatch on the launch stream, eager pass over the same steps",
+                     "traffic": traffic, "traffic_source": traffic_src,
+                     "traffic_over_algorithmic": (traffic / gu_bytes_per_launch) if traffic else None},
     }
+
+    # The same steps with the weights cold: R replicas of the layer (different weights, same shape), step t
+    # on replica t mod R, so that the bytes a step reads were last touched R steps -- R times the hot set -- ago
+    # and cannot come from the memory-side cache.
+    if args.replicas > 1:
+        m["graphs"] = None                                      # release the first measurement's graphs
+        layers = [(routed, shared)] + [build_layer(r) for r in range(1, args.replicas)]
+        lists = [make_calls(rt, sh)[1] for rt, sh in layers]
+        mc = measure(make_step(fn, lists))
+        cold_gbps = bytes_per_step / (mc["ms_per_step"] * 1e-3) / 1e9
+        out["cold_weights"] = {"replicas": args.replicas, "working_set_mb": args.replicas * hot_bytes / 1e6,
+                               "us_per_token": mc["ms_per_step"] * 1e3 / TT, "eager_us_per_token": mc["eager_ms_per_step"] * 1e3 / TT,
+                               "hbm_gbps": cold_gbps, "hbm_frac": cold_gbps / HBM_PEAK_GBPS,
+                               "note": "same inputs and routing, hence the same algorithmic bytes per step; step t reads "
+                                       "replica t mod %d" % args.replicas}
+        del layers, lists, mc
 
     if args.calib_copy_mib:
         src = torch.full((args.calib_copy_mib << 20,), 7, dtype=torch.uint8, device=dev)
@@ -281,8 +357,16 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline and args.shape == "dsv2" and args.nest == "84":      # the oracle leg times the headline workload only
-        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_steps, idx.cpu().numpy(), prec_np)
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_steps, idx_np, prec_np)
     print(json.dumps(out))
+
+
+# HBM bytes per gate/up launch from rocprofv3 counter runs of exactly this command line, keyed by
+# (shape, nest, group, tokens per step, router mat-vec): value, where it was recorded
+MEASURED_TRAFFIC = {
+    ("dsv2", "84", 128, 1, False): (39.54e6 + 0.36e6, "profiles/decode_dsv2lite_gateup_down_hbm_traffic.txt "
+                                    "(FETCH_SIZE and WRITE_SIZE runs of this command, scaled by a 256 MiB copy)"),
+}
 
 
 def prefill_bench(args):
@@ -323,10 +407,13 @@ def prefill_bench(args):
     torch.cuda.synchronize()
     ms = ev0.elapsed_time(ev1) / steps
     flops = 2.0 * T * shp.top_k * 3 * shp.d_model * shp.d_ff + 2.0 * T * 3 * shp.d_model * f_s
+    y_g, idx_g, w_g, _ = B.smoe_prefill_histogram(ctx, routed, shared, x, shp.top_k, w_router=wr, shared_gate_w=wsg,
+                                                  add_residual=True, scratch=scratch)
+    torch.cuda.synchronize()
     wbytes = shp.n_experts * sum(slot_bytes(shp.d_model, shp.d_ff, shp.group, 1))
     if f_s:
         wbytes += sum(slot_bytes(shp.d_model, f_s, shp.group, 1))
-    print(json.dumps({
+    out = ({
         "metric": "prefill MoE-layer ms (%d tokens, grouped expert GEMM + histogram)" % T, "value": ms, "unit": "ms/layer",
         "n_gpus": 1, "steps": steps, "warmup": 3, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 MFMA, fp32 accumulate, u4+u4 sliced weights", "data": "synthetic",
@@ -337,7 +424,10 @@ def prefill_bench(args):
         "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
                      "frac": flops / (ms * 1e-3) / 1e12 / 2500.0, "flops_per_step": flops,
                      "weight_bytes_per_step": wbytes, "weight_gbps": wbytes / (ms * 1e-3) / 1e9, "traffic": None,
-                     "kernel": "whole layer pass (route_batch, group, grouped_gemm<0>, grouped_gemm<1>, combine)"}}))
+                     "kernel": "whole layer pass (route_batch, group, grouped_gemm<0>, grouped_gemm<1>, combine)"}})
+    if not args.no_cpu_baseline and not args.with_shared:
+        out["cpu_baseline"] = cpu_baseline_prefill(wl, T, min(args.cpu_steps, 16), idx_g.cpu().numpy(), w_g.cpu().numpy())
+    print(json.dumps(out))
 
 
 def stack_bench(args):
@@ -470,6 +560,8 @@ def stack_bench(args):
     }
     if not qwen:
         out["lru_stats"] = cache.stats()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_stack(wl, qwen, 4)
     print(json.dumps(out))
 
 
@@ -502,6 +594,66 @@ def cpu_baseline(wl, n_steps, idx_np, prec_np):
             "kind": "oracle", "sample": "first %d of the 1024 decode steps (route + 6 routed + 2 shared experts each), "
             "numpy fp64; expert quantisation outside the timed region" % n_steps,
             "host_cpus": os.cpu_count()}
+
+
+def cpu_baseline_prefill(wl, T, n_tok, idx_np, w_np):
+    """The CPU oracle on the first n_tok tokens of the prefill layer (its routed experts, all high-bit), with the
+    routing the GPU pass produced; scaled to the layer's T tokens."""
+    import numpy as np
+    from oracle import slicemoe_oracle as O
+    from paper_2512_12990_amd import synth
+    shp = wl.layer
+    x = synth.activations(wl.seed, T, shp.d_model, "bf16").float().numpy()[:n_tok]
+    need = sorted({int(e) for e in idx_np[:n_tok].ravel()})
+    experts = {}
+    for e in need:
+        wg, wu, wd = (w.float().cpu().numpy() for w in synth.expert_weights(wl.seed, 0, e, shp.d_model, shp.d_ff, "bf16", "cuda:0"))
+        experts[e] = O.quantize_expert(wg, wu, wd, shp.group, scale_dtype="bf16")
+    c0, t0 = time.process_time(), time.perf_counter()
+    O.prefill_layer(x.astype(np.float64), experts, idx_np[:n_tok], w_np[:n_tok].astype(np.float64))
+    wall = time.perf_counter() - t0
+    cpu = time.process_time() - c0
+    return {"value": wall / n_tok * T * 1e3, "unit": "ms/layer", "cores": max(1, int(round(cpu / wall))), "kind": "oracle",
+            "sample": "first %d of the %d tokens through the layer's routed experts (numpy fp64), scaled by %d/%d; expert "
+                      "quantisation outside the timed region" % (n_tok, T, T, n_tok), "host_cpus": os.cpu_count()}
+
+
+def cpu_baseline_stack(wl, qwen, n_layers):
+    """The CPU oracle on one token through the first n_layers MoE layers of the stack (each layer's input drawn
+    as the workload's activations: the layers are timed, not chained), scaled to us per token-layer."""
+    import numpy as np
+    from oracle import slicemoe_oracle as O
+    from paper_2512_12990_amd import synth
+    shp = wl.layer
+    d, E, k = shp.d_model, shp.n_experts, shp.top_k
+    x = synth.activations(wl.seed, n_layers, d, "bf16").float().numpy().astype(np.float64)
+    jobs = []
+    for l in range(n_layers):
+        if qwen:
+            z = O.router_logits(x[l][None].astype(np.float32), synth.router_weight(wl.seed, l, E, d).numpy())
+            mask = synth.fraction_masks(wl.seed, n_layers, 0, E, 0.3)[l]
+            bias = None
+            wsg = synth.shared_gate_weight(wl.seed, l, d, "bf16").float().numpy()
+        else:
+            z = synth.zipf_logits(wl.seed, l + 1, 1, E).numpy()
+            mask, bias = synth.cached_set_mask(wl.seed + l, E, E // 4, E // 8, 1.0)
+            wsg = None
+        idx, w = O.route(z, bias, k)
+        experts = {}
+        for tag in [int(e) for e in idx[0]] + [1000 + i for i in range(shp.n_shared)]:
+            f = shp.shared_d_ff if tag >= 1000 else shp.d_ff
+            wg, wu, wd = (t.float().cpu().numpy() for t in synth.expert_weights(wl.seed, l, tag, d, f, "bf16", "cuda:0"))
+            experts[tag] = O.quantize_expert(wg, wu, wd, shp.group, scale_dtype="bf16")
+        jobs.append((x[l], experts, idx[0], w[0], O.precision_select(idx[0], w[0], mask),
+                     [experts[1000 + i] for i in range(shp.n_shared)], wsg))
+    c0, t0 = time.process_time(), time.perf_counter()
+    for xl, experts, idx, w, prec, sh, wsg in jobs:
+        O.moe_layer(xl, experts, idx, w, prec, sh, wsg, True)
+    wall = time.perf_counter() - t0
+    cpu = time.process_time() - c0
+    return {"value": wall / n_layers * 1e6, "unit": "us/token-layer", "cores": max(1, int(round(cpu / wall))), "kind": "oracle",
+            "sample": "one token through %d MoE layers of the stack (route + %d routed + %d shared experts each), numpy fp64; "
+                      "expert quantisation outside the timed region" % (n_layers, k, shp.n_shared), "host_cpus": os.cpu_count()}
 
 
 if __name__ == "__main__":
