@@ -166,6 +166,72 @@ def test_prefill_qwen_layer_full_size_sampled_tokens(ctx):
         assert err <= TOL
 
 
+def test_prefill_more_pairs_than_the_grouping_registers_hold(ctx):
+    # 4100 tokens top-3 = 12300 (token, slot) pairs: every thread of the grouping kernel owns a run of 13,
+    # more than the eight it keeps in registers, so the pairs are read one by one in both passes; every
+    # expert gets a dozen 192-row tiles.  (8192 tokens top-4, the long-prompt bench line, runs the same path.)
+    T, E, k, d, f, G = 4100, 5, 3, 128, 64, 32
+    say("prefill, long pair list", T, E, k)
+    shp = synth.LayerShape(d, E, f, k, G, n_shared=1, shared_d_ff=64, act="bf16")
+    pair = LayerPair(ctx, shp, seed=27)
+    x = synth.activations(27, T, d, "bf16").cuda()
+    wr = synth.router_weight(27, 0, E, d, std=0.05).cuda()
+    y, idx, w, hist = B.smoe_prefill_histogram(ctx, pair.routed, pair.shared, x, k, w_router=wr, add_residual=True)
+    ridx, rw = _check_routing(ctx, x, wr, k, idx, w, hist, E)
+    assert int(hist.cpu().numpy().view(np.uint32).max()) > 192 * 8
+    yref = O.prefill_layer(t2np(x).astype(np.float64), pair.oracle_routed(), ridx, rw.astype(np.float32).astype(np.float64),
+                           pair.oracle_shared(), None, add_residual=True)
+    yg = t2np(y)
+    for t in range(T):
+        assert O.max_abs_rel(yg[t], yref[t]) <= TOL, t
+
+
+def test_prefill_qwen_24_layer_chain(ctx):
+    """The prefill workload as stated: 2048 tokens through 24 Qwen1.5-MoE-shaped layers, each layer's output
+    (plus residual, rescaled to unit RMS per token in place of the attention / normalisation blocks that are
+    outside the path) feeding the next.  Per layer: every routing index and the histogram exactly; at the
+    end the top-N slice order over the [24, 60] histogram; sampled tokens of sampled layers against the oracle,
+    which is handed the GPU's own layer input (teacher-forced)."""
+    wl = synth.QWEN_PREFILL
+    shp = wl.layer
+    T, L, E, k, d = wl.prefill_tokens, wl.n_layers, shp.n_experts, shp.top_k, shp.d_model
+    say("qwen prefill chain: quantising %d x %d experts" % (L, E))
+    layers = [LayerPair(ctx, shp, seed=wl.seed, layer=l, gen_device="cuda:0", keep_dense=False) for l in range(L)]
+    wr = [synth.router_weight(wl.seed, l, E, d).cuda() for l in range(L)]
+    x = synth.activations(wl.seed, T, d, "bf16").cuda()
+    scratch = torch.empty(B.smoe_prefill_bytes(T, E, k, d, shp.d_ff), dtype=torch.uint8, device="cuda:0")
+    samples = {0: (0, 2047), 11: (5, 1033), 23: (1, 700, 2046)}
+    hists = np.zeros((L, E), np.uint32)
+    kept = {}
+    for l in range(L):
+        y, idx, w, hist = B.smoe_prefill_histogram(ctx, layers[l].routed, None, x, k, w_router=wr[l], add_residual=True,
+                                                   scratch=scratch)
+        ridx, rw = _check_routing(ctx, x, wr[l], k, idx, w, hist, E)
+        hists[l] = hist.cpu().numpy().view(np.uint32)
+        if l in samples:
+            # the MoE term on its own (no residual) is what the oracle is compared with: next to x it is
+            # small, and a comparison of x + MoE(x) would mostly compare x with itself
+            y_moe = B.smoe_prefill_histogram(ctx, layers[l].routed, None, x, k, w_router=wr[l], add_residual=False,
+                                             scratch=scratch)[0]
+            kept[l] = (t2np(x), t2np(y_moe), ridx, rw)
+            resid = t2np(y) - (t2np(x) + t2np(y_moe))
+            assert np.abs(resid).max() <= 2.0 ** -7 * np.abs(t2np(y)).max()      # y = bf16(x + MoE(x)), two roundings apart
+        yf = y.float()
+        x = (yf * torch.rsqrt((yf * yf).mean(dim=1, keepdim=True) + 1e-6)).to(torch.bfloat16)
+    assert hists.sum() == L * T * k
+    n_keep = (2 * L * E) // 4
+    assert np.array_equal(B.smoe_topn_slices(hists, n_keep), O.topn_slices(hists, n_keep))
+    for l, toks in samples.items():
+        xin, yg, ridx, rw = kept[l]
+        for t in toks:
+            say("  oracle layer", l, "token", t)
+            yref = O.moe_layer(xin[t].astype(np.float64), layers[l].oracle_routed(), ridx[t],
+                               rw[t].astype(np.float32).astype(np.float64), np.ones(k, np.uint8))
+            err = O.max_abs_rel(yg[t], yref)
+            say("    max-abs-rel", err)
+            assert err <= TOL
+
+
 def test_prefill_random_small_shapes(ctx):
     # a seeded sweep over prefill shapes: token counts around the 192-row tile, d_model and d_ff any
     # multiple of 64 (ragged column tiles), every group size, with and without shared experts
