@@ -71,6 +71,8 @@ def main():
                          "figure is reported beside it) or as eager calls only")
     ap.add_argument("--replicas", type=int, default=4,
                     help="decode: layer replicas of the cold-weights figure (0 or 1: skip it)")
+    ap.add_argument("--no-stream-floor", action="store_true",
+                    help="decode: skip the plain-streaming reference measurement")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the timed passes, copy this many MiB device-to-device four times (a kernel of known "
                          "traffic, used to scale the HBM byte counters of a profiler run)")
@@ -333,6 +335,39 @@ def main():
                      "traffic": traffic, "traffic_source": traffic_src,
                      "traffic_over_algorithmic": (traffic / gu_bytes_per_launch) if traffic else None},
     }
+
+    # A practical roof measured in the same run: the same two launch shapes doing nothing but streaming the
+    # step's algorithmic bytes (gate/up bytes on the gate/up grid, down bytes on the down grid) out of the
+    # bank's store, windows rotating through it so that nothing is re-read from a cache; and one launch
+    # over the sum.
+    if TT == 1 and args.shape == "dsv2" and not args.no_stream_floor:
+        m["graphs"] = None
+        sread = B.lib().smoe_stream_read
+        sink = torch.zeros(64, dtype=torch.uint8, device=dev)
+        base = routed._base
+        gub, dnb = int(gu_bytes_per_launch) & ~255, int(bytes_per_step - gu_bytes_per_launch) & ~255
+        span = (routed.nbytes - gub - dnb - 4096) & ~255
+
+        def floor_step(two):
+            def step(t):
+                off = (t * (gub + dnb)) % span
+                if two:
+                    rc = sread(ctx.h, C.c_void_p(base + off), C.c_size_t(gub), C.c_int(512), vp(sink))
+                    rc = rc or sread(ctx.h, C.c_void_p(base + off + gub), C.c_size_t(dnb), C.c_int(256), vp(sink))
+                else:
+                    rc = sread(ctx.h, C.c_void_p(base + off), C.c_size_t(gub + dnb), C.c_int(768), vp(sink))
+                if rc != 0:
+                    raise B.SmoeError("stream read failed: %d" % rc)
+            return step
+        f2 = measure(floor_step(True))
+        f1 = measure(floor_step(False))
+        out["stream_floor"] = {"two_launches_us_per_step": f2["ms_per_step"] * 1e3, "one_launch_us_per_step": f1["ms_per_step"] * 1e3,
+                               "bytes": [gub, dnb], "work_groups": [512, 256],
+                               "value_over_two_launch_floor": ms_per_step / f2["ms_per_step"],
+                               "note": "plain 16-byte-per-lane streaming reads of the step's algorithmic bytes from the bank store "
+                                       "(no routing, no arithmetic, no dependency between the two launches' data), same launch "
+                                       "mode as value"}
+        del f1, f2
 
     # The same steps with the weights cold: R replicas of the layer (different weights, same shape), step t
     # on replica t mod R, so that the bytes a step reads were last touched R steps -- R times the hot set -- ago

@@ -93,6 +93,11 @@ int smoe_last_hip_error(const smoe_ctx* ctx); /* hipError_t of the last failing 
  * number of calls recorded since the last read, and releases the events. */
 int smoe_ctx_timing(smoe_ctx* ctx, int enable);
 int smoe_ctx_timing_read(smoe_ctx* ctx, double* gateup_us, double* down_us, int* n_calls);
+/* Measurement aid, no part of the method.  Enqueues a kernel of n_workgroups x 512 threads that reads
+ * bytes (a multiple of 16 is used) from buf_dev with 16-byte loads and does nothing else: what the same
+ * bytes cost when they are only streamed, as a practical roof beside the decode kernels.  sink_dev: 16
+ * bytes of device memory (never written in practice). */
+int smoe_stream_read(smoe_ctx* ctx, const void* buf_dev, size_t bytes, int n_workgroups, void* sink_dev);
 
 /* ---- quantize / slice (Section 4.2; Table 1 note 1) ------------------------------------- */
 /* Bytes of device memory a bank's store needs. */

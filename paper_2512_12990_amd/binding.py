@@ -46,7 +46,7 @@ _lib = None
 
 EXPORTS = [
     "smoe_workspace_bytes", "smoe_ctx_create", "smoe_ctx_destroy", "smoe_strerror", "smoe_last_hip_error", "smoe_ctx_timing",
-    "smoe_ctx_timing_read",
+    "smoe_ctx_timing_read", "smoe_stream_read",
     "smoe_bank_bytes", "smoe_bank_create", "smoe_bank_destroy", "smoe_quantize_slice", "smoe_export_codes",
     "smoe_route", "smoe_expert_ffn", "smoe_decode_layer", "smoe_decode_layer_multi", "smoe_static_scratch_bytes", "smoe_decode_layer_static",
     "smoe_prefill_bytes", "smoe_prefill_histogram", "smoe_topn_slices",

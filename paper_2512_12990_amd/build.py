@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslicemoe.so")
-SOURCES = ["api.hip", "quantize.hip", "route.hip", "decode.hip", "prefill.hip", "host_cache.cpp"]
+SOURCES = ["api.hip", "quantize.hip", "route.hip", "decode.hip", "prefill.hip", "probe.hip", "host_cache.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 instructions are disabled on purpose: the compiler must not form them
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -173,3 +173,19 @@ def test_out_of_range_expert_index_is_clamped(ctx):
     assert torch.equal(y_bad, y_ok) and torch.equal(p1, p2)
     yref = O.moe_layer(t2np(x).astype(np.float64), pair.oracle_routed(), [0, 2, 5], [0.5, 0.3, 0.2], [1, 1, 0], [])
     assert O.max_abs_rel(t2np(y_ok), yref) <= TOL["bf16"]
+
+
+def test_stream_read_measurement_aid(ctx):
+    # the streaming-read kernel bench.py uses as a practical roof: runs, and rejects bad arguments
+    say("stream read aid")
+    lib = B.lib()
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda:0")
+    sink = torch.zeros(64, dtype=torch.uint8, device="cuda:0")
+    p = lambda t: C.c_void_p(t.data_ptr())
+    assert lib.smoe_stream_read(ctx.h, p(buf), C.c_size_t(1 << 20), 16, p(sink)) == 0
+    assert lib.smoe_stream_read(ctx.h, p(buf), C.c_size_t(1000), 3, p(sink)) == 0      # ragged size: whole 16-byte units only
+    torch.cuda.synchronize()
+    assert int(sink.sum()) == 0
+    assert lib.smoe_stream_read(ctx.h, None, C.c_size_t(1 << 20), 16, p(sink)) == -1
+    assert lib.smoe_stream_read(ctx.h, C.c_void_p(buf.data_ptr() + 4), C.c_size_t(1 << 10), 16, p(sink)) == -3
+    assert lib.smoe_stream_read(ctx.h, p(buf), C.c_size_t(1 << 20), 0, p(sink)) == -2
