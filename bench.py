@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="decode: how the timed steps are launched: replayed from a captured HIP graph (default; the eager "
                          "figure is reported beside it) or as eager calls only")
+    ap.add_argument("--single-launch", action="store_true",
+                    help="decode: also time the same steps with one kernel launch per call (smoe_ctx_single_launch)")
     ap.add_argument("--replicas", type=int, default=4,
                     help="decode: layer replicas of the cold-weights figure (0 or 1: skip it)")
     ap.add_argument("--no-stream-floor", action="store_true",
@@ -233,6 +235,20 @@ def main():
     ms_per_step = m["ms_per_step"]
     windows = [w * 1e3 / TT for w in m["windows"]]
 
+    # The same steps with one kernel launch per call instead of two (smoe_ctx_single_launch; an option, slower here)
+    one = None
+    if TT == 1 and args.single_launch:
+        m["graphs"] = None
+        ctx.single_launch(True)
+        m1 = measure(step)
+        calls1, timeouts1 = ctx.single_launch_status()
+        ctx.single_launch(False)
+        one = {"us_per_token": m1["ms_per_step"] * 1e3, "eager_us_per_token": m1["eager_ms_per_step"] * 1e3,
+               "calls_that_took_it": calls1, "work_groups_timed_out": timeouts1,
+               "note": "same steps, same launch mode as value, one kernel launch per call (gate/up phase, in-kernel hand-over of h, "
+                       "down phase); bit-identical results"}
+        del m1
+
     # A plain device-to-device copy of 256 MiB, for scale: what this machine's HBM delivers to a streaming
     # kernel (bytes read + bytes written per second).
     csrc = torch.full((256 << 20,), 7, dtype=torch.uint8, device=dev)
@@ -335,6 +351,9 @@ def main():
                      "traffic": traffic, "traffic_source": traffic_src,
                      "traffic_over_algorithmic": (traffic / gu_bytes_per_launch) if traffic else None},
     }
+
+    if one is not None:
+        out["single_launch"] = one
 
     # A practical roof measured in the same run: the same two launch shapes doing nothing but streaming the
     # step's algorithmic bytes (gate/up bytes on the gate/up grid, down bytes on the down grid) out of the

@@ -93,6 +93,26 @@ int smoe_last_hip_error(const smoe_ctx* ctx); /* hipError_t of the last failing 
  * number of calls recorded since the last read, and releases the events. */
 int smoe_ctx_timing(smoe_ctx* ctx, int enable);
 int smoe_ctx_timing_read(smoe_ctx* ctx, double* gateup_us, double* down_us, int* n_calls);
+/* Single-launch decode (Section 6.1 item 1: the fused decode step; an option of this implementation,
+ * off by default).  With the mode on, smoe_expert_ffn / smoe_decode_layer run one token's routing,
+ * gate/up projections, the hand-over of the SwiGLU vector and the down projection in ONE kernel launch
+ * instead of two, when the case fits: d_model <= 2048, d_model / 8 no larger than the number of gate/up
+ * work-groups (at most 512), timing off, and all work-groups of the launch resident on the device
+ * together (checked from the occupancy the runtime reports).  Cases that do not fit,
+ * smoe_decode_layer_multi and smoe_decode_layer_static keep the two launches.  Results are
+ * bit-identical in both modes.  On MI355X the two launches are the faster form (15 against 21 us per
+ * token on the DeepSeek-V2-Lite-shaped layer), which is why the mode is an option.
+ *   The work-groups of the single launch wait for each other inside the kernel.  The wait is bounded:
+ * after spin_limit polls (0: the default, 2^20, of the order of a second) a work-group goes on with
+ * whatever it finds and counts itself in n_timeouts, so a launch always ends; a call whose work-groups
+ * cannot all run together (a device shared with another busy process) therefore shows up as a non-zero
+ * n_timeouts and a wrong result, never as a hang.  Enabling enqueues a small kernel on the ctx stream
+ * that clears the hand-over words in the first 64 KiB of the workspace (SMOE_ESIZE for a context
+ * without one); calling it again clears them again.  smoe_ctx_single_launch_status synchronises the
+ * stream and returns the number of decode calls that took the single launch so far and the
+ * work-groups that gave up waiting since the words were last cleared. */
+int smoe_ctx_single_launch(smoe_ctx* ctx, int enable, int spin_limit);
+int smoe_ctx_single_launch_status(smoe_ctx* ctx, long long* n_calls, unsigned* n_timeouts);
 /* Measurement aid, no part of the method.  Enqueues a kernel of n_workgroups x 512 threads that reads
  * bytes (a multiple of 16 is used) from buf_dev with 16-byte loads and does nothing else: what the same
  * bytes cost when they are only streamed, as a practical roof beside the decode kernels.  sink_dev: 16

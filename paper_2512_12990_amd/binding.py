@@ -46,7 +46,7 @@ _lib = None
 
 EXPORTS = [
     "smoe_workspace_bytes", "smoe_ctx_create", "smoe_ctx_destroy", "smoe_strerror", "smoe_last_hip_error", "smoe_ctx_timing",
-    "smoe_ctx_timing_read", "smoe_stream_read",
+    "smoe_ctx_timing_read", "smoe_stream_read", "smoe_ctx_single_launch", "smoe_ctx_single_launch_status",
     "smoe_bank_bytes", "smoe_bank_create", "smoe_bank_destroy", "smoe_quantize_slice", "smoe_export_codes",
     "smoe_route", "smoe_expert_ffn", "smoe_decode_layer", "smoe_decode_layer_multi", "smoe_static_scratch_bytes", "smoe_decode_layer_static",
     "smoe_prefill_bytes", "smoe_prefill_histogram", "smoe_topn_slices",
@@ -115,6 +115,16 @@ class Ctx:
         g, d, n = C.c_double(), C.c_double(), C.c_int()
         _chk(lib().smoe_ctx_timing_read(self.h, C.byref(g), C.byref(d), C.byref(n)), "smoe_ctx_timing_read", self.h)
         return g.value, d.value, n.value
+
+    def single_launch(self, enable: bool, spin_limit: int = 0):
+        """One kernel launch per decode call where the case fits (see smoe_ctx_single_launch)."""
+        _chk(lib().smoe_ctx_single_launch(self.h, C.c_int(int(enable)), C.c_int(spin_limit)), "smoe_ctx_single_launch", self.h)
+
+    def single_launch_status(self):
+        """(decode calls that took the single launch, work-groups that gave up waiting); synchronises."""
+        n, t = C.c_longlong(), C.c_uint()
+        _chk(lib().smoe_ctx_single_launch_status(self.h, C.byref(n), C.byref(t)), "smoe_ctx_single_launch_status", self.h)
+        return n.value, t.value
 
     def close(self):
         if self.h:

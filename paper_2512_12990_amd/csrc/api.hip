@@ -41,6 +41,9 @@ extern "C" int smoe_ctx_create(int device, void* hip_stream, void* workspace_dev
   c->last_hip = 0; c->n_cu = 256; c->timing = 0; c->timing_events = nullptr;
   for (size_t& g : c->down_lds_granted) g = 0;
   for (size_t& g : c->route_lds_granted) g = 0;
+  c->one_launch = 0; c->one_spin_limit = 0; c->one_calls = 0;
+  for (int& b : c->one_blocks_per_cu) b = 0;
+  for (size_t& g : c->one_lds_seen) g = 0;
   hipError_t e = hipSetDevice(device);
   if (e == hipSuccess) {
     hipDeviceProp_t prop;

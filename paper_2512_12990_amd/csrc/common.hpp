@@ -47,6 +47,12 @@ struct smoe_ctx {
   void* timing_events;   // std::vector<hipEvent_t>*, four events per decode call
   size_t down_lds_granted[48];   // dynamic LDS already granted to each down_kernel instantiation on this device
   size_t route_lds_granted[2];   // likewise for route_batch_kernel (bf16, fp32 activations)
+  // single-launch decode (smoe_ctx_single_launch)
+  int one_launch;                // the mode is on
+  int one_spin_limit;            // polls before a work-group gives up waiting for the others
+  long long one_calls;           // decode calls that took the single launch
+  int one_blocks_per_cu[12];     // resident work-groups per CU of each decode_one_kernel instantiation (0: not asked yet, -1: none)
+  size_t one_lds_seen[12];       // dynamic LDS that figure was asked for
 };
 
 struct smoe_bank {
@@ -68,6 +74,7 @@ struct RouteRec {
 
 // workspace layout (offsets in bytes)
 #define WS_REC_OFF 0                         // RouteRec
+#define WS_SYNC_OFF (8 << 10)                // hand-over words of the single-launch decode kernel (parity, timeouts, two flag arrays)
 #define WS_IDX_OFF (16 << 10)                // routing scratch of smoe_decode_layer without given logits
 #define WS_H_OFF (64 << 10)                  // float h[total_f]
 

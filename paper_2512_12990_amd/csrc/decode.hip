@@ -173,6 +173,12 @@ template <int FMT> struct PlaneT { typedef uint4 t; enum { BYTES = 16 }; };
 template <> struct PlaneT<1> { typedef uint2 t; enum { BYTES = 8 }; };
 template <> struct PlaneT<2> { typedef uint3 t; enum { BYTES = 12 }; };
 template <int FMT> __device__ __forceinline__ typename PlaneT<FMT>::t pload(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff);
+// The same load at device scope (sc1): it returns what other compute dies have written through, whatever
+// this die's L2 holds.
+__device__ __forceinline__ uint4 bload128_dev(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 16);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 template <> __device__ __forceinline__ uint4 pload<0>(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) { return bload128(r, voff, soff); }
 template <> __device__ __forceinline__ uint2 pload<1>(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) { return bload64(r, voff, soff); }
 template <> __device__ __forceinline__ uint3 pload<2>(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
@@ -648,13 +654,29 @@ struct GuPiece {
   int prec;
 };
 
-template <int ACT, int SCB, int FMT>
-__global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, const float* bias, const uint8_t* mask, const void* x_in,
-                                                        int E, int k, int do_route, int d_model, int n_wg, int n_se,
-                                                        DecodeArgs a) {
-  __shared__ int sel_lds[SMOE_MAX_TOPK], prec_lds[SMOE_MAX_TOPK];
-  __shared__ __align__(16) uint8_t xvec[StageTraits<ACT>::COMBO_BYTES];
-  __shared__ float2 xcs[64];
+// hand-over words of the single-launch kernel (see grid_wait)
+#define ONE_MAX_WG 512                                 /* work-groups a single launch can hand over between */
+#define ONE_PARITY 0                                   /* word: which flag array the running launch uses */
+#define ONE_TIMEOUTS 1                                 /* word: work-groups that ever gave up waiting */
+#define ONE_FLAGS(par) (64 + (par) * ONE_MAX_WG)       /* word offset of flag array 0 / 1: one word per work-group */
+#define ONE_SYNC_WORDS (64 + 2 * ONE_MAX_WG)
+
+// A value other work-groups read: within one launch (WT, the single-launch kernel) it is stored
+// write-through at device scope, so that once the store is acknowledged (vmcnt) the value is where
+// every other compute die's loads find it, without a write-back of the whole L2 afterwards; across a
+// kernel boundary an ordinary store does.
+template <bool WT, typename T> __device__ __forceinline__ void put_shared(T* p, T v) {
+  if (WT) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
+}
+
+// The gate/up phase of one work-group (the body of gateup_kernel, and the first half of the
+// single-launch kernel).  KARG_BYTES: size of the calling kernel's argument segment.  WT: h and the
+// routing record are stored write-through at device scope (see put_shared).
+template <int ACT, int SCB, int FMT, int KARG_BYTES, bool WT>
+__device__ __forceinline__ void gateup_body(const float* logits, const float* bias, const uint8_t* mask, const void* x_in, int E, int k,
+                                            int do_route, int d_model, int n_wg, int n_se, DecodeArgs& a, int* sel_lds, int* prec_lds,
+                                            uint8_t* xvec, float2* xcs, unsigned* const* sync, unsigned* par) {
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   // Several tokens in one launch: grid (8, tokens, work-groups / 8), so that the work-groups that
   // read the same weight rows for different tokens are dispatched together on one XCD and share
@@ -678,8 +700,10 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
   RouteRegs rr = {};
   if (stager) load8_raw<ACT>(x_in, (size_t)xt * 8, xraw);
   route_load(in, lane, rr, router);
-  KARGS_FETCH(DEC_LEAD_BYTES + (int)sizeof(DecodeArgs));      // four pointers and six 4-byte leading parameters, then the struct
+  KARGS_FETCH(KARG_BYTES);      // four pointers and six 4-byte leading parameters, then the struct(s)
   __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+  // (single launch: the parity of the hand-over, needed when the work-group arrives -- see grid_wait)
+  if (WT) *par = __hip_atomic_load(*sync + ONE_PARITY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);      // (consumed at the end of the phase)
   if (tok) {
     a.h += (size_t)tok * DEC_H_STRIDE(a.n_shared * a.f_s, a.f_r);
     a.rec += tok;
@@ -752,7 +776,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
         float uv = lane_value(x, um[t], ul[t], pc.prec, (int)zu[t], scale_val<SCB>(su[t], odd));
         av = wave_sum_to63(av);
         uv = wave_sum_to63(uv);
-        if (lane == 63) a.h[pc.hb + n_wg * t] = av * __builtin_amdgcn_rcpf(1.0f + __expf(-av)) * uv;
+        if (lane == 63) put_shared<WT>(&a.h[pc.hb + n_wg * t], av * __builtin_amdgcn_rcpf(1.0f + __expf(-av)) * uv);
       }
     }
   };
@@ -787,7 +811,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
     if (router) {                                        // publish for the down kernel and the caller
       if (!have_w) myw = E <= 64 ? route_weights<1>(in, a, lane, rr, mysel) : route_weights<4>(in, a, lane, rr, mysel);
       if (lane < k) {
-        a.rec->sel[lane] = mysel; a.rec->prec[lane] = myprec; a.rec->w[lane] = myw;
+        put_shared<WT>(&a.rec->sel[lane], mysel); put_shared<WT>(&a.rec->prec[lane], myprec); put_shared<WT>(&a.rec->w[lane], myw);
         if (a.prec_out) a.prec_out[lane] = (uint8_t)myprec;
         if (a.idx_out) a.idx_out[lane] = mysel;
         if (a.w_out) a.w_out[lane] = myw;
@@ -815,7 +839,7 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
         }
         g = 1.0f / (1.0f + expf(-wave_sum(p)));
       }
-      if (lane == 0) a.rec->gamma = g;
+      if (lane == 0) put_shared<WT>(&a.rec->gamma, g);
     }
   }
   XR<ACT> x = {};
@@ -843,6 +867,17 @@ __global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, con
       e_cur = uni(e_cur + nb);
     }
   }
+}
+
+template <int ACT, int SCB, int FMT>
+__global__ __launch_bounds__(DEC_NT) void gateup_kernel(const float* logits, const float* bias, const uint8_t* mask, const void* x_in,
+                                                        int E, int k, int do_route, int d_model, int n_wg, int n_se,
+                                                        DecodeArgs a) {
+  __shared__ int sel_lds[SMOE_MAX_TOPK], prec_lds[SMOE_MAX_TOPK];
+  __shared__ __align__(16) uint8_t xvec[StageTraits<ACT>::COMBO_BYTES];
+  __shared__ float2 xcs[64];
+  gateup_body<ACT, SCB, FMT, DEC_LEAD_BYTES + (int)sizeof(DecodeArgs), false>(logits, bias, mask, x_in, E, k, do_route, d_model, n_wg, n_se, a,
+                                                                             sel_lds, prec_lds, xvec, xcs, nullptr, nullptr);
 }
 
 // ---------------------------------------------------------------------------------- gate/up kernel, wide rows
@@ -1009,24 +1044,76 @@ __device__ __forceinline__ float wave_sum4_to_last(float v0, float v1, float v2,
 
 #define DEC_HQ 4      // h words of 8 values per lane that cover one combo (64 chunks)
 
-template <int ACT, int SCB, int FMT, int RPW>      // RPW output rows per work-group
-__global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const float* h, int n_combo_s, int n_pieces, int psh, int f_s,
-                                                      int f_r, int ks_s, int ks_r, int inv_ks_s, int inv_ks_r, int nsf,
-                                                      DecodeArgs a) {
-  extern __shared__ __align__(16) uint8_t dyn[];     // [per wave: h digits of one combo, chunk figures][partials]
+// What the single-launch kernel adds to the arguments of the two kernels.
+struct OneArgs {
+  unsigned* sync;                  // hand-over words in the workspace, see below
+  int n_combo_s, n_pieces, psh;    // the down split (the down kernel's leading parameters)
+  int n_dn;                        // work-groups that go on to a down phase
+  int spin_limit;                  // polls before a work-group gives up waiting
+  int pad0;
+};
+static_assert(sizeof(DecodeArgs) + sizeof(OneArgs) + DEC_LEAD_BYTES <= 8 * 64, "KARGS_FETCH covers eight lines");
+
+// The grid-wide hand-over of the single-launch kernel.  No read-modify-write: every work-group owns one
+// word of a flag array and sets it (write-through) once all its waves' stores of h are acknowledged; a
+// waiting wave reads the whole array with device-scope loads until every word is set.  Two arrays take
+// turns: the launch uses the one the parity word names (every work-group reads the parity in its first
+// instructions, long before it arrives), work-group 0 clears the other array for the next launch and,
+// once its own wait is over -- so every work-group has arrived and has therefore read the parity --
+// flips the parity.  Launches of one context are ordered by its stream, so the next launch finds its
+// array cleared and the parity flipped.  The wait is bounded: after spin_limit polls the work-group
+// goes on (its result is then wrong) and counts itself in the timeouts word, which the host reads
+// back; work-group 0 flips the parity all the same, and the work-groups that arrive late only set
+// words of an array that is cleared again before it is next used.  All work-groups of the launch
+// must be resident together (the host checks the occupancy).
+__device__ __forceinline__ void grid_set_flag(unsigned* sync, unsigned par, int wg) {
+  __hip_atomic_store(sync + ONE_FLAGS(par) + wg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// one wave; n_wg <= ONE_MAX_WG: lane l looks at words 8 l .. 8 l + 7
+__device__ __forceinline__ void grid_wait(unsigned* sync, unsigned par, int n_wg, int wg, int spin_limit, int lane) {
+  if (wg == 0) {      // the other array, all of it, for the next launch
+    uint4* o = (uint4*)(sync + ONE_FLAGS(par ^ 1u) + 8 * lane);
+    o[0] = make_uint4(0, 0, 0, 0);
+    o[1] = make_uint4(0, 0, 0, 0);
+  }
+  const __amdgpu_buffer_rsrc_t RF = make_rsrc(sync + ONE_FLAGS(par), (unsigned)n_wg * 4u);      // words past n_wg read as 0
+  const int mine = min(8, max(0, n_wg - 8 * lane));                                               // words this lane must see set
+  int spins = 0;
+  for (;;) {
+    const uint4 f0 = bload128_dev(RF, (unsigned)lane * 32u, 0), f1 = bload128_dev(RF, (unsigned)lane * 32u, 16);
+    const int set = (int)(f0.x + f0.y + f0.z + f0.w + f1.x + f1.y + f1.z + f1.w);
+    if (__builtin_amdgcn_ballot_w64(set < mine) == 0) break;
+    if (++spins >= spin_limit) {
+      if (lane == 0) __hip_atomic_fetch_add(sync + ONE_TIMEOUTS, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      break;
+    }
+    __builtin_amdgcn_s_sleep(1);
+  }
+  if (wg == 0 && lane == 0) __hip_atomic_store(sync + ONE_PARITY, par ^ 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The down phase of one work-group: the body of down_kernel, and the second half of the single-launch
+// kernel (ONE).  There the expert and precision of a routed slot come from the work-group's own routing
+// decision in LDS, a wave first puts the loads of its piece's first rows in flight and only then joins
+// the hand-over (the last wave, which does the polling, issues no loads before it: a poll's answer would
+// queue behind them), and h and the gate weights are read after it.
+template <int ACT, int SCB, int FMT, int RPW, bool ONE>
+__device__ __forceinline__ void down_body(const int* rec, const float* h, int n_combo_s, int n_pieces, int psh, int f_s, int f_r, int ks_s,
+                                          int ks_r, int inv_ks_s, int inv_ks_r, int nsf, const DecodeArgs& a, uint8_t* dyn, int wg, int tok,
+                                          const int* sel_lds, const int* prec_lds, const OneArgs* one, int n_wg, unsigned par) {
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   constexpr int XB = StageTraits<ACT>::COMBO_BYTES, WS = XB + 64 * 8;
   constexpr int DEC_RB = ACT == SMOE_BF16 ? 4 : 2;      // rows per batch (the fp32 path keeps 32 activations per lane in registers)
   uint8_t* xbuf = dyn + wave * WS;
   float2* xcs = (float2*)(xbuf + XB);
   float* part = (float*)(dyn + DEC_NW * WS);         // [combo][row]
-  const int tok = blockIdx.y;                          // see gateup_kernel
-  const int n0 = ((int)blockIdx.x + 8 * (int)blockIdx.z) * RPW;
-  if (tok) {
-    rec += tok * (int)(sizeof(RouteRec) / 4);
-    h += (size_t)tok * DEC_H_STRIDE(nsf, f_r);
+  const int n0 = wg * RPW;
+  bool kargs_here = ONE, handed_over = !ONE;
+  const bool poller = ONE && wave == DEC_NW - 1;
+  if (ONE && wave >= n_pieces) {                     // a wave without a piece still takes part in the hand-over
+    if (poller) grid_wait(one->sync, par, n_wg, wg, one->spin_limit, lane);
+    lds_barrier();
   }
-  bool kargs_here = false;
 
   for (int p = wave; p < n_pieces; p += DEC_NW) {
     // ---- which piece (leading parameters only)
@@ -1042,20 +1129,31 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
     // 16+s, 32+s, gamma in word 48)
     const __amdgpu_buffer_rsrc_t RH = make_rsrc(h + hoff, (unsigned)cw * 128u);
     uint4 hraw[DEC_HQ][2];
+    int rec_word = 0;
+    auto load_h = [&]() {
 #pragma unroll
-    for (int q = 0; q < DEC_HQ; q++) {
-      hraw[q][0] = bload128(RH, (unsigned)(lane + 64 * q) * 32u, 0);
-      hraw[q][1] = bload128(RH, (unsigned)(lane + 64 * q) * 32u, 16);
+      for (int q = 0; q < DEC_HQ; q++) {
+        // (single launch: h and the record were written in this very launch, by other compute dies too)
+        hraw[q][0] = ONE ? bload128_dev(RH, (unsigned)(lane + 64 * q) * 32u, 0) : bload128(RH, (unsigned)(lane + 64 * q) * 32u, 0);
+        hraw[q][1] = ONE ? bload128_dev(RH, (unsigned)(lane + 64 * q) * 32u, 16) : bload128(RH, (unsigned)(lane + 64 * q) * 32u, 16);
+      }
+      rec_word = ONE ? __hip_atomic_load(rec + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : rec[lane];
+    };
+    int e, prec;
+    if (ONE) {
+      e = is_sh ? slot : uni(sel_lds[is_sh ? 0 : slot]);
+      prec = is_sh ? 1 : uni(prec_lds[is_sh ? 0 : slot]);
+      if (handed_over) load_h();
+    } else {
+      load_h();
+      if (!kargs_here) {      // two pointers and ten 4-byte leading parameters, then the struct
+        KARGS_FETCH(DEC_LEAD_BYTES + (int)sizeof(DecodeArgs));
+        kargs_here = true;
+      }
+      __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+      e = is_sh ? slot : __builtin_amdgcn_readlane(rec_word, slot);
+      prec = is_sh ? 1 : __builtin_amdgcn_readlane(rec_word, SMOE_MAX_TOPK + slot);
     }
-    const int rec_word = rec[lane];
-    if (!kargs_here) {      // two pointers and ten 4-byte leading parameters, then the struct
-      KARGS_FETCH(DEC_LEAD_BYTES + (int)sizeof(DecodeArgs));
-      kargs_here = true;
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
-    const int e = is_sh ? slot : __builtin_amdgcn_readlane(rec_word, slot);
-    const int prec = is_sh ? 1 : __builtin_amdgcn_readlane(rec_word, SMOE_MAX_TOPK + slot);
-    const float wt = __int_as_float(__builtin_amdgcn_readlane(rec_word, is_sh ? 3 * SMOE_MAX_TOPK : 2 * SMOE_MAX_TOPK + slot));
 
     // ---- the piece's rows: per batch of DEC_RB rows issue metadata, then planes; then h -> digits
     // while they stream in; then the dot products
@@ -1075,10 +1173,17 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
     unsigned zo = (unsigned)e * md.zs32 + (unsigned)(n0 + row0) * ng + (unsigned)g0;
     unsigned so = (unsigned)e * md.ss32 + (unsigned)(n0 + row0) * srow + (SCB ? (unsigned)(g0 & ~1) * 2u : (unsigned)g0 * 4u);
     XR<ACT> x = {};
+    float wt = 0.0f;
     for (int b0 = 0; b0 < n_rows; b0 += DEC_RB) {
       const int nr = min(DEC_RB, n_rows - b0);
       typename PlaneT<FMT>::t wm[DEC_RB], wl[DEC_RB];
       uint32_t zz[DEC_RB], ss[DEC_RB];
+      if (ONE && !handed_over && poller) {           // (b0 == 0 of the wave's first piece)
+        grid_wait(one->sync, par, n_wg, wg, one->spin_limit, lane);
+        lds_barrier();
+        load_h();
+        handed_over = true;
+      }
 #pragma unroll
       for (int r = 0; r < DEC_RB; r++) {
         zz[r] = bload8(R.zp, r < nr ? vz : DEC_OOB, zo + (unsigned)r * ng);
@@ -1092,7 +1197,13 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
       }
       __builtin_amdgcn_sched_barrier(0);
       po += DEC_RB * rowb; zo += DEC_RB * ng; so += DEC_RB * srow;
+      if (ONE && !handed_over) {                     // the rows are in flight: now wait for the other work-groups' h
+        lds_barrier();
+        load_h();
+        handed_over = true;
+      }
       if (b0 == 0) {
+        wt = __int_as_float(__builtin_amdgcn_readlane(rec_word, is_sh ? 3 * SMOE_MAX_TOPK : 2 * SMOE_MAX_TOPK + slot));
         // h -> LDS in digit form (the four lanes of a quad hold one chunk), back as one chunk per lane
 #pragma unroll
         for (int q = 0; q < DEC_HQ; q++) {
@@ -1125,6 +1236,48 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
     if (a.add_residual) acc += load_act<ACT>(a.x, n);
     store_act<ACT>(a.y, n, acc);
   }
+}
+
+template <int ACT, int SCB, int FMT, int RPW>      // RPW output rows per work-group
+__global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const float* h, int n_combo_s, int n_pieces, int psh, int f_s,
+                                                      int f_r, int ks_s, int ks_r, int inv_ks_s, int inv_ks_r, int nsf,
+                                                      DecodeArgs a) {
+  extern __shared__ __align__(16) uint8_t dyn[];     // [per wave: h digits of one combo, chunk figures][partials]
+  const int tok = blockIdx.y;                          // see gateup_kernel
+  if (tok) {
+    rec += tok * (int)(sizeof(RouteRec) / 4);
+    h += (size_t)tok * DEC_H_STRIDE(nsf, f_r);
+  }
+  down_body<ACT, SCB, FMT, RPW, false>(rec, h, n_combo_s, n_pieces, psh, f_s, f_r, ks_s, ks_r, inv_ks_s, inv_ks_r, nsf, a, dyn,
+                                       (int)blockIdx.x + 8 * (int)blockIdx.z, tok, nullptr, nullptr, nullptr, 0, 0u);
+}
+
+// ---------------------------------------------------------------------------------- single-launch kernel
+// One token, rows of at most 64 chunks: the gate/up phase of n_wg work-groups, a grid-wide hand-over of
+// h, and the down phase in the first n_dn of them, all in one launch (an option of the context; the
+// two launches are the default because they measured faster on this hardware: data handed from one
+// compute die to another inside a kernel costs several microseconds, the end of a kernel a fraction
+// of one).  Same arithmetic in the same order as the two kernels: results are bit-identical.
+template <int ACT, int SCB, int FMT>
+__global__ __launch_bounds__(DEC_NT, 4) void decode_one_kernel(const float* logits, const float* bias, const uint8_t* mask, const void* x_in,
+                                                               int E, int k, int do_route, int d_model, int n_wg, int n_se, DecodeArgs a,
+                                                               OneArgs o) {
+  __shared__ int sel_lds[SMOE_MAX_TOPK], prec_lds[SMOE_MAX_TOPK];
+  __shared__ __align__(16) uint8_t xvec[StageTraits<ACT>::COMBO_BYTES];
+  __shared__ float2 xcs[64];
+  extern __shared__ __align__(16) uint8_t dyn[];
+  unsigned par = 0;
+  gateup_body<ACT, SCB, FMT, DEC_LEAD_BYTES + (int)sizeof(DecodeArgs) + (int)sizeof(OneArgs), true>(logits, bias, mask, x_in, E, k, do_route, d_model,
+                                                                                           n_wg, n_se, a, sel_lds, prec_lds, xvec, xcs, &o.sync, &par);
+  // every wave's part of h (and work-group 0's routing record) acknowledged before the work-group counts itself in
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  par = (unsigned)uni((int)par) & 1u;
+  __syncthreads();
+  const int wg = blockIdx.x;
+  if (threadIdx.x == 0) grid_set_flag(o.sync, par, wg);
+  if (wg >= o.n_dn) return;
+  down_body<ACT, SCB, FMT, DEC_RPW, true>((const int*)a.rec, a.h, o.n_combo_s, o.n_pieces, o.psh, a.f_s, a.f_r, a.ks_s, a.ks_r, a.inv_ks_s,
+                                          a.inv_ks_r, a.n_shared * a.f_s, a, dyn, wg, 0, sel_lds, prec_lds, &o, n_wg, par);
 }
 
 // ---------------------------------------------------------------------------------- host entry
@@ -1162,6 +1315,40 @@ static int launch_decode_t(smoe_ctx* ctx, const RouteIn& in, DecodeArgs& a, int 
   const bool wide = a.d_model > 2048;                 // rows of more than 64 chunks: the k-sliced gate/up kernel
   const int* recw = (const int*)a.rec;
   const int nsf = a.n_shared * a.f_s;
+  // ---- single launch, if the context asks for it and the case fits: one token, rows of at most 64
+  // chunks, 8 output rows per down work-group, no more down work-groups than gate/up work-groups, the
+  // context's own workspace (its hand-over words were cleared when the mode was switched on), and all
+  // work-groups resident at once
+  if (ctx->one_launch && T == 1 && !wide && RPW == DEC_RPW && n_dn <= n_wg && n_wg <= ONE_MAX_WG && !evs && (uint8_t*)a.rec == ctx->ws + WS_REC_OFF) {
+    const size_t lds1 = lds;
+    int& per_cu = ctx->one_blocks_per_cu[((ACT * 2 + SCB) * 3 + FMT)];
+    size_t& lds_seen = ctx->one_lds_seen[((ACT * 2 + SCB) * 3 + FMT)];
+    bool ok = true;
+    if (per_cu == 0 || lds1 > lds_seen) {
+      if (lds1 > 48u * 1024u &&
+          hipFuncSetAttribute((const void*)decode_one_kernel<ACT, SCB, FMT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1) != hipSuccess) {
+        (void)hipGetLastError();
+        ok = false;
+      }
+      int nb = 0;
+      if (ok && hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)decode_one_kernel<ACT, SCB, FMT>, DEC_NT, lds1) != hipSuccess) {
+        (void)hipGetLastError();
+        ok = false;
+      }
+      if (ok) { per_cu = nb > 0 ? nb : -1; lds_seen = lds1; }
+    }
+    if (ok && per_cu > 0 && (long)per_cu * ctx->n_cu >= n_wg) {
+      OneArgs o{};
+      o.sync = (unsigned*)(ctx->ws + WS_SYNC_OFF);
+      o.n_combo_s = n_combo_s; o.n_pieces = n_pieces; o.psh = psh; o.n_dn = n_dn;
+      o.spin_limit = ctx->one_spin_limit;
+      decode_one_kernel<ACT, SCB, FMT><<<g1, blk, lds1, ctx->stream>>>(in.logits, in.bias, in.mask, a.x, in.E, in.k, in.do_route, a.d_model,
+                                                                     n_wg, n_se, a, o);
+      HIPCHK(ctx, hipGetLastError());
+      ctx->one_calls++;
+      return SMOE_OK;
+    }
+  }
   if (evs) {
     // measurement aid: the dispatches themselves carry start/stop events (no extra marker packets)
     hipEvent_t ev[4];
@@ -1279,6 +1466,36 @@ static int launch_decode(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank
 }
 
 #undef DEC_LAUNCH
+
+// Clears the hand-over words of the single-launch kernel (a kernel, not a memset: the call may sit in
+// a stream that is being captured).
+__global__ void one_sync_clear_kernel(unsigned* words) {
+  for (int i = threadIdx.x; i < ONE_SYNC_WORDS; i += blockDim.x) words[i] = 0u;
+}
+
+extern "C" int smoe_ctx_single_launch(smoe_ctx* ctx, int enable, int spin_limit) {
+  if (!ctx) return SMOE_EINVAL;
+  if (!enable) { ctx->one_launch = 0; return SMOE_OK; }
+  if (!ctx->ws || ctx->ws_bytes < (size_t)WS_H_OFF) return SMOE_ESIZE;
+  if (spin_limit < 0) return SMOE_EINVAL;
+  HIPCHK(ctx, hipSetDevice(ctx->device));
+  one_sync_clear_kernel<<<1, 256, 0, ctx->stream>>>((unsigned*)(ctx->ws + WS_SYNC_OFF));
+  HIPCHK(ctx, hipGetLastError());
+  ctx->one_launch = 1;
+  ctx->one_spin_limit = spin_limit ? spin_limit : (1 << 20);
+  return SMOE_OK;
+}
+
+extern "C" int smoe_ctx_single_launch_status(smoe_ctx* ctx, long long* n_calls, unsigned* n_timeouts) {
+  if (!ctx || !n_calls || !n_timeouts) return SMOE_EINVAL;
+  *n_calls = ctx->one_calls;
+  *n_timeouts = 0;
+  if (!ctx->ws) return SMOE_OK;
+  HIPCHK(ctx, hipSetDevice(ctx->device));
+  HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+  HIPCHK(ctx, hipMemcpy(n_timeouts, ctx->ws + WS_SYNC_OFF + 4 * ONE_TIMEOUTS, 4, hipMemcpyDeviceToHost));
+  return SMOE_OK;
+}
 
 extern "C" int smoe_expert_ffn(smoe_ctx* ctx, const smoe_bank* routed, const smoe_bank* shared, const void* x_dev,
                                int act_dtype, int k, const int32_t* idx_dev, const float* w_dev,
