@@ -154,6 +154,14 @@ def test_workspace_bytes_and_ctx_create_validation():
     assert create(C.c_int(-1), None, C.c_void_p(0x1000), C.c_size_t(1 << 20), C.byref(h)) == -1
 
 
+def test_single_launch_calls_reject_null_arguments():
+    # (argument checks only: they return before any device call)
+    lib = B.lib()
+    n, t = C.c_longlong(), C.c_uint()
+    assert lib.smoe_ctx_single_launch(None, C.c_int(1), C.c_int(0)) == -1
+    assert lib.smoe_ctx_single_launch_status(None, C.byref(n), C.byref(t)) == -1
+
+
 def test_no_device_allocation_in_the_library_sources():
     # the boundary's rule: device memory belongs to the caller
     csrc = os.path.join(ROOT, "paper_2512_12990_amd", "csrc")
