@@ -174,9 +174,10 @@ template <> struct PlaneT<1> { typedef uint2 t; enum { BYTES = 8 }; };
 template <> struct PlaneT<2> { typedef uint3 t; enum { BYTES = 12 }; };
 template <int FMT> __device__ __forceinline__ typename PlaneT<FMT>::t pload(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff);
 // The same load at device scope (sc1): it returns what other compute dies have written through, whatever
-// this die's L2 holds.
+// this die's L2 holds.  Marked volatile for the compiler (bit 31 of the cache-policy operand): a poll
+// loop must issue it anew every time round.
 __device__ __forceinline__ uint4 bload128_dev(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
-  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 16);
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, (int)(16u | 0x80000000u));
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 template <> __device__ __forceinline__ uint4 pload<0>(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) { return bload128(r, voff, soff); }
@@ -1258,8 +1259,11 @@ __global__ __launch_bounds__(DEC_NT) void down_kernel(const int* rec, const floa
 // two launches are the default because they measured faster on this hardware: data handed from one
 // compute die to another inside a kernel costs several microseconds, the end of a kernel a fraction
 // of one).  Same arithmetic in the same order as the two kernels: results are bit-identical.
+// (bf16 activations: at most 128 vector registers, so that two work-groups share a CU like those of
+// gateup_kernel; the fp32 path keeps 32 activations per lane and gets the full register file, one
+// work-group per CU.)
 template <int ACT, int SCB, int FMT>
-__global__ __launch_bounds__(DEC_NT, 4) void decode_one_kernel(const float* logits, const float* bias, const uint8_t* mask, const void* x_in,
+__global__ __launch_bounds__(DEC_NT, ACT == SMOE_F32 ? 2 : 4) void decode_one_kernel(const float* logits, const float* bias, const uint8_t* mask, const void* x_in,
                                                                int E, int k, int do_route, int d_model, int n_wg, int n_se, DecodeArgs a,
                                                                OneArgs o) {
   __shared__ int sel_lds[SMOE_MAX_TOPK], prec_lds[SMOE_MAX_TOPK];
