@@ -253,7 +253,8 @@ def test_group32_layer(ctx, dt):
         say("  fused", fused, "worst max-abs-rel", worst)
 
 
-@pytest.mark.parametrize("T,dt", [(2, "f32"), (5, "bf16"), (16, "bf16")])
+# (down work-groups of 8 output rows at 2 tokens, 16 at 5, 32 at 8, 64 at 12 and 16)
+@pytest.mark.parametrize("T,dt", [(2, "f32"), (5, "bf16"), (8, "bf16"), (12, "f32"), (16, "bf16")])
 def test_multi_token_layer(ctx, T, dt):
     # T tokens through one layer in one pair of launches: every token must come out exactly as from
     # its own smoe_decode_layer call (bit for bit: same kernels, same order of operations) and
